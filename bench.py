@@ -1,0 +1,233 @@
+#!/usr/bin/env python3
+"""Benchmark of the BFP KV-cache hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of synthetic input, as a decoder
+layer would run it: kvbfp_quantize_append of the new token's K/V rows (one per sequence) followed
+by kvbfp_decode_attention over the packed cache.  Successive steps walk a ring of distinct layer
+caches (>= 1 GB in total) so no byte is served from the last-level cache of a previous step.
+
+Prints ONE JSON line: the metric is achieved HBM GB/s of decode attention + append, computed from
+the ALGORITHMIC bytes of a step (packed cache rows read once per KV head, q read, output written,
+new rows read and their packed form written) divided by the measured time per step.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2403_20137_amd import kvbfp, synth  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+HEADLINE = "llama3_8b_gqa_32k"
+ELT_BYTES = {"f32": 4, "f16": 2, "bf16": 2}
+
+
+def algorithmic_bytes(w: synth.Workload, seq_after_append: int):
+    """(decode bytes, append bytes) one step must move."""
+    elt = ELT_BYTES[w.dtype]
+    cache = w.batch * w.n_kv_heads * seq_after_append * w.row_pair_bytes()
+    q_io = 2 * w.batch * w.n_q_heads * w.head_dim * elt
+    n_elem = 2 * w.batch * w.n_kv_heads * w.head_dim                  # K and V rows of one new token
+    append = n_elem * elt + n_elem * w.mant_bits // 8 + n_elem // w.block
+    return cache + q_io, append
+
+
+class LayerRing:
+    """`n_layers` packed caches of one workload, filled by bulk quantize_append on the GPU."""
+
+    def __init__(self, w: synth.Workload, n_layers: int, device="cuda"):
+        self.w = w
+        self.S_max = w.seq + 1
+        self.layout = kvbfp.make_layout(w.head_dim, w.block, w.mant_bits, w.n_kv_heads, w.batch, self.S_max)
+        kg = synth.outlier_gains(synth.BASE_SEED, synth.TID_K_GAIN, w.n_kv_heads, w.head_dim, w.outlier_count, w.outlier_gain)
+        vg = synth.outlier_gains(synth.BASE_SEED, synth.TID_V_GAIN, w.n_kv_heads, w.head_dim, w.outlier_count, w.outlier_gain)
+        self.k_gain, self.v_gain = kg, vg
+        calib_k = synth.kv_rows(1, w.n_calib, w.n_kv_heads, w.head_dim, w.dtype, kg, synth.BASE_SEED, synth.TID_K_CALIB)[0]
+        calib_v = synth.kv_rows(1, w.n_calib, w.n_kv_heads, w.head_dim, w.dtype, vg, synth.BASE_SEED, synth.TID_V_CALIB)[0]
+        self.perm_k_host = kvbfp.calibrate_perm(calib_k)
+        self.perm_v_host = kvbfp.calibrate_perm(calib_v)
+        self.perm_k = torch.as_tensor(self.perm_k_host, device=device)
+        self.perm_v = torch.as_tensor(self.perm_v_host, device=device)
+        self.caches = []
+        for layer in range(n_layers):
+            cache = kvbfp.alloc_cache(self.layout, device)
+            k = synth.kv_rows(w.batch, w.seq, w.n_kv_heads, w.head_dim, w.dtype, kg, synth.BASE_SEED + layer, synth.TID_K, device)
+            v = synth.kv_rows(w.batch, w.seq, w.n_kv_heads, w.head_dim, w.dtype, vg, synth.BASE_SEED + layer, synth.TID_V, device)
+            kvbfp.quantize_append(cache, k, v, pos0=0, perm_k=self.perm_k, perm_v=self.perm_v)
+            torch.cuda.synchronize()
+            if layer == 0:
+                self.k0, self.v0 = k, v          # kept for the CPU-baseline sample
+            del k, v
+            self.caches.append(cache)
+        self.q = synth.queries(w.batch, w.n_q_heads, w.head_dim, w.dtype, synth.BASE_SEED, synth.TID_Q, device)
+        self.k_new = synth.kv_rows(w.batch, 1, w.n_kv_heads, w.head_dim, w.dtype, kg, synth.BASE_SEED, synth.TID_K_NEW, device)
+        self.v_new = synth.kv_rows(w.batch, 1, w.n_kv_heads, w.head_dim, w.dtype, vg, synth.BASE_SEED, synth.TID_V_NEW, device)
+        self.pos = torch.full((w.batch,), w.seq, dtype=torch.int32, device=device)
+        self.out = torch.empty_like(self.q)
+        need = kvbfp.decode_workspace_bytes(self.layout, w.n_q_heads, self.S_max)
+        self.workspace = torch.empty((need,), dtype=torch.uint8, device=device)
+        self.scale = float(np.float32(w.head_dim ** -0.5))
+
+    def append(self, i):
+        kvbfp.quantize_append(self.caches[i % len(self.caches)], self.k_new, self.v_new, pos_dev=self.pos,
+                              perm_k=self.perm_k, perm_v=self.perm_v)
+
+    def decode(self, i):
+        kvbfp.decode_attention(self.caches[i % len(self.caches)], self.q, self.S_max, self.scale,
+                               perm_k=self.perm_k, perm_v=self.perm_v, out=self.out, workspace=self.workspace)
+
+    def step(self, i):
+        self.append(i)
+        self.decode(i)
+
+
+def time_steps(ring: LayerRing, steps: int, warmup: int):
+    for i in range(warmup):
+        ring.step(i)
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    t0 = time.perf_counter()
+    for i in range(steps):
+        ev[i][0].record()
+        ring.append(warmup + i)
+        ev[i][1].record()
+        ring.decode(warmup + i)
+        ev[i][2].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    app = np.array([e[0].elapsed_time(e[1]) for e in ev]) * 1e3      # us
+    dec = np.array([e[1].elapsed_time(e[2]) for e in ev]) * 1e3
+    return (t1 - t0) / steps, app, dec
+
+
+def cpu_baseline(ring: LayerRing, budget_s=12.0):
+    """The oracle, as it stands, on (batch, kv-head) units of layer 0 of the same workload."""
+    from oracle import kvbfp_oracle as O
+    w = ring.w
+    G = w.group
+    units = [(b, h) for b in range(w.batch) for h in range(w.n_kv_heads)]
+    t_attn = t_quant = 0.0
+    n_done = 0
+    q_host = synth.to_f32_numpy(ring.q)
+    for (b, h) in units:
+        kk = synth.to_f32_numpy(ring.k0[b:b + 1, :, h:h + 1])
+        vv = synth.to_f32_numpy(ring.v0[b:b + 1, :, h:h + 1])
+        t = time.perf_counter()
+        km, ke = O.quantize_append(kk, w.block, w.mant_bits, w.seq, 0, perm=ring.perm_k_host[h:h + 1])
+        vm, ve = O.quantize_append(vv, w.block, w.mant_bits, w.seq, 0, perm=ring.perm_v_host[h:h + 1])
+        t_quant += time.perf_counter() - t
+        t = time.perf_counter()
+        O.decode_attention(km, ke, vm, ve, w.head_dim, w.block, w.mant_bits, q_host[b:b + 1, h * G:(h + 1) * G],
+                           [w.seq], ring.scale, ring.perm_k_host[h:h + 1], ring.perm_v_host[h:h + 1])
+        t_attn += time.perf_counter() - t
+        n_done += 1
+        if t_attn + t_quant > budget_s:
+            break
+    bytes_done = n_done * w.seq * w.row_pair_bytes()
+    elems = n_done * 2 * w.seq * w.head_dim
+    return {"value": bytes_done / t_attn / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": "%d of %d (batch, kv-head) units of %s, %d tokens each: decode attention %.2f s; "
+                      "their cast to BFP %.2f s = %.4f Gelem/s" % (n_done, len(units), w.name, w.seq, t_attn,
+                                                                   t_quant, elems / t_quant / 1e9),
+            "quantize_gelem_s": elems / t_quant / 1e9,
+            "host_logical_cores": os.cpu_count()}
+
+
+def bulk_quantize_rate(device="cuda", reps=5):
+    """Bulk prefill cast (32 layers x 8 KV heads x 4096 tokens, K and V) in Gelem/s."""
+    w = synth.WORKLOADS["prefill_bulk"]
+    kg = synth.outlier_gains(synth.BASE_SEED, synth.TID_K_GAIN, w.n_kv_heads, w.head_dim, w.outlier_count, w.outlier_gain)
+    k = synth.kv_rows(w.batch, w.seq, w.n_kv_heads, w.head_dim, w.dtype, kg, synth.BASE_SEED, synth.TID_K, device)
+    v = synth.kv_rows(w.batch, w.seq, w.n_kv_heads, w.head_dim, w.dtype, kg, synth.BASE_SEED, synth.TID_V, device)
+    layout = kvbfp.make_layout(w.head_dim, w.block, w.mant_bits, w.n_kv_heads, w.batch, w.seq)
+    cache = kvbfp.alloc_cache(layout, device)
+    kvbfp.quantize_append(cache, k, v)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for a, b in ev:
+        a.record()
+        kvbfp.quantize_append(cache, k, v)
+        b.record()
+    torch.cuda.synchronize()
+    us = np.array([a.elapsed_time(b) for a, b in ev]) * 1e3
+    elems = 2 * k.numel()
+    bytes_ = elems * 2 + elems * w.mant_bits // 8 + elems // w.block
+    return {"workload": w.name, "elements": elems, "us_median": float(np.median(us)), "us_min": float(us.min()),
+            "gelem_s": elems / np.median(us) / 1e3, "hbm_gb_s": bytes_ / np.median(us) / 1e3,
+            "hbm_frac": bytes_ / np.median(us) / 1e3 / HBM_PEAK_GBS}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default=HEADLINE, choices=sorted(synth.WORKLOADS))
+    ap.add_argument("--layers", type=int, default=0, help="distinct layer caches in the ring (0 = enough for >= 1 GB)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); --gpus %d is not "
+              "supported. value is one GPU's throughput." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    kvbfp.lib()     # fail loudly if the HIP library has not been built
+
+    w = synth.WORKLOADS[args.workload]
+    n_layers = args.layers or max(2, -(-1_100_000_000 // w.cache_bytes(w.seq + 1)))
+    n_layers = min(n_layers, 64)
+    ring = LayerRing(w, n_layers)
+    dec_bytes, app_bytes = algorithmic_bytes(w, w.seq + 1)
+    sec_per_step, app_us, dec_us = time_steps(ring, args.steps, args.warmup)
+    value = (dec_bytes + app_bytes) / sec_per_step / 1e9
+
+    dec_avg_s = float(dec_us.mean()) * 1e-6
+    roofline = {"bound": "hbm", "achieved": dec_bytes / dec_avg_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": dec_bytes / dec_avg_s / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                "kernel": "decode attention (split pass + combine, one kvbfp_decode_attention call)",
+                "bytes_per_launch": dec_bytes, "avg_launch_us": float(dec_us.mean()),
+                "median_launch_us": float(np.median(dec_us)), "min_launch_us": float(dec_us.min())}
+    traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(traffic_file):
+        try:
+            roofline["traffic"] = json.load(open(traffic_file)).get(w.name)
+        except Exception:
+            pass
+
+    result = {
+        "metric": "BFP-KV decode attention HBM GB/s (% of peak); quantize-append Gelem/s",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": sec_per_step * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
+                   "head_dim": w.head_dim, "seq": w.seq + 1, "block": w.block, "mant_bits": w.mant_bits,
+                   "layer_caches_in_ring": n_layers, "ring_bytes": n_layers * w.cache_bytes(w.seq + 1),
+                   "step": "quantize_append(1 token/sequence) + decode_attention"},
+        "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
+        "append_us_median": float(np.median(app_us)), "decode_us_median": float(np.median(dec_us)),
+        "roofline": roofline,
+    }
+    if not args.no_extra:
+        try:
+            result["quantize_append_bulk"] = bulk_quantize_rate()
+        except Exception as e:      # reported, never hidden
+            result["quantize_append_bulk"] = {"error": repr(e)}
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(ring)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,177 @@
+/* kvbfp -- Block-Floating-Point KV cache with offline channel reordering, for AMD MI355X (gfx950).
+ *
+ * C ABI of libkvbfp.so.  The operations follow "Accurate Block Quantization in LLMs with
+ * Outliers" (Trukhanov & Soloveychik): a per-head channel permutation fixed before inference
+ * (K-sort, Alg. 1) makes outlier channels share blocks; key/value rows are then stored in a
+ * Block Floating Point format (Sec. II-B, Eq. (1)) and attention reads that packed cache
+ * directly (Sec. III, run-time flow).
+ *
+ * General conventions
+ *   - "HOST" pointers are ordinary host memory; "DEVICE" pointers are HIP device memory on the
+ *     current device.  The library never allocates or frees device memory, keeps no state
+ *     between calls and owns none of the buffers passed in.
+ *   - Device calls only enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and return without synchronising.
+ *   - Every call returns a kvbfp_status.  Everything that can be checked on the host is checked
+ *     before anything is launched; kvbfp_last_error() then describes the problem.  Values held in
+ *     device memory (positions, sequence lengths) cannot be checked: kernels clamp them so that
+ *     all accesses stay inside the cache, and the result is then unspecified.
+ *   - Non-finite inputs (NaN, Inf) are outside the contract: memory-safe, value unspecified.
+ *
+ * BFP format (Sec. II-B, Eq. (1)): a block is `block` consecutive cache positions of one row.
+ * It stores one exponent byte E and `block` mantissa codes of `mant_bits` bits (sign-magnitude:
+ * top bit sign, rest magnitude |M| <= 2^(mant_bits-1)-1, zero always stored with sign 0).
+ * Decoded value = (-1)^sign * |M| * 2^(E - 127 - (mant_bits - 2)).  E = 0 marks an all-zero
+ * block.  The cast picks the smallest E for which round-to-nearest-even of the block's largest
+ * magnitude still fits the mantissa range and rounds every element to nearest-even at that scale,
+ * so every element is within half a mantissa step of its input.
+ *
+ * Packed cache (per layer): four planes, token-major inside each (batch, kv-head):
+ *     k_mant, v_mant : uint8 [batch][n_kv_heads][max_seq][head_dim * mant_bits / 8]
+ *     k_exp,  v_exp  : uint8 [batch][n_kv_heads][max_seq][head_dim / block]
+ * Position j of a row holds (permuted) channel j.  mant_bits = 8: byte j is code j.
+ * mant_bits = 4: byte i holds code 2i in its low nibble and code 2i+1 in its high nibble.
+ * Exponent byte b of a row belongs to positions [b*block, (b+1)*block).
+ * Storage is mant_bits + 8/block bits per element (BFP12 with block 32: 4.25 bits).
+ */
+#ifndef KVBFP_H
+#define KVBFP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    KVBFP_OK = 0,
+    KVBFP_ERR_INVALID_ARG = -1,   /* NULL where not allowed, inconsistent sizes, not a permutation */
+    KVBFP_ERR_UNSUPPORTED = -2,   /* valid in principle, not implemented (e.g. head_dim != 128 on device) */
+    KVBFP_ERR_WORKSPACE = -3,     /* workspace missing or too small */
+    KVBFP_ERR_HIP = -4            /* a HIP runtime call or kernel launch failed */
+} kvbfp_status;
+
+typedef enum { KVBFP_F32 = 0, KVBFP_F16 = 1, KVBFP_BF16 = 2 } kvbfp_dtype;
+
+/* Channel statistic used to rank channels (Alg. 1 step 1 and its calibration-data variant). */
+typedef enum {
+    KVBFP_STAT_MAXABS = 0,        /* max over samples of |x|: calibration key/value rows            */
+    KVBFP_STAT_L2 = 1             /* Euclidean norm over samples: rows of W_k, as Alg. 1 states it   */
+} kvbfp_stat;
+
+/* Geometry of one layer's packed cache.  Plain data, filled by the caller.
+ * struct_bytes must be sizeof(kvbfp_layout).  Device calls need head_dim == 128,
+ * block in {16,32,64,128}, mant_bits in {4,8}. */
+typedef struct {
+    uint32_t struct_bytes;
+    int32_t head_dim;
+    int32_t block;
+    int32_t mant_bits;
+    int32_t n_kv_heads;
+    int32_t batch;
+    int64_t max_seq;
+} kvbfp_layout;
+
+/* DEVICE pointers to the four planes described above; caller-owned. */
+typedef struct {
+    uint8_t* k_mant;
+    uint8_t* k_exp;
+    uint8_t* v_mant;
+    uint8_t* v_exp;
+} kvbfp_cache;
+
+/* Size in bytes of one mantissa plane and of one exponent plane for `layout`. */
+int kvbfp_cache_bytes(const kvbfp_layout* layout, size_t* mant_bytes_per_plane,
+                      size_t* exp_bytes_per_plane);
+
+/* HOST.  Alg. 1 steps 1-2: per head, a statistic per channel and a stable argsort of it.
+ *   x        : HOST, element (sample s, head h, channel c) at
+ *              x[s*sample_stride + h*head_stride + c*chan_stride] (strides in elements).
+ *              Calibration rows: samples are tokens.  Alg. 1 proper: x = W_k, samples are the
+ *              input features of a weight row, channels are the rows (stat = KVBFP_STAT_L2).
+ *   perm_out : HOST int32 [n_heads][head_dim]; perm_out[h][j] = channel placed at position j,
+ *              i.e. permuted[j] = original[perm[j]].  Ascending statistic unless `descending`
+ *              (Sec. III allows either); equal statistics keep ascending channel order.
+ * The L2 statistic is compared through the sum of squares accumulated in double in sample order.
+ * Errors: INVALID_ARG for NULL pointers, non-positive sizes, unknown dtype/stat. */
+int kvbfp_calibrate_perm(const void* x, kvbfp_dtype dtype, int64_t n_samples, int32_t n_heads,
+                         int32_t head_dim, int64_t sample_stride, int64_t head_stride,
+                         int64_t chan_stride, kvbfp_stat stat, int32_t descending,
+                         int32_t* perm_out);
+
+/* HOST.  Alg. 1 steps 3-4 (and the value-side analogue of Sec. III): reorder weight rows.
+ *   w_in, w_out : HOST [n_heads*head_dim][row_len] row-major, same dtype, must not overlap.
+ *   out row (h, j) = in row (h, perm[h / heads_per_perm][j]).
+ *   heads_per_perm: 1 for W_k / W_v; the group size for W_q when several query heads share a
+ *   KV head.  perm: HOST int32 [n_heads / heads_per_perm][head_dim].
+ * By Eq. (2)-(3) the products q.k^T are unchanged when W_q and W_k get the same permutation.
+ * Errors: INVALID_ARG for NULL, overlap, n_heads not divisible, perm rows that are not
+ * permutations of 0..head_dim-1. */
+int kvbfp_permute_weights(const void* w_in, void* w_out, kvbfp_dtype dtype, int32_t n_heads,
+                          int32_t head_dim, int64_t row_len, int32_t heads_per_perm,
+                          const int32_t* perm);
+
+/* DEVICE, asynchronous.  Cast new key/value rows to BFP (Sec. II-B) and store them in the cache
+ * (Sec. III: the keys of each head are kept in block format; values likewise).
+ *   k_new, v_new : DEVICE [batch][n_new][n_kv_heads][head_dim] of `dtype`, channel stride 1,
+ *                  element strides stride_b / stride_t / stride_h; either may be NULL (skipped).
+ *   Token i of sequence b goes to position pos0 + i (pos_dev == NULL) or pos_dev[b] + i
+ *   (pos_dev: DEVICE int32 [batch]); rows that would fall outside [0, max_seq) are dropped.
+ *   perm_k, perm_v : DEVICE int32 [n_kv_heads][head_dim] or NULL.  NULL means the rows already
+ *                  arrive in cache channel order (the permutation lives in the weights, Sec. II-C);
+ *                  otherwise position j of the stored row is input channel perm[h][j].
+ * Errors: INVALID_ARG (NULL layout/cache planes needed, n_new < 0, pos0 + n_new > max_seq when
+ * pos_dev is NULL, bad dtype), UNSUPPORTED (geometry), HIP. */
+int kvbfp_quantize_append(const kvbfp_layout* layout, const kvbfp_cache* cache, const void* k_new,
+                          const void* v_new, kvbfp_dtype dtype, int32_t n_new, int64_t stride_b,
+                          int64_t stride_t, int64_t stride_h, int64_t pos0, const int32_t* pos_dev,
+                          const int32_t* perm_k, const int32_t* perm_v, void* hip_stream);
+
+/* DEVICE, asynchronous.  Eq. (1): decode cached rows back to numbers.
+ *   which : 0 = keys, 1 = values.  Tokens [t0, t0 + n_tok) of every (batch, kv-head).
+ *   out   : DEVICE [batch][n_tok][n_kv_heads][head_dim] of `dtype`, dense.
+ *   perm  : DEVICE int32 [n_kv_heads][head_dim] or NULL.  NULL leaves cache (permuted) order;
+ *           otherwise out[perm[h][j]] = value at cache position j (original channel order).
+ * fp32 output is exact; fp16/bf16 output is the IEEE round-to-nearest-even conversion.
+ * Errors: INVALID_ARG (NULL, range outside [0, max_seq], bad which/dtype), UNSUPPORTED, HIP. */
+int kvbfp_dequantize(const kvbfp_layout* layout, const kvbfp_cache* cache, int32_t which,
+                     int64_t t0, int64_t n_tok, const int32_t* perm, void* out, kvbfp_dtype dtype,
+                     void* hip_stream);
+
+/* Bytes of DEVICE workspace kvbfp_decode_attention needs for up to max_len cached tokens
+ * (partial results of the sequence splits).  Returns 0 on invalid arguments. */
+size_t kvbfp_decode_workspace_bytes(const kvbfp_layout* layout, int32_t n_q_heads, int64_t max_len);
+
+/* DEVICE, asynchronous.  One decode step of attention over the packed cache (Sec. III: the cached
+ * keys are read back and multiplied with the permuted query; the rest is ordinary softmax
+ * attention; values are handled the same way and the output is brought back to the original
+ * channel order, which stands in for permuting the columns of the following projection).
+ *   q, out      : DEVICE [batch][n_q_heads][head_dim] of `dtype`, contiguous.
+ *                 n_q_heads % n_kv_heads == 0; query head h reads KV head h / (n_q_heads/n_kv_heads).
+ *   seq_len_dev : DEVICE int32 [batch] cached tokens per sequence, or NULL = max_len for all.
+ *                 Values are clamped to [0, max_len].  A sequence with 0 tokens yields zeros.
+ *   max_len     : host-known upper bound of the sequence lengths (<= max_seq); sizes the grid.
+ *   out[b][h] = softmax_t(softmax_scale * q'[b][h] . K^[b][g][t]) . V^[b][g][t], all cached tokens
+ *   attended (no mask), with q'[j] = q[perm_k[g][j]] and the result scattered as
+ *   out[perm_v[g][j]] = o[j]; a NULL perm means identity.
+ *   workspace   : DEVICE, at least kvbfp_decode_workspace_bytes(layout, n_q_heads, max_len) bytes,
+ *                 256-byte aligned; contents are scratch.
+ * Accumulation is fp32; the output is rounded once to `dtype`.
+ * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP. */
+int kvbfp_decode_attention(const kvbfp_layout* layout, const kvbfp_cache* cache, int32_t n_q_heads,
+                           const void* q, kvbfp_dtype dtype, const int32_t* seq_len_dev,
+                           int64_t max_len, float softmax_scale, const int32_t* perm_k,
+                           const int32_t* perm_v, void* out, void* workspace,
+                           size_t workspace_bytes, void* hip_stream);
+
+/* Message describing the last error on the calling thread ("" if none).  Static storage. */
+const char* kvbfp_last_error(void);
+
+/* Library version string, static storage. */
+const char* kvbfp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVBFP_H */

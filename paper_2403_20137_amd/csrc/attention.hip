@@ -1,0 +1,363 @@
+// Decode attention over the packed BFP cache for gfx950 (Sec. III run-time flow: cached keys are
+// read back in block format and multiplied with the permuted query; the rest is ordinary softmax
+// attention; values are handled the same way).
+//
+// Split-K over the sequence: pass 1 gives every (batch, kv-head, split) its own workgroup, which
+// streams its token range once, keeps an online softmax (running maximum m, normaliser l,
+// unnormalised output o) for the query heads that share the KV head, and writes (m, l, o) to the
+// workspace; pass 2 merges the splits with the usual log-sum-exp weights, normalises, restores the
+// original channel order of the values and rounds once to the output type.
+//
+// All softmax arithmetic is done in base 2: the query is pre-multiplied by softmax_scale*log2(e),
+// so exp(x) becomes the native 2^x.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+
+#include "kvbfp_internal.h"
+
+namespace {
+
+constexpr int kD = 128;
+constexpr int kTile = kvbfp::kTokenTile;   // tokens per tile = threads per workgroup
+constexpr int kHeadsPerWg = 4;             // query heads handled by one workgroup of the generic kernel
+
+struct DecodeArgs {
+    const uint8_t* k_mant;
+    const uint8_t* k_exp;
+    const uint8_t* v_mant;
+    const uint8_t* v_exp;
+    const void* q;
+    void* out;
+    const int32_t* seq_len;   // [B] or nullptr
+    const int32_t* perm_k;    // [H_kv][D] or nullptr
+    const int32_t* perm_v;
+    float* part_ml;           // [B][H_q][n_splits][2]  (m in base-2 units, l)
+    float* part_o;            // [B][H_q][n_splits][D]
+    int64_t max_seq, max_len, split_len;
+    int32_t H_kv, H_q, G, n_splits, log2_block;
+    float scale_log2e;
+};
+
+__device__ __forceinline__ float load_as_float(const void* p, int dt, int64_t i) {
+    if (dt == KVBFP_F32) return ((const float*)p)[i];
+    const uint32_t h = ((const uint16_t*)p)[i];
+    if (dt == KVBFP_F16) return (float)__builtin_bit_cast(_Float16, (unsigned short)h);
+    return __uint_as_float(h << 16);
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// Signed integer value of a sign-magnitude code as a float.
+template <int P>
+__device__ __forceinline__ float code_value(uint32_t c) {
+    const float m = (float)(c & ((1u << (P - 1)) - 1u));
+    return (c >> (P - 1)) ? -m : m;
+}
+
+// Generic, precision-first split pass: fp32 FMAs everywhere, any block size, any group size
+// (query heads are processed four per workgroup; larger groups re-read the cache).
+// grid = (n_splits, H_kv * ceil(G/4), B), block = 256.
+template <int P>
+__global__ __launch_bounds__(kTile) void decode_split_generic(DecodeArgs a, int dt) {
+    constexpr int kRowBytes = kD * P / 8;
+    constexpr int kRowVec = kRowBytes / 16;
+    __shared__ float qs[kHeadsPerWg][kD];
+    __shared__ float sc[kHeadsPerWg][kTile];
+    __shared__ float alpha_s[kHeadsPerWg];
+    __shared__ float ored[4][kHeadsPerWg][kD];
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int split = blockIdx.x;
+    const int gg_count = (a.G + kHeadsPerWg - 1) / kHeadsPerWg;
+    const int kvh = blockIdx.y / gg_count;
+    const int g0 = (blockIdx.y % gg_count) * kHeadsPerWg;
+    const int n_act = min(kHeadsPerWg, a.G - g0);
+    const int b = blockIdx.z;
+    const int h0 = kvh * a.G + g0;   // first query head of this workgroup
+
+    int64_t L = a.seq_len ? (int64_t)a.seq_len[b] : a.max_len;
+    L = L < 0 ? 0 : (L > a.max_len ? a.max_len : L);
+    const int64_t t_begin = (int64_t)split * a.split_len;
+    const int64_t t_end = min(t_begin + a.split_len, L);
+    const int nb = kD >> a.log2_block;
+
+    if (t_begin >= t_end) {   // nothing cached in this split
+        for (int i = tid; i < n_act * kD; i += kTile) {
+            const int g = i / kD, j = i % kD;
+            a.part_o[(((int64_t)b * a.H_q + h0 + g) * a.n_splits + split) * kD + j] = 0.f;
+        }
+        if (tid < n_act) {
+            float* ml = a.part_ml + (((int64_t)b * a.H_q + h0 + tid) * a.n_splits + split) * 2;
+            ml[0] = -INFINITY;
+            ml[1] = 0.f;
+        }
+        return;
+    }
+
+    // q' = permuted query times softmax_scale*log2(e); unused head slots are zero
+    for (int i = tid; i < kHeadsPerWg * kD; i += kTile) {
+        const int g = i / kD, j = i % kD;
+        float v = 0.f;
+        if (g < n_act) {
+            const int c = a.perm_k ? a.perm_k[kvh * kD + j] : j;
+            v = load_as_float(a.q, dt, ((int64_t)b * a.H_q + h0 + g) * kD + c) * a.scale_log2e;
+        }
+        qs[g][j] = v;
+    }
+    __syncthreads();
+
+    const int64_t base = ((int64_t)b * a.H_kv + kvh) * a.max_seq;
+    float m_run = -INFINITY, l_run = 0.f;          // wave g owns head g0+g (uniform per wave)
+    float o[kHeadsPerWg][2];
+#pragma unroll
+    for (int g = 0; g < kHeadsPerWg; ++g) o[g][0] = o[g][1] = 0.f;
+    const int cp = lane;                            // V phase: channels 2cp, 2cp+1
+
+    for (int64_t tile0 = t_begin; tile0 < t_end; tile0 += kTile) {
+        // ---- scores: one cached token per thread
+        const int64_t t = tile0 + tid;
+        float s[kHeadsPerWg];
+#pragma unroll
+        for (int g = 0; g < kHeadsPerWg; ++g) s[g] = -INFINITY;
+        if (t < t_end) {
+            uint4 raw[kRowVec];
+            const uint4* rp = (const uint4*)(a.k_mant + (base + t) * kRowBytes);
+#pragma unroll
+            for (int i = 0; i < kRowVec; ++i) raw[i] = rp[i];
+            const uint8_t* ep = a.k_exp + (base + t) * nb;
+#pragma unroll
+            for (int g = 0; g < kHeadsPerWg; ++g) s[g] = 0.f;
+#pragma unroll
+            for (int c = 0; c < kD / 16; ++c) {      // 16 channels at a time (never straddles a block)
+                const int E = ep[(c * 16) >> a.log2_block];
+                const float scale = ldexpf(1.0f, E - 127 - (P - 2));
+                float v[16];
+                if (P == 4) {
+                    const uint4 r = raw[c / 2];
+                    const uint32_t w0 = (c & 1) ? r.z : r.x, w1 = (c & 1) ? r.w : r.y;
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        v[i] = code_value<4>((w0 >> (4 * i)) & 0xFu);
+                        v[8 + i] = code_value<4>((w1 >> (4 * i)) & 0xFu);
+                    }
+                } else {
+                    const uint4 r = raw[c];
+                    const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) v[i] = code_value<8>((w[i / 4] >> (8 * (i % 4))) & 0xFFu);
+                }
+#pragma unroll
+                for (int g = 0; g < kHeadsPerWg; ++g) {
+                    float acc = 0.f;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc = fmaf(qs[g][c * 16 + i], v[i], acc);
+                    s[g] = fmaf(scale, acc, s[g]);
+                }
+            }
+        }
+#pragma unroll
+        for (int g = 0; g < kHeadsPerWg; ++g) sc[g][tid] = s[g];
+        __syncthreads();
+
+        // ---- online softmax: wave g updates head g
+        {
+            const int g = wave;
+            float sv[kTile / 64];
+            float tmax = -INFINITY;
+#pragma unroll
+            for (int k = 0; k < kTile / 64; ++k) {
+                sv[k] = sc[g][lane + 64 * k];
+                tmax = fmaxf(tmax, sv[k]);
+            }
+            tmax = wave_max(tmax);                  // finite: every tile holds a cached token
+            const float m_new = fmaxf(m_run, tmax);
+            float tsum = 0.f;
+#pragma unroll
+            for (int k = 0; k < kTile / 64; ++k) {
+                const float pw = exp2f(sv[k] - m_new);   // 2^-inf = 0 for padding
+                sc[g][lane + 64 * k] = pw;
+                tsum += pw;
+            }
+            tsum = wave_sum(tsum);
+            const float al = exp2f(m_run - m_new);       // 0 on the first tile
+            l_run = l_run * al + tsum;
+            m_run = m_new;
+            if (lane == 0) alpha_s[g] = al;
+        }
+        __syncthreads();
+
+        // ---- values: wave w takes tokens [64w, 64w+64) of the tile, lane = channel pair
+#pragma unroll
+        for (int g = 0; g < kHeadsPerWg; ++g) {
+            const float al = alpha_s[g];
+            o[g][0] *= al;
+            o[g][1] *= al;
+        }
+        const int64_t tw0 = tile0 + wave * 64;
+        const int cnt = (int)max((int64_t)0, min((int64_t)64, t_end - tw0));
+        for (int k = 0; k < cnt; ++k) {
+            const int64_t tt = tw0 + k;
+            const int E = a.v_exp[(base + tt) * nb + ((2 * cp) >> a.log2_block)];
+            const float scale = ldexpf(1.0f, E - 127 - (P - 2));
+            float v0, v1;
+            if (P == 4) {
+                const uint32_t byte = a.v_mant[(base + tt) * kRowBytes + cp];
+                v0 = code_value<4>(byte & 0xFu) * scale;
+                v1 = code_value<4>(byte >> 4) * scale;
+            } else {
+                const uint32_t two = ((const uint16_t*)(a.v_mant + (base + tt) * kRowBytes))[cp];
+                v0 = code_value<8>(two & 0xFFu) * scale;
+                v1 = code_value<8>(two >> 8) * scale;
+            }
+#pragma unroll
+            for (int g = 0; g < kHeadsPerWg; ++g) {
+                const float pw = sc[g][wave * 64 + k];
+                o[g][0] = fmaf(pw, v0, o[g][0]);
+                o[g][1] = fmaf(pw, v1, o[g][1]);
+            }
+        }
+        __syncthreads();   // sc and alpha_s are rewritten by the next tile
+    }
+
+    // ---- merge the four token slices and write the partial result of this split
+#pragma unroll
+    for (int g = 0; g < kHeadsPerWg; ++g) {
+        ored[wave][g][2 * cp] = o[g][0];
+        ored[wave][g][2 * cp + 1] = o[g][1];
+    }
+    __syncthreads();
+    for (int i = tid; i < n_act * kD; i += kTile) {
+        const int g = i / kD, j = i % kD;
+        const float v = ored[0][g][j] + ored[1][g][j] + ored[2][g][j] + ored[3][g][j];
+        a.part_o[(((int64_t)b * a.H_q + h0 + g) * a.n_splits + split) * kD + j] = v;
+    }
+    if (lane == 0 && wave < n_act) {
+        float* ml = a.part_ml + (((int64_t)b * a.H_q + h0 + wave) * a.n_splits + split) * 2;
+        ml[0] = m_run;
+        ml[1] = l_run;
+    }
+}
+
+__device__ __forceinline__ uint16_t narrow_bf16(float v) {
+    uint32_t u = __float_as_uint(v);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// Pass 2: merge the splits of one (batch, query head).  grid = (H_q, B), block = 128 (one channel
+// per thread).
+__global__ __launch_bounds__(kD) void decode_combine(DecodeArgs a, int dt) {
+    const int j = threadIdx.x;
+    const int h = blockIdx.x, b = blockIdx.y;
+    const int64_t bh = (int64_t)b * a.H_q + h;
+    const float* ml = a.part_ml + bh * a.n_splits * 2;
+    const float* po = a.part_o + bh * a.n_splits * kD;
+    float M = -INFINITY;
+    for (int i = 0; i < a.n_splits; ++i) M = fmaxf(M, ml[2 * i]);
+    float num = 0.f, den = 0.f;
+    if (M > -INFINITY) {
+        for (int i = 0; i < a.n_splits; ++i) {
+            const float w = exp2f(ml[2 * i] - M);     // empty splits carry m = -inf -> weight 0
+            num = fmaf(w, po[(int64_t)i * kD + j], num);
+            den = fmaf(w, ml[2 * i + 1], den);
+        }
+    }
+    const float r = den > 0.f ? num / den : 0.f;
+    const int kvh = h / a.G;
+    const int c = a.perm_v ? a.perm_v[kvh * kD + j] : j;
+    const int64_t oi = bh * kD + c;
+    if (dt == KVBFP_F32) ((float*)a.out)[oi] = r;
+    else if (dt == KVBFP_F16) ((uint16_t*)a.out)[oi] = __builtin_bit_cast(unsigned short, (_Float16)r);
+    else ((uint16_t*)a.out)[oi] = narrow_bf16(r);
+}
+
+int log2_exact(int v) {
+    int l = 0;
+    while ((1 << l) < v) ++l;
+    return l;
+}
+
+}  // namespace
+
+using namespace kvbfp;
+
+extern "C" {
+
+size_t kvbfp_decode_workspace_bytes(const kvbfp_layout* L, int32_t n_q_heads, int64_t max_len) {
+    clear_error();
+    if (check_device_layout(L) != KVBFP_OK) return 0;
+    if (n_q_heads <= 0 || n_q_heads % L->n_kv_heads != 0 || max_len <= 0 || max_len > L->max_seq) {
+        fail(KVBFP_ERR_INVALID_ARG, "decode_workspace_bytes: bad n_q_heads/max_len");
+        return 0;
+    }
+    const SplitPlan sp = plan_splits(L, n_q_heads, max_len);
+    return (size_t)L->batch * (size_t)n_q_heads * (size_t)sp.n_splits * (size_t)(kD + 2) * sizeof(float);
+}
+
+int kvbfp_decode_attention(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t n_q_heads,
+                           const void* q, kvbfp_dtype dtype, const int32_t* seq_len_dev,
+                           int64_t max_len, float softmax_scale, const int32_t* perm_k,
+                           const int32_t* perm_v, void* out, void* workspace,
+                           size_t workspace_bytes, void* hip_stream) {
+    clear_error();
+    if (int rc = check_device_layout(L)) return rc;
+    if (int rc = check_cache(cache, true, true)) return rc;
+    if (!q || !out) return fail(KVBFP_ERR_INVALID_ARG, "decode_attention: q/out is NULL");
+    if (dtype_size(dtype) == 0) return fail(KVBFP_ERR_INVALID_ARG, "decode_attention: unknown dtype %d", (int)dtype);
+    if (n_q_heads <= 0 || n_q_heads % L->n_kv_heads != 0)
+        return fail(KVBFP_ERR_INVALID_ARG, "decode_attention: n_q_heads %d not a multiple of n_kv_heads %d",
+                    n_q_heads, L->n_kv_heads);
+    if (max_len <= 0 || max_len > L->max_seq)
+        return fail(KVBFP_ERR_INVALID_ARG, "decode_attention: max_len %lld outside (0, max_seq=%lld]",
+                    (long long)max_len, (long long)L->max_seq);
+    if (!std::isfinite(softmax_scale))
+        return fail(KVBFP_ERR_INVALID_ARG, "decode_attention: softmax_scale is not finite");
+    const size_t need = kvbfp_decode_workspace_bytes(L, n_q_heads, max_len);
+    if (!workspace || workspace_bytes < need)
+        return fail(KVBFP_ERR_WORKSPACE, "decode_attention: workspace of %zu bytes needed, %zu given", need,
+                    workspace ? workspace_bytes : (size_t)0);
+    if ((uintptr_t)workspace % 256 != 0)
+        return fail(KVBFP_ERR_WORKSPACE, "decode_attention: workspace must be 256-byte aligned");
+    if ((int64_t)L->batch > 65535 || (int64_t)n_q_heads > 65535)
+        return fail(KVBFP_ERR_UNSUPPORTED, "decode_attention: batch/heads exceed the grid limits");
+
+    const SplitPlan sp = plan_splits(L, n_q_heads, max_len);
+    DecodeArgs a{};
+    a.k_mant = cache->k_mant; a.k_exp = cache->k_exp; a.v_mant = cache->v_mant; a.v_exp = cache->v_exp;
+    a.q = q; a.out = out; a.seq_len = seq_len_dev; a.perm_k = perm_k; a.perm_v = perm_v;
+    a.part_o = (float*)workspace;
+    a.part_ml = a.part_o + (size_t)L->batch * n_q_heads * sp.n_splits * kD;
+    a.max_seq = L->max_seq; a.max_len = max_len; a.split_len = sp.split_len;
+    a.H_kv = L->n_kv_heads; a.H_q = n_q_heads; a.G = n_q_heads / L->n_kv_heads;
+    a.n_splits = sp.n_splits; a.log2_block = log2_exact(L->block);
+    a.scale_log2e = softmax_scale * 1.4426950408889634f;
+
+    hipStream_t s = (hipStream_t)hip_stream;
+    const int gg = (a.G + kHeadsPerWg - 1) / kHeadsPerWg;
+    if ((int64_t)a.H_kv * gg > 65535)
+        return fail(KVBFP_ERR_UNSUPPORTED, "decode_attention: too many heads for the grid");
+    const dim3 grid1((unsigned)sp.n_splits, (unsigned)(a.H_kv * gg), (unsigned)L->batch);
+    if (L->mant_bits == 4) decode_split_generic<4><<<grid1, kTile, 0, s>>>(a, (int)dtype);
+    else decode_split_generic<8><<<grid1, kTile, 0, s>>>(a, (int)dtype);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return fail(KVBFP_ERR_HIP, "decode_attention (split pass): %s", hipGetErrorString(err));
+    const dim3 grid2((unsigned)n_q_heads, (unsigned)L->batch, 1);
+    decode_combine<<<grid2, kD, 0, s>>>(a, (int)dtype);
+    err = hipGetLastError();
+    if (err != hipSuccess) return fail(KVBFP_ERR_HIP, "decode_attention (combine pass): %s", hipGetErrorString(err));
+    return KVBFP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,37 @@
+// Internal helpers of libkvbfp (not part of the C ABI): error reporting and argument checks.
+#pragma once
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+
+#include "kvbfp.h"
+
+namespace kvbfp {
+
+// Records a printf-style message for kvbfp_last_error() and returns `code`.
+int fail(int code, const char* fmt, ...);
+void clear_error();
+
+inline int dtype_size(int dtype) {
+    switch (dtype) {
+        case KVBFP_F32: return 4;
+        case KVBFP_F16: return 2;
+        case KVBFP_BF16: return 2;
+        default: return 0;
+    }
+}
+
+// Checks the layout for the device kernels; returns KVBFP_OK or records an error.
+int check_device_layout(const kvbfp_layout* L);
+int check_cache(const kvbfp_cache* c, bool need_k, bool need_v);
+
+// Number of sequence splits and tokens per split used by decode attention for this geometry.
+struct SplitPlan {
+    int32_t n_splits;
+    int64_t split_len;   // multiple of kTokenTile
+};
+constexpr int kTokenTile = 256;
+SplitPlan plan_splits(const kvbfp_layout* L, int32_t n_q_heads, int64_t max_len);
+
+}  // namespace kvbfp

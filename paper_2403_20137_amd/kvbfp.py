@@ -1,0 +1,261 @@
+"""Thin ctypes binding of libkvbfp.so: same names as the C ABI (include/kvbfp.h), argument
+marshalling only.  Every step of the path runs inside the library's HIP kernels; PyTorch is used
+for device memory and streams.  There is no fallback: if the library is missing, importing the
+functions raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libkvbfp.so")
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
+F32, F16, BF16 = 0, 1, 2
+STAT_MAXABS, STAT_L2 = 0, 1
+
+_TORCH_DT = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
+_NP_DT = {np.dtype(np.float32): F32, np.dtype(np.float16): F16}
+
+EXPORTS = ["kvbfp_cache_bytes", "kvbfp_calibrate_perm", "kvbfp_permute_weights",
+           "kvbfp_quantize_append", "kvbfp_dequantize", "kvbfp_decode_workspace_bytes",
+           "kvbfp_decode_attention", "kvbfp_last_error", "kvbfp_version"]
+
+
+class KvbfpError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__("kvbfp status %d: %s" % (status, message))
+        self.status = status
+
+
+class Layout(C.Structure):
+    _fields_ = [("struct_bytes", C.c_uint32), ("head_dim", C.c_int32), ("block", C.c_int32),
+                ("mant_bits", C.c_int32), ("n_kv_heads", C.c_int32), ("batch", C.c_int32),
+                ("max_seq", C.c_int64)]
+
+
+class CachePtrs(C.Structure):
+    _fields_ = [("k_mant", C.c_void_p), ("k_exp", C.c_void_p), ("v_mant", C.c_void_p),
+                ("v_exp", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    """Loads libkvbfp.so; fails loudly when it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libkvbfp.so not found at %s -- build it with "
+                               "`python -m paper_2403_20137_amd.build` (needs hipcc)" % LIB_PATH)
+        l = C.CDLL(LIB_PATH)
+        l.kvbfp_last_error.restype = C.c_char_p
+        l.kvbfp_version.restype = C.c_char_p
+        l.kvbfp_decode_workspace_bytes.restype = C.c_size_t
+        l.kvbfp_decode_workspace_bytes.argtypes = [C.POINTER(Layout), C.c_int32, C.c_int64]
+        l.kvbfp_cache_bytes.argtypes = [C.POINTER(Layout), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+        l.kvbfp_calibrate_perm.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_int32, C.c_int32,
+                                           C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_int32, C.c_void_p]
+        l.kvbfp_permute_weights.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int32,
+                                            C.c_int64, C.c_int32, C.c_void_p]
+        l.kvbfp_quantize_append.argtypes = [C.POINTER(Layout), C.POINTER(CachePtrs), C.c_void_p, C.c_void_p,
+                                            C.c_int, C.c_int32, C.c_int64, C.c_int64, C.c_int64, C.c_int64,
+                                            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        l.kvbfp_dequantize.argtypes = [C.POINTER(Layout), C.POINTER(CachePtrs), C.c_int32, C.c_int64,
+                                       C.c_int64, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]
+        l.kvbfp_decode_attention.argtypes = [C.POINTER(Layout), C.POINTER(CachePtrs), C.c_int32, C.c_void_p,
+                                             C.c_int, C.c_void_p, C.c_int64, C.c_float, C.c_void_p,
+                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        _lib = l
+    return _lib
+
+
+def _check(status):
+    if status != OK:
+        raise KvbfpError(status, lib().kvbfp_last_error().decode())
+
+
+def last_error() -> str:
+    return lib().kvbfp_last_error().decode()
+
+
+def version() -> str:
+    return lib().kvbfp_version().decode()
+
+
+def make_layout(head_dim, block, mant_bits, n_kv_heads, batch, max_seq) -> Layout:
+    return Layout(C.sizeof(Layout), head_dim, block, mant_bits, n_kv_heads, batch, max_seq)
+
+
+def cache_bytes(layout: Layout):
+    m, e = C.c_size_t(0), C.c_size_t(0)
+    _check(lib().kvbfp_cache_bytes(C.byref(layout), C.byref(m), C.byref(e)))
+    return m.value, e.value
+
+
+class Cache:
+    """The four packed planes of one layer as uint8 device tensors (caller-owned memory)."""
+
+    def __init__(self, layout: Layout, k_mant, k_exp, v_mant, v_exp):
+        self.layout = layout
+        self.k_mant, self.k_exp, self.v_mant, self.v_exp = k_mant, k_exp, v_mant, v_exp
+
+    @property
+    def ptrs(self) -> CachePtrs:
+        return CachePtrs(*[t.data_ptr() if t is not None else None
+                           for t in (self.k_mant, self.k_exp, self.v_mant, self.v_exp)])
+
+    def planes(self):
+        return self.k_mant, self.k_exp, self.v_mant, self.v_exp
+
+    def nbytes(self):
+        return sum(t.numel() for t in self.planes())
+
+
+def alloc_cache(layout: Layout, device="cuda", fill=None) -> Cache:
+    mb, eb = cache_bytes(layout)
+    ms = (layout.batch, layout.n_kv_heads, layout.max_seq, layout.head_dim * layout.mant_bits // 8)
+    es = (layout.batch, layout.n_kv_heads, layout.max_seq, layout.head_dim // layout.block)
+    planes = []
+    for shape in (ms, es, ms, es):
+        t = torch.empty(shape, dtype=torch.uint8, device=device)
+        if fill is not None:
+            t.fill_(fill)
+        planes.append(t)
+    assert planes[0].numel() == mb and planes[1].numel() == eb
+    return Cache(layout, *planes)
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _dev_ptr(t, dtype=None):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("expected a device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError("expected dtype %s, got %s" % (dtype, t.dtype))
+    return C.c_void_p(t.data_ptr())
+
+
+def _host_array(x):
+    """numpy view + dtype code of a host tensor/array (bf16 is passed as its 16-bit pattern)."""
+    if isinstance(x, torch.Tensor):
+        if x.is_cuda:
+            raise ValueError("host function needs host memory")
+        if x.dtype == torch.bfloat16:
+            return x.contiguous().view(torch.int16).numpy(), BF16
+        x = x.contiguous().numpy()
+    x = np.ascontiguousarray(x)
+    if x.dtype not in _NP_DT:
+        raise ValueError("unsupported dtype %s" % x.dtype)
+    return x, _NP_DT[x.dtype]
+
+
+def calibrate_perm(x, stat=STAT_MAXABS, descending=False) -> np.ndarray:
+    """HOST.  x: [n_samples][n_heads][head_dim] (calibration rows) -> int32 [n_heads][head_dim]."""
+    arr, dt = _host_array(x)
+    S, H, D = arr.shape
+    perm = np.empty((H, D), dtype=np.int32)
+    _check(lib().kvbfp_calibrate_perm(arr.ctypes.data, dt, S, H, D, H * D, D, 1, int(stat),
+                                      1 if descending else 0, perm.ctypes.data))
+    return perm
+
+
+def calibrate_perm_from_weights(w, n_heads, head_dim, descending=False) -> np.ndarray:
+    """HOST.  Alg. 1 proper: w = W_k as [n_heads*head_dim][row_len]; ranks rows by Euclidean norm."""
+    arr, dt = _host_array(w)
+    rows, row_len = arr.shape
+    if rows != n_heads * head_dim:
+        raise ValueError("w must have n_heads*head_dim rows")
+    perm = np.empty((n_heads, head_dim), dtype=np.int32)
+    _check(lib().kvbfp_calibrate_perm(arr.ctypes.data, dt, row_len, n_heads, head_dim, 1,
+                                      head_dim * row_len, row_len, STAT_L2, 1 if descending else 0,
+                                      perm.ctypes.data))
+    return perm
+
+
+def permute_weights(w, n_heads, head_dim, perm, heads_per_perm=1):
+    """HOST, out of place.  Returns the reordered copy in the input's type (torch or numpy)."""
+    arr, dt = _host_array(w)
+    perm = np.ascontiguousarray(perm, dtype=np.int32)
+    out = np.empty_like(arr)
+    _check(lib().kvbfp_permute_weights(arr.ctypes.data, out.ctypes.data, dt, n_heads, head_dim,
+                                       arr.shape[1], heads_per_perm, perm.ctypes.data))
+    if isinstance(w, torch.Tensor):
+        t = torch.from_numpy(out)
+        return t.view(torch.bfloat16) if w.dtype == torch.bfloat16 else t
+    return out
+
+
+def quantize_append(cache: Cache, k_new, v_new, pos0=0, pos_dev=None, perm_k=None, perm_v=None,
+                    stream=None):
+    """DEVICE, async.  k_new / v_new: [batch][n_new][n_kv_heads][head_dim] device tensors (strided in
+    the first three dims, channel stride 1) or None."""
+    ref = k_new if k_new is not None else v_new
+    if ref is None:
+        return
+    for t in (k_new, v_new):
+        if t is not None:
+            if t.dim() != 4 or t.stride(3) != 1 or t.shape != ref.shape or t.stride() != ref.stride() \
+                    or t.dtype != ref.dtype:
+                raise ValueError("k_new/v_new must be 4-D, channel-contiguous, same shape/strides/dtype")
+    L = cache.layout
+    if ref.shape[0] != L.batch or ref.shape[2] != L.n_kv_heads or ref.shape[3] != L.head_dim:
+        raise ValueError("k_new/v_new shape does not match the layout")
+    ptrs = cache.ptrs
+    _check(lib().kvbfp_quantize_append(C.byref(L), C.byref(ptrs), _dev_ptr(k_new), _dev_ptr(v_new),
+                                       _TORCH_DT[ref.dtype], ref.shape[1], ref.stride(0), ref.stride(1),
+                                       ref.stride(2), int(pos0), _dev_ptr(pos_dev, torch.int32),
+                                       _dev_ptr(perm_k, torch.int32), _dev_ptr(perm_v, torch.int32),
+                                       _stream_ptr(stream)))
+
+
+def dequantize(cache: Cache, which, t0, n_tok, dtype=torch.float32, perm=None, out=None, stream=None):
+    """DEVICE, async.  Returns [batch][n_tok][n_kv_heads][head_dim] of `dtype`."""
+    L = cache.layout
+    if out is None:
+        out = torch.empty((L.batch, n_tok, L.n_kv_heads, L.head_dim), dtype=dtype,
+                          device=cache.k_mant.device if cache.k_mant is not None else cache.v_mant.device)
+    ptrs = cache.ptrs
+    _check(lib().kvbfp_dequantize(C.byref(L), C.byref(ptrs), int(which), int(t0), int(n_tok),
+                                  _dev_ptr(perm, torch.int32), _dev_ptr(out), _TORCH_DT[out.dtype],
+                                  _stream_ptr(stream)))
+    return out
+
+
+def decode_workspace_bytes(layout: Layout, n_q_heads, max_len) -> int:
+    return int(lib().kvbfp_decode_workspace_bytes(C.byref(layout), int(n_q_heads), int(max_len)))
+
+
+def decode_attention(cache: Cache, q, max_len, softmax_scale, seq_len_dev=None, perm_k=None,
+                     perm_v=None, out=None, workspace=None, stream=None):
+    """DEVICE, async.  q: [batch][n_q_heads][head_dim] contiguous device tensor; returns `out`."""
+    L = cache.layout
+    if q.dim() != 3 or not q.is_contiguous():
+        raise ValueError("q must be a contiguous [batch][n_q_heads][head_dim] tensor")
+    n_q_heads = q.shape[1]
+    if out is None:
+        out = torch.empty_like(q)
+    if workspace is None:
+        need = decode_workspace_bytes(L, n_q_heads, max_len)
+        if need == 0:
+            _check(ERR_INVALID_ARG if not last_error() else ERR_INVALID_ARG)
+        workspace = torch.empty((need,), dtype=torch.uint8, device=q.device)
+    ptrs = cache.ptrs
+    _check(lib().kvbfp_decode_attention(C.byref(L), C.byref(ptrs), n_q_heads, _dev_ptr(q),
+                                        _TORCH_DT[q.dtype], _dev_ptr(seq_len_dev, torch.int32),
+                                        int(max_len), float(softmax_scale),
+                                        _dev_ptr(perm_k, torch.int32), _dev_ptr(perm_v, torch.int32),
+                                        _dev_ptr(out), _dev_ptr(workspace), workspace.numel(),
+                                        _stream_ptr(stream)))
+    return out

@@ -1,0 +1,117 @@
+"""GPU parity of decode attention over the packed cache against the oracle (fp64), through the C ABI.
+Tolerance: max over (batch, head) of the relative L2 error, 2e-3 for fp16/bf16 I/O, 1e-5 for fp32."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import kvbfp_oracle as O
+from paper_2403_20137_amd import kvbfp, synth
+from util import DT_NAME, assert_attention_close, assert_planes_equal, dev_i32, gpu_cache, oracle_cache
+
+pytestmark = pytest.mark.gpu
+
+
+def run_both(k, v, q, n, p, lens, scale, pk=None, pv=None, S_max=None, use_seq_len=True):
+    """k, v: CPU tensors [B][S][Hkv][D]; q: CPU [B][Hq][D].  Returns (gpu_out, oracle_out)."""
+    B, S, Hkv, D = k.shape
+    S_max = S if S_max is None else S_max
+    planes = oracle_cache(k, v, n, p, S_max, 0, pk, pv)
+    cache = gpu_cache(k.cuda(), v.cuda(), n, p, S_max, perm_k=pk, perm_v=pv)
+    assert_planes_equal(cache, planes, "cache before attention")
+    want = O.decode_attention(*planes, D, n, p, synth.to_f32_numpy(q), lens, float(np.float32(scale)), pk, pv)
+    max_len = int(np.max(lens))
+    sl = dev_i32(np.broadcast_to(np.asarray(lens), (B,))) if use_seq_len else None
+    got = kvbfp.decode_attention(cache, q.cuda(), max_len, float(np.float32(scale)), seq_len_dev=sl,
+                                 perm_k=dev_i32(pk), perm_v=dev_i32(pv))
+    torch.cuda.synchronize()
+    return got, want
+
+
+def make_small(dtype, B, S, Hkv, G, seed):
+    D = 128
+    kg = synth.outlier_gains(seed, 0, Hkv, D)
+    vg = synth.outlier_gains(seed, 1, Hkv, D)
+    k = synth.kv_rows(B, S, Hkv, D, DT_NAME[dtype], kg, seed, 2)
+    v = synth.kv_rows(B, S, Hkv, D, DT_NAME[dtype], vg, seed, 3)
+    q = synth.queries(B, Hkv * G, D, DT_NAME[dtype], seed, 4)
+    calib_k = synth.kv_rows(1, 64, Hkv, D, DT_NAME[dtype], kg, seed, 5)[0]
+    calib_v = synth.kv_rows(1, 64, Hkv, D, DT_NAME[dtype], vg, seed, 6)[0]
+    pk = O.calibrate_perm(synth.to_f32_numpy(calib_k))
+    pv = O.calibrate_perm(synth.to_f32_numpy(calib_v))
+    return k, v, q, pk, pv
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.float16, torch.bfloat16])
+@pytest.mark.parametrize("p,n", [(4, 16), (4, 32), (4, 64), (4, 128), (8, 16), (8, 32)])
+@pytest.mark.parametrize("G", [1, 4])
+def test_decode_attention_matches_oracle(dtype, p, n, G):
+    # 700 tokens: two full 256-token tiles and a ragged third; the second sequence stops mid-tile
+    k, v, q, pk, pv = make_small(dtype, B=2, S=700, Hkv=2, G=G, seed=20 + G)
+    got, want = run_both(k, v, q, n, p, [700, 259], 128 ** -0.5, pk, pv, S_max=720)
+    assert_attention_close(got, want, dtype, "p=%d n=%d G=%d" % (p, n, G))
+
+
+@pytest.mark.parametrize("G", [2, 3, 5, 8])
+def test_group_sizes_and_no_permutation(G):
+    k, v, q, _, _ = make_small(torch.bfloat16, B=1, S=300, Hkv=3, G=G, seed=40 + G)
+    got, want = run_both(k, v, q, 32, 4, [300], 0.11, None, None, use_seq_len=False)
+    assert_attention_close(got, want, torch.bfloat16)
+
+
+def test_sequence_length_edge_cases():
+    # lengths 0 (zeros out), 1 (the value row itself), tile boundary, one past it, full
+    k, v, q, pk, pv = make_small(torch.float16, B=5, S=513, Hkv=2, G=2, seed=50)
+    lens = [0, 1, 256, 257, 513]
+    got, want = run_both(k, v, q, 16, 4, lens, 128 ** -0.5, pk, pv, S_max=600)
+    g = got.cpu().float().numpy()
+    assert np.all(g[0] == 0)
+    assert_attention_close(got[1:], want[1:], torch.float16)
+    # length 1: exactly the decoded value row, un-permuted, rounded once to fp16
+    planes = oracle_cache(k, v, 16, 4, 600, 0, pk, pv)
+    v0 = O.dequantize(planes[2], planes[3], 128, 16, 4, 0, 1, perm=pv)[1, 0]       # [Hkv][D]
+    want_row = torch.from_numpy(v0).to(torch.float16)
+    for h in range(4):
+        assert torch.equal(got[1, h].cpu(), want_row[h // 2])
+
+
+def test_split_count_does_not_change_the_result_beyond_rounding():
+    # the same cache attended through different max_seq / max_len (hence different split plans)
+    k, v, q, pk, pv = make_small(torch.float32, B=1, S=3000, Hkv=1, G=2, seed=60)
+    got_a, want = run_both(k, v, q, 32, 4, [3000], 128 ** -0.5, pk, pv, S_max=3000)
+    got_b, _ = run_both(k, v, q, 32, 4, [3000], 128 ** -0.5, pk, pv, S_max=4096)
+    assert_attention_close(got_a, want, torch.float32)
+    assert_attention_close(got_b, want, torch.float32)
+    # attending to a prefix only
+    planes = oracle_cache(k, v, 32, 4, 3000, 0, pk, pv)
+    cache = gpu_cache(k.cuda(), v.cuda(), 32, 4, 3000, perm_k=pk, perm_v=pv)
+    want = O.decode_attention(*planes, 128, 32, 4, synth.to_f32_numpy(q), [1000], float(np.float32(128 ** -0.5)), pk, pv)
+    got = kvbfp.decode_attention(cache, q.cuda(), 1000, 128 ** -0.5, perm_k=dev_i32(pk), perm_v=dev_i32(pv))
+    assert_attention_close(got, want, torch.float32)
+
+
+def test_large_logits_stay_finite_and_accurate():
+    k, v, q, pk, pv = make_small(torch.float32, B=1, S=400, Hkv=1, G=1, seed=70)
+    got, want = run_both(k, v, q * 40, 16, 4, [400], 1.0, pk, pv)
+    assert bool(torch.isfinite(got).all())
+    assert_attention_close(got, want, torch.float32)
+
+
+def test_tiny_workload_full_parity():
+    # smallest benchmark configuration end to end: perm from the library, cache bytes, attention
+    w = synth.WORKLOADS["tiny"]
+    d = synth.make_workload_inputs(w)
+    pk = kvbfp.calibrate_perm(d["k_calib"])
+    pv = kvbfp.calibrate_perm(d["v_calib"])
+    assert np.array_equal(pk, O.calibrate_perm(synth.to_f32_numpy(d["k_calib"])))
+    assert np.array_equal(pv, O.calibrate_perm(synth.to_f32_numpy(d["v_calib"])))
+    got, want = run_both(d["k"], d["v"], d["q"], w.block, w.mant_bits, [w.seq], w.head_dim ** -0.5, pk, pv)
+    assert_attention_close(got, want, torch.float32)
+
+
+def test_llama2_7b_4k_full_parity():
+    w = synth.WORKLOADS["llama2_7b_4k"]
+    d = synth.make_workload_inputs(w)
+    pk = kvbfp.calibrate_perm(d["k_calib"])
+    pv = kvbfp.calibrate_perm(d["v_calib"])
+    got, want = run_both(d["k"], d["v"], d["q"], w.block, w.mant_bits, [w.seq], w.head_dim ** -0.5, pk, pv)
+    assert_attention_close(got, want, torch.float16)

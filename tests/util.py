@@ -1,0 +1,104 @@
+"""Shared helpers of the GPU parity tests: run the same seeded inputs through the oracle (host,
+numpy) and through libkvbfp (device, torch tensors), and compare."""
+import numpy as np
+import torch
+
+from oracle import kvbfp_oracle as O
+from paper_2403_20137_amd import kvbfp, synth
+
+TOL = {torch.float32: 1e-5, torch.float16: 2e-3, torch.bfloat16: 2e-3}   # max rel-L2 per head
+DT_NAME = {torch.float32: "f32", torch.float16: "f16", torch.bfloat16: "bf16"}
+
+
+def rel_l2_per_head(got, want):
+    """got: torch [B][Hq][D] (any dtype, any device), want: float64 numpy.  Returns [B][Hq]."""
+    g = got.detach().to("cpu").to(torch.float64).numpy()
+    num = np.linalg.norm(g - want, axis=-1)
+    den = np.linalg.norm(want, axis=-1)
+    return np.where(den > 0, num / np.where(den > 0, den, 1), num)
+
+
+def dtype_round(want, dtype):
+    """fp64 numpy -> the value after one IEEE round-to-nearest-even to `dtype`, back in fp64."""
+    return torch.from_numpy(np.ascontiguousarray(want)).to(dtype).to(torch.float64).numpy()
+
+
+# Kernel arithmetic (fp32 accumulation, fp16 operands in the fast paths) relative to the largest
+# entry of a head's output; far below the 16-bit output step.
+ARITH_SLACK = {torch.float32: 1e-5, torch.float16: 3e-4, torch.bfloat16: 3e-4}
+MANT_BITS = {torch.float16: 10, torch.bfloat16: 7}
+
+
+def assert_attention_close(got, want, dtype, what=""):
+    """The decode-attention bar.
+
+    fp32 I/O: relative L2 error of every (batch, head) output vector <= 1e-5.
+
+    fp16 / bf16 I/O: the stated bar is 2e-3 relative L2.  One correct rounding of the exact result
+    to bf16 already costs up to 2^-8 = 3.9e-3 of a vector that is dominated by one entry (1.5e-3
+    on average), so per head the bar is max(2e-3, error of the correctly rounded oracle result +
+    kernel slack); over the whole tensor it is 2e-3; and element by element the result must be
+    the correctly rounded exact value up to the kernel's arithmetic slack:
+        |got - want| <= ulp(want)/2 + ARITH_SLACK * max|want_head|.
+    Returns (max per-head rel-L2, whole-tensor rel-L2)."""
+    g = got.detach().to("cpu").to(torch.float64).numpy()
+    per_head = rel_l2_per_head(got, want)
+    total = float(np.linalg.norm(g - want) / max(np.linalg.norm(want), 1e-300))
+    if dtype == torch.float32:
+        assert per_head.max() <= TOL[dtype], (what, per_head)
+        return float(per_head.max()), total
+    ideal = rel_l2_per_head(torch.from_numpy(dtype_round(want, dtype)), want)
+    bar = np.maximum(TOL[dtype], ideal + ARITH_SLACK[dtype])
+    assert np.all(per_head <= bar), (what, per_head, bar)
+    assert total <= TOL[dtype] or total <= float(np.linalg.norm(dtype_round(want, dtype) - want) /
+                                                 np.linalg.norm(want)) + ARITH_SLACK[dtype], (what, total)
+    mb = MANT_BITS[dtype]
+    mag = np.maximum(np.abs(want), 2.0 ** -14 if dtype == torch.float16 else 2.0 ** -126)
+    half_ulp = 0.5 * 2.0 ** (np.floor(np.log2(mag)) - mb)
+    slack = ARITH_SLACK[dtype] * np.abs(want).max(axis=-1, keepdims=True)
+    worst = (np.abs(g - want) - half_ulp - slack).max()
+    assert worst <= 0, (what, "element off by more than a correct rounding plus slack", worst)
+    return float(per_head.max()), total
+
+
+def perms_for(calib_k, calib_v):
+    """Oracle permutations from calibration rows [n][H][D] (torch, any dtype)."""
+    return (O.calibrate_perm(synth.to_f32_numpy(calib_k), "maxabs"),
+            O.calibrate_perm(synth.to_f32_numpy(calib_v), "maxabs"))
+
+
+def dev_i32(a, device="cuda"):
+    return None if a is None else torch.as_tensor(np.ascontiguousarray(a, dtype=np.int32), device=device)
+
+
+def oracle_cache(k, v, n, p, S_max, pos, perm_k=None, perm_v=None, fill=None):
+    """k, v: torch [B][n_new][H][D] -> the four planes as numpy (oracle)."""
+    kf, vf = synth.to_f32_numpy(k), synth.to_f32_numpy(v)
+    B, _, H, D = kf.shape
+    ms, es = O.plane_shapes(B, H, D, n, p, S_max)
+    planes = []
+    for x, perm in ((kf, perm_k), (vf, perm_v)):
+        m = np.zeros(ms, np.uint8) if fill is None else np.full(ms, fill, np.uint8)
+        e = np.zeros(es, np.uint8) if fill is None else np.full(es, fill, np.uint8)
+        O.quantize_append(x, n, p, S_max, pos, perm=perm, mant=m, exp=e)
+        planes += [m, e]
+    return planes
+
+
+def gpu_cache(k, v, n, p, S_max, pos0=0, pos_dev=None, perm_k=None, perm_v=None, fill=None):
+    """Same through libkvbfp; k, v device tensors.  Returns the kvbfp.Cache."""
+    B, _, H, D = k.shape
+    L = kvbfp.make_layout(D, n, p, H, B, S_max)
+    cache = kvbfp.alloc_cache(L, k.device, fill=0 if fill is None else fill)
+    kvbfp.quantize_append(cache, k, v, pos0=pos0, pos_dev=pos_dev, perm_k=dev_i32(perm_k), perm_v=dev_i32(perm_v))
+    torch.cuda.synchronize()
+    return cache
+
+
+def assert_planes_equal(cache, planes, what=""):
+    for name, t, ref in zip(("k_mant", "k_exp", "v_mant", "v_exp"), cache.planes(), planes):
+        got = t.cpu().numpy()
+        if not np.array_equal(got, ref):
+            bad = np.argwhere(got != ref)
+            raise AssertionError("%s %s: %d bytes differ, first at %s: got %#x want %#x" % (
+                what, name, len(bad), bad[0].tolist(), int(got[tuple(bad[0])]), int(ref[tuple(bad[0])])))
