@@ -15,7 +15,10 @@
 #include <cmath>
 #include <cstdint>
 
+#include "decode_args.h"
 #include "kvbfp_internal.h"
+
+using kvbfp::DecodeArgs;
 
 namespace {
 
@@ -23,22 +26,6 @@ constexpr int kD = 128;
 constexpr int kTile = kvbfp::kTokenTile;   // tokens per tile = threads per workgroup
 constexpr int kHeadsPerWg = 4;             // query heads handled by one workgroup of the generic kernel
 
-struct DecodeArgs {
-    const uint8_t* k_mant;
-    const uint8_t* k_exp;
-    const uint8_t* v_mant;
-    const uint8_t* v_exp;
-    const void* q;
-    void* out;
-    const int32_t* seq_len;   // [B] or nullptr
-    const int32_t* perm_k;    // [H_kv][D] or nullptr
-    const int32_t* perm_v;
-    float* part_ml;           // [B][H_q][n_splits][2]  (m in base-2 units, l)
-    float* part_o;            // [B][H_q][n_splits][D]
-    int64_t max_seq, max_len, split_len;
-    int32_t H_kv, H_q, G, n_splits, log2_block;
-    float scale_log2e;
-};
 
 __device__ __forceinline__ float load_as_float(const void* p, int dt, int64_t i) {
     if (dt == KVBFP_F32) return ((const float*)p)[i];
@@ -349,9 +336,17 @@ int kvbfp_decode_attention(const kvbfp_layout* L, const kvbfp_cache* cache, int3
     if ((int64_t)a.H_kv * gg > 65535)
         return fail(KVBFP_ERR_UNSUPPORTED, "decode_attention: too many heads for the grid");
     const dim3 grid1((unsigned)sp.n_splits, (unsigned)(a.H_kv * gg), (unsigned)L->batch);
-    if (L->mant_bits == 4) decode_split_generic<4><<<grid1, kTile, 0, s>>>(a, (int)dtype);
-    else decode_split_generic<8><<<grid1, kTile, 0, s>>>(a, (int)dtype);
-    hipError_t err = hipGetLastError();
+    auto aligned16 = [](const void* p) { return ((uintptr_t)p & 15u) == 0; };
+    const bool fast = L->mant_bits == 4 && a.G <= 8 && dtype != KVBFP_F32 && aligned16(a.k_mant) &&
+                      aligned16(a.v_mant) && aligned16(a.k_exp) && aligned16(a.v_exp);
+    hipError_t err;
+    if (fast) {
+        err = launch_decode_split_mfma(a, (int)dtype, L->block, L->batch, s);
+    } else {
+        if (L->mant_bits == 4) decode_split_generic<4><<<grid1, kTile, 0, s>>>(a, (int)dtype);
+        else decode_split_generic<8><<<grid1, kTile, 0, s>>>(a, (int)dtype);
+        err = hipGetLastError();
+    }
     if (err != hipSuccess) return fail(KVBFP_ERR_HIP, "decode_attention (split pass): %s", hipGetErrorString(err));
     const dim3 grid2((unsigned)n_q_heads, (unsigned)L->batch, 1);
     decode_combine<<<grid2, kD, 0, s>>>(a, (int)dtype);

@@ -1,0 +1,365 @@
+// Fast split pass of decode attention for 4-bit mantissas on gfx950 (Sec. III run-time flow).
+//
+// Why matrix cores: with G query heads sharing one KV head, a cached element takes 2*G multiply-
+// adds but arrives at 0.53 bytes.  At 8 TB/s the vector ALUs (64 lanes x 4 SIMDs x 256 CUs, one
+// fp32 op per lane per clock without packed math) can spend about 2.5 instructions per element;
+// unpacking a sign-magnitude nibble costs >= 1.25 of them, which leaves no room for even G = 1
+// worth of dot2 instructions at full bandwidth, let alone G = 4.  The skinny products
+// (G x 128) . (128 x T) and (G x T) . (T x 128) therefore go to the MFMA pipe, which is otherwise
+// idle, and the vector ALUs only unpack.
+//
+// Unpacking without integer->float conversions: a code s|mmm widened to the byte s0000mmm is the
+// OCP FP8-E4M3 subnormal (-1)^s * m * 2^-9, so v_cvt_scalef32_pk_bf16_fp8 turns two codes into
+// two exact bf16 values and applies the block's power-of-two scale in the same instruction.
+// Cost per 8 codes: 6 bit operations + 4 conversions.
+//
+// Score product  S = Q . K^T  (v_mfma_f32_16x16x32_bf16, A = query rows, B = keys):
+//   lane (j = lane%16, kg = lane/16) loads the 16-byte chunk kg of the key row of token j
+//   (32 channels, i.e. whole blocks) and feeds it to 4 MFMAs; A holds the query split into three
+//   bf16 limbs (24 significant bits) in rows 4*head + limb, so the product keeps fp32 accuracy.
+// Value product  O = P . V  (same instruction, A = probabilities, B = values):
+//   the reduction index enumerates (token, channel parity): a converted register already holds
+//   the two channels of one token, and the probabilities sit in rows (head, parity, limb) with
+//   zeros in the other parity's slots, so no transposition of the 4-bit data is ever needed.
+//   Lane (j, kg) loads dword j (8 channels) of the value rows of tokens 4kg..4kg+3.
+// Each wavefront owns every fourth 64-token tile of its split and keeps its own online-softmax
+// state; the four wavefronts of a workgroup merge once at the end.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+
+#include "decode_args.h"
+#include "kvbfp_internal.h"
+
+namespace {
+
+using kvbfp::DecodeArgs;
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kD = 128;
+constexpr int kWaves = 4;
+constexpr int kSuper = 64;   // tokens per wavefront iteration (4 MFMA column tiles of 16)
+// Cached values are produced as value * 2^-16 so that the conversion's scale exponent stays a
+// normal fp32 exponent for every stored exponent byte >= 10; the query carries the inverse factor.
+constexpr int kShift = 16;
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+// all-reduce over the 16 lanes of a DPP row
+__device__ __forceinline__ float row_max(float v) {
+    v = fmaxf(v, dpp_f<0xB1>(v));
+    v = fmaxf(v, dpp_f<0x4E>(v));
+    v = fmaxf(v, dpp_f<0x141>(v));
+    v = fmaxf(v, dpp_f<0x140>(v));
+    return v;
+}
+__device__ __forceinline__ float row_sum(float v) {
+    v += dpp_f<0xB1>(v);
+    v += dpp_f<0x4E>(v);
+    v += dpp_f<0x141>(v);
+    v += dpp_f<0x140>(v);
+    return v;
+}
+
+__device__ __forceinline__ float load_as_float(const void* p, int dt, int64_t i) {
+    if (dt == KVBFP_F32) return ((const float*)p)[i];
+    const uint32_t h = ((const uint16_t*)p)[i];
+    if (dt == KVBFP_F16) return (float)__builtin_bit_cast(_Float16, (unsigned short)h);
+    return __uint_as_float(h << 16);
+}
+
+// fp32 scale operand 2^(E - 129 + 9 - kShift): a code m, read as the FP8 subnormal m * 2^-9, times
+// it equals m * 2^(E - 127 - 2) * 2^-kShift.  Only the exponent field of the operand is used by the
+// conversion; exponent bytes below 10 (magnitudes under 2^-116) collapse to the smallest scale.
+__device__ __forceinline__ float scale_operand(uint32_t E) {
+    const int f = (int)E + 7 - kShift;      // (E - 129 + 9 - kShift) + 127
+    return __uint_as_float((uint32_t)max(f, 0) << 23);
+}
+
+// 8 sign-magnitude nibbles -> 8 bf16 values in slot order [c0,c2,c4,c6,c1,c3,c5,c7]
+struct Unpacked { bf16x2 p[4]; };
+__device__ __forceinline__ Unpacked unpack8(uint32_t w, float scale) {
+    const uint32_t lo = ((w << 4) & 0x80808080u) | (w & 0x07070707u);          // even nibbles as FP8 bytes
+    const uint32_t hi = (w & 0x80808080u) | ((w >> 4) & 0x07070707u);          // odd nibbles
+    Unpacked u;
+    u.p[0] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, scale, false);      // (c0, c2)
+    u.p[1] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, scale, true);       // (c4, c6)
+    u.p[2] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, scale, false);      // (c1, c3)
+    u.p[3] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, scale, true);       // (c5, c7)
+    return u;
+}
+__device__ __forceinline__ bf16x8 join(bf16x2 a, bf16x2 b, bf16x2 c, bf16x2 d) {
+    bf16x8 r;
+    r[0] = a[0]; r[1] = a[1]; r[2] = b[0]; r[3] = b[1];
+    r[4] = c[0]; r[5] = c[1]; r[6] = d[0]; r[7] = d[1];
+    return r;
+}
+// channel offset inside a dword of MFMA slot x
+__device__ __forceinline__ int slot_channel(int x) { return (x < 4) ? 2 * x : 2 * (x - 4) + 1; }
+
+// N = block size, HG = groups of four query heads per KV head (G <= 4*HG).
+// grid = (n_splits, H_kv, B), block = 256 (four wavefronts).
+template <int N, int HG>
+__global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt) {
+    constexpr int NB = kD / N;
+    constexpr int NH = HG * 4;
+    __shared__ float q_s[NH][kD];                               // scaled, permuted queries
+    __shared__ __align__(16) uint16_t p_s[kWaves][HG][2][4][kSuper];   // probabilities, bf16 hi/lo limbs
+    __shared__ float o_s[kWaves][NH][kD];                       // per-wavefront outputs for the merge
+    __shared__ float ml_s[kWaves][NH][2];
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int j = lane & 15, kg = lane >> 4;
+    const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+    const int h0 = kvh * a.G;
+
+    int64_t L = a.seq_len ? (int64_t)a.seq_len[b] : a.max_len;
+    L = L < 0 ? 0 : (L > a.max_len ? a.max_len : L);
+    const int64_t t_begin = (int64_t)split * a.split_len;
+    const int64_t t_end = min(t_begin + a.split_len, L);
+
+    if (t_begin >= t_end) {   // nothing cached in this split
+        for (int i = tid; i < a.G * kD; i += 256)
+            a.part_o[(((int64_t)b * a.H_q + h0 + i / kD) * a.n_splits + split) * kD + (i % kD)] = 0.f;
+        if (tid < a.G) {
+            float* ml = a.part_ml + (((int64_t)b * a.H_q + h0 + tid) * a.n_splits + split) * 2;
+            ml[0] = -INFINITY;
+            ml[1] = 0.f;
+        }
+        return;
+    }
+
+    // q' = permuted query * softmax_scale*log2(e) * 2^kShift; head slots beyond G are zero
+    for (int i = tid; i < NH * kD; i += 256) {
+        const int g = i / kD, c = i % kD;
+        float v = 0.f;
+        if (g < a.G) {
+            const int src = a.perm_k ? a.perm_k[kvh * kD + c] : c;
+            v = load_as_float(a.q, dt, ((int64_t)b * a.H_q + h0 + g) * kD + src) * a.scale_log2e * (float)(1 << kShift);
+        }
+        q_s[g][c] = v;
+    }
+    __syncthreads();
+
+    // A operands of the score product: row r = lane%16 = 4*head + limb, k-slot (kg, x) of MFMA d
+    // is channel 32*kg + 8*d + slot_channel(x).
+    bf16x8 aq[HG][4];
+    {
+        const int gi = j >> 2, limb = j & 3;
+#pragma unroll
+        for (int hg = 0; hg < HG; ++hg)
+#pragma unroll
+            for (int d = 0; d < 4; ++d)
+#pragma unroll
+                for (int x = 0; x < 8; ++x) {
+                    const float f = q_s[hg * 4 + gi][32 * kg + 8 * d + slot_channel(x)];
+                    const __bf16 l0 = (__bf16)f;
+                    const float r1 = f - (float)l0;
+                    const __bf16 l1 = (__bf16)r1;
+                    const float r2 = r1 - (float)l1;
+                    const __bf16 l2 = (__bf16)r2;
+                    aq[hg][d][x] = limb == 0 ? l0 : (limb == 1 ? l1 : (limb == 2 ? l2 : (__bf16)0.0f));
+                }
+    }
+
+    // selectors that place a probability in the low (parity 0) or high (parity 1) half of an
+    // A register of the value product; row r = j = 4*head + 2*parity + limb
+    const int a_head = j >> 2, a_par = (j >> 1) & 1, a_limb = j & 1;
+    const uint32_t sel_even = a_par ? 0x01000c0cu : 0x0c0c0100u;   // halfword 0 of the source
+    const uint32_t sel_odd = a_par ? 0x03020c0cu : 0x0c0c0302u;    // halfword 1 of the source
+
+    const int64_t base = ((int64_t)b * a.H_kv + kvh) * a.max_seq;
+    const uint8_t* k_mant = a.k_mant + base * 64;
+    const uint8_t* v_mant = a.v_mant + base * 64;
+    const uint8_t* k_exp = a.k_exp + base * NB;
+    const uint8_t* v_exp = a.v_exp + base * NB;
+    const int64_t t_last = t_end - 1;
+
+    float m_run[HG], l_run[HG];
+    f32x4 o_acc[HG][4];
+#pragma unroll
+    for (int hg = 0; hg < HG; ++hg) {
+        m_run[hg] = -INFINITY;
+        l_run[hg] = 0.f;
+#pragma unroll
+        for (int m = 0; m < 4; ++m) o_acc[hg][m] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    for (int64_t T0 = t_begin + (int64_t)wave * kSuper; T0 < t_end; T0 += kWaves * kSuper) {
+        // ---------------- scores of 64 tokens
+        f32x4 s_acc[HG][4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t row = min(T0 + 16 * u + j, t_last);          // clamped: tail tokens are masked below
+            const u32x4 raw = *(const u32x4*)(k_mant + row * 64 + kg * 16);
+            float sc0, sc1;
+            if (N == 16) {
+                const uint32_t e2 = *(const uint16_t*)(k_exp + row * NB + 2 * kg);
+                sc0 = scale_operand(e2 & 0xFFu);
+                sc1 = scale_operand(e2 >> 8);
+            } else {
+                const int idx = N == 32 ? kg : (N == 64 ? (kg >> 1) : 0);
+                sc0 = sc1 = scale_operand(k_exp[row * NB + idx]);
+            }
+#pragma unroll
+            for (int hg = 0; hg < HG; ++hg) s_acc[hg][u] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const Unpacked kk = unpack8(raw[d], d < 2 ? sc0 : sc1);
+                const bf16x8 bk = join(kk.p[0], kk.p[1], kk.p[2], kk.p[3]);
+#pragma unroll
+                for (int hg = 0; hg < HG; ++hg)
+                    s_acc[hg][u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aq[hg][d], bk, s_acc[hg][u], 0, 0, 0);
+            }
+        }
+
+        // ---------------- online softmax; lane (j, kg) owns head kg of each group, tokens 16u + j
+#pragma unroll
+        for (int hg = 0; hg < HG; ++hg) {
+            float s[4];
+            float tmax = -INFINITY;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float v = s_acc[hg][u][0] + s_acc[hg][u][1] + s_acc[hg][u][2];   // the three limbs
+                s[u] = (T0 + 16 * u + j < t_end) ? v : -INFINITY;
+                tmax = fmaxf(tmax, s[u]);
+            }
+            tmax = row_max(tmax);                                   // finite: the tile holds a cached token
+            const float m_new = fmaxf(m_run[hg], tmax);
+            const float alpha = exp2f(m_run[hg] - m_new);           // 0 on the first tile
+            float psum = 0.f;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float pw = exp2f(s[u] - m_new);
+                const __bf16 ph = (__bf16)pw;
+                const __bf16 pl = (__bf16)(pw - (float)ph);
+                psum += (float)ph + (float)pl;
+                p_s[wave][hg][0][kg][16 * u + j] = __builtin_bit_cast(unsigned short, ph);
+                p_s[wave][hg][1][kg][16 * u + j] = __builtin_bit_cast(unsigned short, pl);
+            }
+            l_run[hg] = l_run[hg] * alpha + psum;                   // per-lane partial; summed at the end
+            m_run[hg] = m_new;
+#pragma unroll
+            for (int m = 0; m < 4; ++m) o_acc[hg][m] *= alpha;      // this lane's rows all belong to head kg
+        }
+
+        // the probabilities just written are read back below by other lanes of this wavefront
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+        // ---------------- values of the same 64 tokens
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            Unpacked vv[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int64_t row = min(T0 + 16 * u + 4 * kg + i, t_last);
+                const uint32_t w = *(const uint32_t*)(v_mant + row * 64 + 4 * j);
+                const uint32_t E = v_exp[row * NB + ((8 * j) / N)];
+                vv[i] = unpack8(w, scale_operand(E));
+            }
+#pragma unroll
+            for (int hg = 0; hg < HG; ++hg) {
+                // probabilities of tokens 16u + 4kg .. +3 for this lane's row (head, parity, limb)
+                const uint2 pp = *(const uint2*)&p_s[wave][hg][a_limb][a_head][16 * u + 4 * kg];
+                uint32_t ar[4];
+                ar[0] = __builtin_amdgcn_perm(pp.x, pp.x, sel_even);
+                ar[1] = __builtin_amdgcn_perm(pp.x, pp.x, sel_odd);
+                ar[2] = __builtin_amdgcn_perm(pp.y, pp.y, sel_even);
+                ar[3] = __builtin_amdgcn_perm(pp.y, pp.y, sel_odd);
+                const bf16x8 ap = __builtin_bit_cast(bf16x8, u32x4{ar[0], ar[1], ar[2], ar[3]});
+#pragma unroll
+                for (int m = 0; m < 4; ++m) {
+                    const bf16x8 bv = join(vv[0].p[m], vv[1].p[m], vv[2].p[m], vv[3].p[m]);
+                    o_acc[hg][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ap, bv, o_acc[hg][m], 0, 0, 0);
+                }
+            }
+        }
+        // the next tile overwrites the probability buffer
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+
+    // ---------------- per-wavefront result to LDS: lane (j, kg) holds head kg, channels 8j..8j+7
+#pragma unroll
+    for (int hg = 0; hg < HG; ++hg) {
+        const float lsum = row_sum(l_run[hg]);
+        const int head = hg * 4 + kg;
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            // rows (parity 0: hi, lo), (parity 1: hi, lo); MFMA m holds slots (m) -> channels below
+            const int c_even = 8 * j + slot_channel(2 * m);       // parity 0 channel of pair m
+            const int c_odd = 8 * j + slot_channel(2 * m + 1);    // parity 1 channel of pair m
+            o_s[wave][head][c_even] = o_acc[hg][m][0] + o_acc[hg][m][1];
+            o_s[wave][head][c_odd] = o_acc[hg][m][2] + o_acc[hg][m][3];
+        }
+        if (j == 0) {
+            ml_s[wave][head][0] = m_run[hg];
+            ml_s[wave][head][1] = lsum;
+        }
+    }
+    __syncthreads();
+
+    // ---------------- merge the four wavefronts, write this split's partial result
+    for (int i = tid; i < a.G * kD; i += 256) {
+        const int g = i / kD, c = i % kD;
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) M = fmaxf(M, ml_s[w][g][0]);
+        float acc = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const float mw = ml_s[w][g][0];
+            if (mw > -INFINITY) acc = fmaf(exp2f(mw - M), o_s[w][g][c], acc);
+        }
+        a.part_o[(((int64_t)b * a.H_q + h0 + g) * a.n_splits + split) * kD + c] = acc * (float)(1 << kShift);
+    }
+    if (tid < a.G) {
+        const int g = tid;
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) M = fmaxf(M, ml_s[w][g][0]);
+        float lsum = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const float mw = ml_s[w][g][0];
+            if (mw > -INFINITY) lsum = fmaf(exp2f(mw - M), ml_s[w][g][1], lsum);
+        }
+        float* ml = a.part_ml + (((int64_t)b * a.H_q + h0 + g) * a.n_splits + split) * 2;
+        ml[0] = M;
+        ml[1] = lsum;
+    }
+}
+
+template <int HG>
+hipError_t launch_n(const DecodeArgs& a, int dt, int block, dim3 grid, hipStream_t s) {
+    switch (block) {
+        case 16: decode_split_mfma_p4<16, HG><<<grid, 256, 0, s>>>(a, dt); break;
+        case 32: decode_split_mfma_p4<32, HG><<<grid, 256, 0, s>>>(a, dt); break;
+        case 64: decode_split_mfma_p4<64, HG><<<grid, 256, 0, s>>>(a, dt); break;
+        default: decode_split_mfma_p4<128, HG><<<grid, 256, 0, s>>>(a, dt); break;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+namespace kvbfp {
+
+hipError_t launch_decode_split_mfma(const DecodeArgs& a, int dtype, int block, int batch, hipStream_t s) {
+    const dim3 grid((unsigned)a.n_splits, (unsigned)a.H_kv, (unsigned)batch);
+    if (a.G <= 4) return launch_n<1>(a, dtype, block, grid, s);
+    return launch_n<2>(a, dtype, block, grid, s);
+}
+
+}  // namespace kvbfp
