@@ -28,6 +28,7 @@
 
 #include <cmath>
 #include <cstdint>
+#include <type_traits>
 
 #include "decode_args.h"
 #include "kvbfp_internal.h"
@@ -79,8 +80,9 @@ __device__ __forceinline__ float load_as_float(const void* p, int dt, int64_t i)
 // it equals m * 2^(E - 127 - 2) * 2^-kShift.  Only the exponent field of the operand is used by the
 // conversion; exponent bytes below 10 (magnitudes under 2^-116) collapse to the smallest scale.
 __device__ __forceinline__ float scale_operand(uint32_t E) {
-    const int f = (int)E + 7 - kShift;      // (E - 129 + 9 - kShift) + 127
-    return __uint_as_float((uint32_t)max(f, 0) << 23);
+    // exponent field (E - 129 + 9 - kShift) + 127 = E - (kShift - 7), saturating at 0
+    const unsigned short f = __builtin_elementwise_sub_sat((unsigned short)E, (unsigned short)(kShift - 7));
+    return __uint_as_float((uint32_t)f << 23);
 }
 
 // 8 sign-magnitude nibbles -> 8 bf16 values in slot order [c0,c2,c4,c6,c1,c3,c5,c7]
@@ -176,12 +178,14 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
     const uint32_t sel_even = a_par ? 0x01000c0cu : 0x0c0c0100u;   // halfword 0 of the source
     const uint32_t sel_odd = a_par ? 0x03020c0cu : 0x0c0c0302u;    // halfword 1 of the source
 
-    const int64_t base = ((int64_t)b * a.H_kv + kvh) * a.max_seq;
-    const uint8_t* k_mant = a.k_mant + base * 64;
-    const uint8_t* v_mant = a.v_mant + base * 64;
-    const uint8_t* k_exp = a.k_exp + base * NB;
-    const uint8_t* v_exp = a.v_exp + base * NB;
-    const int64_t t_last = t_end - 1;
+    // Plane bases of this (batch, kv-head) are wave-uniform (scalar registers); everything inside
+    // the split is addressed with 32-bit offsets from them.
+    const int64_t base = ((int64_t)b * a.H_kv + kvh) * a.max_seq + t_begin;
+    const uint8_t* __restrict__ k_mant = a.k_mant + base * 64;
+    const uint8_t* __restrict__ v_mant = a.v_mant + base * 64;
+    const uint8_t* __restrict__ k_exp = a.k_exp + base * NB;
+    const uint8_t* __restrict__ v_exp = a.v_exp + base * NB;
+    const int n_tok = (int)(t_end - t_begin);       // tokens of this split, <= split_len
 
     float m_run[HG], l_run[HG];
     f32x4 o_acc[HG][4];
@@ -193,21 +197,44 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
         for (int m = 0; m < 4; ++m) o_acc[hg][m] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    for (int64_t T0 = t_begin + (int64_t)wave * kSuper; T0 < t_end; T0 += kWaves * kSuper) {
+    // Per-lane byte offsets inside a 64-token tile; the tile's base pointers are wave-uniform, so a
+    // load is (scalar base) + (this lane offset) + (compile-time constant).
+    const uint32_t koff = (uint32_t)j * 64u + (uint32_t)kg * 16u;                       // key row j, chunk kg
+    const uint32_t keoff = (uint32_t)j * NB + (N == 16 ? 2u * kg : (N == 32 ? (uint32_t)kg : (N == 64 ? (uint32_t)(kg >> 1) : 0u)));
+    const uint32_t voff = (uint32_t)(4 * kg) * 64u + 4u * (uint32_t)j;                  // value rows 4kg.., dword j
+    const uint32_t veoff = (uint32_t)(4 * kg) * NB + (uint32_t)((8 * j) / N);
+
+    // One 64-token tile starting at token T0 of the split.  FULL: all 64 tokens are cached, no
+    // clamping or masking; otherwise rows are clamped to the last cached token and masked.
+    auto tile = [&](const int T0, auto full_tag) {
+        constexpr bool FULL = decltype(full_tag)::value;
+        const uint8_t* __restrict__ kp = k_mant + (size_t)T0 * 64;
+        const uint8_t* __restrict__ vp = v_mant + (size_t)T0 * 64;
+        const uint8_t* __restrict__ kep = k_exp + (size_t)T0 * NB;
+        const uint8_t* __restrict__ vep = v_exp + (size_t)T0 * NB;
+        const int left = n_tok - T0;                 // cached tokens from T0 on (>= 1)
+
         // ---------------- scores of 64 tokens
         f32x4 s_acc[HG][4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const int64_t row = min(T0 + 16 * u + j, t_last);          // clamped: tail tokens are masked below
-            const u32x4 raw = *(const u32x4*)(k_mant + row * 64 + kg * 16);
+            uint32_t mo, eo;
+            if (FULL) {
+                mo = koff + 1024u * u;
+                eo = keoff + 16u * NB * u;
+            } else {
+                const uint32_t r = (uint32_t)min(16 * u + j, left - 1);
+                mo = r * 64u + (uint32_t)kg * 16u;
+                eo = r * NB + (keoff - (uint32_t)j * NB);
+            }
+            const u32x4 raw = *(const u32x4*)(kp + mo);
             float sc0, sc1;
             if (N == 16) {
-                const uint32_t e2 = *(const uint16_t*)(k_exp + row * NB + 2 * kg);
+                const uint32_t e2 = *(const uint16_t*)(kep + eo);
                 sc0 = scale_operand(e2 & 0xFFu);
                 sc1 = scale_operand(e2 >> 8);
             } else {
-                const int idx = N == 32 ? kg : (N == 64 ? (kg >> 1) : 0);
-                sc0 = sc1 = scale_operand(k_exp[row * NB + idx]);
+                sc0 = sc1 = scale_operand(kep[eo]);
             }
 #pragma unroll
             for (int hg = 0; hg < HG; ++hg) s_acc[hg][u] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -229,12 +256,12 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const float v = s_acc[hg][u][0] + s_acc[hg][u][1] + s_acc[hg][u][2];   // the three limbs
-                s[u] = (T0 + 16 * u + j < t_end) ? v : -INFINITY;
+                s[u] = (FULL || 16 * u + j < left) ? v : -INFINITY;
                 tmax = fmaxf(tmax, s[u]);
             }
             tmax = row_max(tmax);                                   // finite: the tile holds a cached token
             const float m_new = fmaxf(m_run[hg], tmax);
-            const float alpha = exp2f(m_run[hg] - m_new);           // 0 on the first tile
+            const float alpha = exp2f(m_run[hg] - m_new);           // 0 on the first tile, 1 when the maximum stays
             float psum = 0.f;
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -247,8 +274,13 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
             }
             l_run[hg] = l_run[hg] * alpha + psum;                   // per-lane partial; summed at the end
             m_run[hg] = m_new;
+            // Rescale the running output only when some head's maximum moved (exact: alpha == 1
+            // otherwise).  The accumulators sit in the MFMA result registers, so skipping saves the
+            // round trip.  This lane's rows all belong to head kg.
+            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
-            for (int m = 0; m < 4; ++m) o_acc[hg][m] *= alpha;      // this lane's rows all belong to head kg
+                for (int m = 0; m < 4; ++m) o_acc[hg][m] *= alpha;
+            }
         }
 
         // the probabilities just written are read back below by other lanes of this wavefront
@@ -262,10 +294,17 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
             Unpacked vv[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const int64_t row = min(T0 + 16 * u + 4 * kg + i, t_last);
-                const uint32_t w = *(const uint32_t*)(v_mant + row * 64 + 4 * j);
-                const uint32_t E = v_exp[row * NB + ((8 * j) / N)];
-                vv[i] = unpack8(w, scale_operand(E));
+                uint32_t mo, eo;
+                if (FULL) {
+                    mo = voff + 64u * (16 * u + i);
+                    eo = veoff + NB * (16 * u + i);
+                } else {
+                    const uint32_t r = (uint32_t)min(16 * u + 4 * kg + i, left - 1);
+                    mo = r * 64u + 4u * (uint32_t)j;
+                    eo = r * NB + (uint32_t)((8 * j) / N);
+                }
+                const uint32_t w = *(const uint32_t*)(vp + mo);
+                vv[i] = unpack8(w, scale_operand(vep[eo]));
             }
 #pragma unroll
             for (int hg = 0; hg < HG; ++hg) {
@@ -288,6 +327,12 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+
+    {
+        int T0 = wave * kSuper;
+        for (; T0 + kSuper <= n_tok; T0 += kWaves * kSuper) tile(T0, std::true_type{});
+        if (T0 < n_tok) tile(T0, std::false_type{});     // at most one ragged tile per wavefront
     }
 
     // ---------------- per-wavefront result to LDS: lane (j, kg) holds head kg, channels 8j..8j+7
