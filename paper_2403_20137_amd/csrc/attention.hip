@@ -244,21 +244,58 @@ __device__ __forceinline__ uint16_t narrow_bf16(float v) {
 }
 
 // Pass 2: merge the splits of one (batch, query head).  grid = (H_q, B), block = 128 (one channel
-// per thread).
+// per thread).  The (m, l) pairs go through LDS once; the partial outputs are read with eight
+// independent loads in flight per thread, so the pass costs a couple of memory round trips
+// rather than one per split.
 __global__ __launch_bounds__(kD) void decode_combine(DecodeArgs a, int dt) {
+    constexpr int kMaxLds = 1024;
+    __shared__ float w_s[kMaxLds];          // m_i, then the weight 2^(m_i - M)
+    __shared__ float l_s[kMaxLds];
     const int j = threadIdx.x;
     const int h = blockIdx.x, b = blockIdx.y;
     const int64_t bh = (int64_t)b * a.H_q + h;
     const float* ml = a.part_ml + bh * a.n_splits * 2;
     const float* po = a.part_o + bh * a.n_splits * kD;
-    float M = -INFINITY;
-    for (int i = 0; i < a.n_splits; ++i) M = fmaxf(M, ml[2 * i]);
+    const int n = a.n_splits;
     float num = 0.f, den = 0.f;
-    if (M > -INFINITY) {
-        for (int i = 0; i < a.n_splits; ++i) {
-            const float w = exp2f(ml[2 * i] - M);     // empty splits carry m = -inf -> weight 0
-            num = fmaf(w, po[(int64_t)i * kD + j], num);
-            den = fmaf(w, ml[2 * i + 1], den);
+    if (n <= kMaxLds) {
+        for (int i = j; i < n; i += kD) {
+            const float2 v = *(const float2*)(ml + 2 * i);
+            w_s[i] = v.x;
+            l_s[i] = v.y;
+        }
+        __syncthreads();
+        float M = -INFINITY;
+        for (int i = 0; i < n; ++i) M = fmaxf(M, w_s[i]);
+        __syncthreads();
+        if (M > -INFINITY) {
+            for (int i = j; i < n; i += kD) w_s[i] = exp2f(w_s[i] - M);   // empty splits carry m = -inf -> weight 0
+            __syncthreads();
+            int i = 0;
+            for (; i + 8 <= n; i += 8) {
+                float v[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) v[k] = po[(int64_t)(i + k) * kD + j];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    num = fmaf(w_s[i + k], v[k], num);
+                    den = fmaf(w_s[i + k], l_s[i + k], den);
+                }
+            }
+            for (; i < n; ++i) {
+                num = fmaf(w_s[i], po[(int64_t)i * kD + j], num);
+                den = fmaf(w_s[i], l_s[i], den);
+            }
+        }
+    } else {   // very many splits: plain two-pass loop
+        float M = -INFINITY;
+        for (int i = 0; i < n; ++i) M = fmaxf(M, ml[2 * i]);
+        if (M > -INFINITY) {
+            for (int i = 0; i < n; ++i) {
+                const float w = exp2f(ml[2 * i] - M);
+                num = fmaf(w, po[(int64_t)i * kD + j], num);
+                den = fmaf(w, ml[2 * i + 1], den);
+            }
         }
     }
     const float r = den > 0.f ? num / den : 0.f;

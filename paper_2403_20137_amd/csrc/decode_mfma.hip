@@ -386,11 +386,365 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
     }
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// LDS-staged variant (block 16 or 32): the same arithmetic, but the packed rows travel
+// global -> LDS by DMA (global_load_lds) instead of through registers, so every wavefront keeps
+// most of a 64-token tile in flight without holding registers for it.
+//
+// Each wavefront owns a private staging area of four 16-token stages for keys and four for values
+// (mantissas 1 KB + exponent bytes per stage).  A stage is re-filled for the wavefront's next tile
+// right after its last read, in the fixed order K0..K3, V0..V3, two DMA instructions per stage.
+// DMA completes in issue order, so when a stage is about to be read exactly seven younger stages
+// (14 instructions) may still be outstanding: one s_waitcnt vmcnt(14) per stage is the whole
+// synchronisation (vmcnt(0) once nothing is being re-filled any more).  The compiler does not
+// model the DMA -> ds_read dependency, hence the explicit waits and scheduling barriers; the main
+// loop contains no other vector-memory instruction.
+//
+// Key stage: DMA lane 4r+c fetches chunk c ^ (r/4 % 4) of row r (four neighbouring lanes cover one
+// 64-byte row, so the global access coalesces like a linear copy); lane (j, kg) then reads slot
+// 4j + (kg ^ (j/4 % 4)), which spreads every group of 16 lanes over all banks.  Value stage: the 16 rows are stored in the order 4*(row%4) + row/4, which makes the
+// dword reads of lanes (j, kg) -> row 4kg+i, dword j hit 64 different banks.
+#define KVBFP_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
+#define KVBFP_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+constexpr int vmcnt_imm(int n) { return (n & 0xF) | (0x7 << 4) | (0xF << 8) | ((n >> 4) << 14); }
+
+template <int N, int HG>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4)))
+void decode_split_lds_p4(DecodeArgs a, int dt) {
+    static_assert(N == 16 || N == 32, "LDS pipeline is built for blocks of 16 or 32");
+    constexpr int NB = kD / N;
+    constexpr int NH = HG * 4;
+    constexpr int kTileTok = 64;
+    // per-wavefront staging area
+    constexpr int kKm = 0;                         // 4 stages x 1024 B key mantissas
+    constexpr int kVm = kKm + 4096;                // 4 stages x 1024 B value mantissas
+    constexpr int kKe = kVm + 4096;                // 4 stages x 64 lanes x 4 B key exponents (own dword per lane)
+    constexpr int kVe = kKe + 1024;                // 4 stages x 16 tokens x NB value exponents
+    constexpr int kPs = kVe + 4 * 16 * NB;         // probabilities: [HG][2 limbs][4 heads][64 tokens] bf16
+    constexpr int kWaveBytes = kPs + HG * 2 * 4 * kTileTok * 2;
+    constexpr int kQl = kWaves * kWaveBytes;       // query limbs: [NH*4 rows][128] bf16, slot order
+    constexpr int kTotal = kQl + NH * 4 * kD * 2;
+    static_assert(kWaves * NH * kD * 4 + kWaves * NH * 8 <= kQl, "merge buffers alias the staging area");
+    __shared__ __align__(16) uint8_t smem[kTotal];
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int j = lane & 15, kg = lane >> 4;
+    const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+    const int h0 = kvh * a.G;
+
+    int64_t L = a.seq_len ? (int64_t)a.seq_len[b] : a.max_len;
+    L = L < 0 ? 0 : (L > a.max_len ? a.max_len : L);
+    const int64_t t_begin = (int64_t)split * a.split_len;
+    const int64_t t_end = min(t_begin + a.split_len, L);
+
+    if (t_begin >= t_end) {   // nothing cached in this split
+        for (int i = tid; i < a.G * kD; i += 256)
+            a.part_o[(((int64_t)b * a.H_q + h0 + i / kD) * a.n_splits + split) * kD + (i % kD)] = 0.f;
+        if (tid < a.G) {
+            float* ml = a.part_ml + (((int64_t)b * a.H_q + h0 + tid) * a.n_splits + split) * 2;
+            ml[0] = -INFINITY;
+            ml[1] = 0.f;
+        }
+        return;
+    }
+
+    const int64_t base = ((int64_t)b * a.H_kv + kvh) * a.max_seq + t_begin;
+    const uint8_t* __restrict__ k_mant = a.k_mant + base * 64;
+    const uint8_t* __restrict__ v_mant = a.v_mant + base * 64;
+    const uint8_t* __restrict__ k_exp = a.k_exp + base * NB;
+    const uint8_t* __restrict__ v_exp = a.v_exp + base * NB;
+    const int n_tok = (int)(t_end - t_begin);
+
+    uint8_t* const wbase = smem + wave * kWaveBytes;
+
+    // ---- DMA source offsets of this lane inside a 16-token stage (full stage) -------------------
+    // keys: own chunk; values: slot (position p = lane/4, chunk c = lane%4) <- row 4*(p%4) + p/4
+    const int vp_pos = lane >> 2, vp_c = lane & 3;
+    const int vrow_of_slot = 4 * (vp_pos & 3) + (vp_pos >> 2);
+    const int kd_row = lane >> 2, kd_chunk = (lane & 3) ^ ((lane >> 4) & 3);            // DMA lane -> (row, chunk)
+    const uint32_t k_src = (uint32_t)kd_row * 64u + (uint32_t)kd_chunk * 16u;
+    const uint32_t v_src = (uint32_t)vrow_of_slot * 64u + (uint32_t)vp_c * 16u;
+    const uint32_t ke_src = (uint32_t)j * NB + (N == 16 ? 4u * (uint32_t)(kg >> 1) : 0u);   // dword holding this lane's byte(s)
+    const uint32_t ve_src = (uint32_t)lane * 4u;                                           // linear, lanes < 4*NB
+
+    // Fills stage u (keys or values) with the 16 tokens starting at token t of the split.
+    auto fill_keys = [&](const int u, const int t) {
+        const int left = n_tok - t;                // may be <= 0 for stages past the end: clamp to the last token
+        const uint8_t* mp = k_mant + (int64_t)t * 64;
+        const uint8_t* ep = k_exp + (int64_t)t * NB;
+        uint32_t mo = k_src, eo = ke_src;
+        if (left < 16) {
+            // left - 1 may be negative: rows before t are cached too
+            mo = (uint32_t)(min(kd_row, left - 1) * 64 + kd_chunk * 16);
+            eo = (uint32_t)(min(j, left - 1) * NB + (N == 16 ? 4 * (kg >> 1) : 0));
+        }
+        __builtin_amdgcn_global_load_lds(KVBFP_GPTR(mp + (int32_t)mo), KVBFP_LPTR(wbase + kKm + u * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(KVBFP_GPTR(ep + (int32_t)eo), KVBFP_LPTR(wbase + kKe + u * 256), 4, 0, 0);
+    };
+    auto fill_vals = [&](const int u, const int t) {
+        const int left = n_tok - t;
+        const uint8_t* mp = v_mant + (int64_t)t * 64;
+        const uint8_t* ep = v_exp + (int64_t)t * NB;
+        uint32_t mo = v_src;
+        int eo = (int)ve_src;
+        if (left < 16) {
+            const int r = min(vrow_of_slot, left - 1);
+            mo = (uint32_t)(r * 64 + vp_c * 16);
+            // exponent bytes are fetched as linear dwords; past the last token re-read the last row's
+            const int tok = min((int)(ve_src / NB), left - 1);
+            eo = tok * NB + (int)(ve_src % NB);
+        }
+        __builtin_amdgcn_global_load_lds(KVBFP_GPTR(mp + (int32_t)mo), KVBFP_LPTR(wbase + kVm + u * 1024), 16, 0, 0);
+        // only the first 4*NB lanes carry exponent bytes (the stage holds 16*NB of them); the
+        // instruction is still issued once per wavefront, which is what the vmcnt bookkeeping counts
+        if (lane < 4 * NB)
+            __builtin_amdgcn_global_load_lds(KVBFP_GPTR(ep + eo), KVBFP_LPTR(wbase + kVe + u * 16 * NB), 4, 0, 0);
+    };
+
+    // ---- first tile of this wavefront goes out before anything else ------------------------------
+    const int T_first = wave * kTileTok;
+    const bool has_work = T_first < n_tok;
+    if (has_work) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) fill_keys(u, T_first + 16 * u);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) fill_vals(u, T_first + 16 * u);
+    }
+
+    // ---- query limbs to LDS (whole workgroup), in MFMA slot order ---------------------------------
+    // row 4*head + limb; position 32*kg + 8*d + x holds channel 32*kg + 8*d + slot_channel(x)
+    {
+        uint16_t* ql = (uint16_t*)(smem + kQl);
+        for (int i = tid; i < NH * kD; i += 256) {
+            const int g = i / kD, pos = i % kD;
+            const int c = (pos & ~7) + slot_channel(pos & 7);
+            float f = 0.f;
+            if (g < a.G) {
+                const int src = a.perm_k ? a.perm_k[kvh * kD + c] : c;
+                f = load_as_float(a.q, dt, ((int64_t)b * a.H_q + h0 + g) * kD + src) * a.scale_log2e * (float)(1 << kShift);
+            }
+            const __bf16 l0 = (__bf16)f;
+            const float r1 = f - (float)l0;
+            const __bf16 l1 = (__bf16)r1;
+            const __bf16 l2 = (__bf16)(r1 - (float)l1);
+            ql[(4 * g + 0) * kD + pos] = __builtin_bit_cast(unsigned short, l0);
+            ql[(4 * g + 1) * kD + pos] = __builtin_bit_cast(unsigned short, l1);
+            ql[(4 * g + 2) * kD + pos] = __builtin_bit_cast(unsigned short, l2);
+            ql[(4 * g + 3) * kD + pos] = 0;
+        }
+    }
+    __syncthreads();
+    bf16x8 aq[HG][4];
+#pragma unroll
+    for (int hg = 0; hg < HG; ++hg)
+#pragma unroll
+        for (int d = 0; d < 4; ++d)
+            aq[hg][d] = *(const bf16x8*)(smem + kQl + ((hg * 16 + j) * kD + 32 * kg + 8 * d) * 2);
+
+    const int a_head = j >> 2, a_par = (j >> 1) & 1, a_limb = j & 1;
+    const uint32_t sel_even = a_par ? 0x01000c0cu : 0x0c0c0100u;
+    const uint32_t sel_odd = a_par ? 0x03020c0cu : 0x0c0c0302u;
+
+    float m_run[HG], l_run[HG];
+    f32x4 o_acc[HG][4];
+#pragma unroll
+    for (int hg = 0; hg < HG; ++hg) {
+        m_run[hg] = -INFINITY;
+        l_run[hg] = 0.f;
+#pragma unroll
+        for (int m = 0; m < 4; ++m) o_acc[hg][m] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    // ---- LDS read offsets of this lane inside a stage --------------------------------------------
+    const uint8_t* const kq = wbase + kKm + (4 * j + (kg ^ ((j >> 2) & 3))) * 16;           // row j, chunk kg
+    const uint8_t* const keq = wbase + kKe + lane * 4 + (N == 32 ? kg : 2 * (kg & 1));     // own exponent byte(s)
+    const uint8_t* const vq = wbase + kVm + kg * 64 + j * 4;                               // + i*256: row 4kg+i sits at position 4i+kg
+    const uint8_t* const veq = wbase + kVe + (4 * kg) * NB + (8 * j) / N;                  // + i*NB
+    uint16_t* const ps = (uint16_t*)(wbase + kPs);
+
+    if (has_work) {
+        constexpr int kStep = kWaves * kTileTok;
+        for (int T0 = T_first; T0 < n_tok; T0 += kStep) {
+            const int T1 = T0 + kStep;
+            const bool more = T1 < n_tok;            // wave-uniform
+            const int left = n_tok - T0;
+
+            // ---------------- scores
+            f32x4 s_acc[HG][4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                __builtin_amdgcn_sched_barrier(0);
+                if (more) __builtin_amdgcn_s_waitcnt(vmcnt_imm(14)); else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+                __builtin_amdgcn_sched_barrier(0);
+                const u32x4 raw = *(const u32x4*)(kq + u * 1024);
+                float sc0, sc1;
+                if (N == 16) {
+                    const uint32_t e2 = *(const uint16_t*)(keq + u * 256);
+                    sc0 = scale_operand(e2 & 0xFFu);
+                    sc1 = scale_operand(e2 >> 8);
+                } else {
+                    sc0 = sc1 = scale_operand(*(keq + u * 256));
+                }
+#pragma unroll
+                for (int hg = 0; hg < HG; ++hg) s_acc[hg][u] = f32x4{0.f, 0.f, 0.f, 0.f};
+                Unpacked kk[4];
+#pragma unroll
+                for (int d = 0; d < 4; ++d) kk[d] = unpack8(raw[d], d < 2 ? sc0 : sc1);
+                // the stage has been read into registers: re-fill it for the next tile
+                __builtin_amdgcn_sched_barrier(0);
+                if (more) fill_keys(u, T1 + 16 * u);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    const bf16x8 bk = join(kk[d].p[0], kk[d].p[1], kk[d].p[2], kk[d].p[3]);
+#pragma unroll
+                    for (int hg = 0; hg < HG; ++hg)
+                        s_acc[hg][u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aq[hg][d], bk, s_acc[hg][u], 0, 0, 0);
+                }
+            }
+
+            // ---------------- online softmax; lane (j, kg) owns head kg of each group, tokens 16u + j
+#pragma unroll
+            for (int hg = 0; hg < HG; ++hg) {
+                float s[4];
+                float tmax = -INFINITY;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const float v = s_acc[hg][u][0] + s_acc[hg][u][1] + s_acc[hg][u][2];
+                    s[u] = (16 * u + j < left) ? v : -INFINITY;
+                    tmax = fmaxf(tmax, s[u]);
+                }
+                tmax = row_max(tmax);
+                const float m_new = fmaxf(m_run[hg], tmax);
+                const float alpha = exp2f(m_run[hg] - m_new);
+                float psum = 0.f;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const float pw = exp2f(s[u] - m_new);
+                    const __bf16 ph = (__bf16)pw;
+                    const __bf16 pl = (__bf16)(pw - (float)ph);
+                    psum += (float)ph + (float)pl;
+                    ps[((hg * 2 + 0) * 4 + kg) * kTileTok + 16 * u + j] = __builtin_bit_cast(unsigned short, ph);
+                    ps[((hg * 2 + 1) * 4 + kg) * kTileTok + 16 * u + j] = __builtin_bit_cast(unsigned short, pl);
+                }
+                l_run[hg] = l_run[hg] * alpha + psum;
+                m_run[hg] = m_new;
+                if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+                    for (int m = 0; m < 4; ++m) o_acc[hg][m] *= alpha;
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+            // ---------------- values
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                __builtin_amdgcn_sched_barrier(0);
+                if (more) __builtin_amdgcn_s_waitcnt(vmcnt_imm(14)); else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+                __builtin_amdgcn_sched_barrier(0);
+                Unpacked vv[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t w = *(const uint32_t*)(vq + u * 1024 + i * 256);
+                    const uint32_t E = *(veq + u * 16 * NB + i * NB);
+                    vv[i] = unpack8(w, scale_operand(E));
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (more) fill_vals(u, T1 + 16 * u);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int hg = 0; hg < HG; ++hg) {
+                    const uint2 pp = *(const uint2*)&ps[((hg * 2 + a_limb) * 4 + a_head) * kTileTok + 16 * u + 4 * kg];
+                    uint32_t ar[4];
+                    ar[0] = __builtin_amdgcn_perm(pp.x, pp.x, sel_even);
+                    ar[1] = __builtin_amdgcn_perm(pp.x, pp.x, sel_odd);
+                    ar[2] = __builtin_amdgcn_perm(pp.y, pp.y, sel_even);
+                    ar[3] = __builtin_amdgcn_perm(pp.y, pp.y, sel_odd);
+                    const bf16x8 ap = __builtin_bit_cast(bf16x8, u32x4{ar[0], ar[1], ar[2], ar[3]});
+#pragma unroll
+                    for (int m = 0; m < 4; ++m) {
+                        const bf16x8 bv = join(vv[0].p[m], vv[1].p[m], vv[2].p[m], vv[3].p[m]);
+                        o_acc[hg][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ap, bv, o_acc[hg][m], 0, 0, 0);
+                    }
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+    }
+
+    // ---- merge the four wavefronts (buffers alias the staging areas, all DMA has landed) ---------
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __syncthreads();
+    float* const o_s = (float*)smem;                              // [kWaves][NH][kD]
+    float* const ml_s = (float*)(smem + kWaves * NH * kD * 4);    // [kWaves][NH][2]
+#pragma unroll
+    for (int hg = 0; hg < HG; ++hg) {
+        const float lsum = row_sum(l_run[hg]);
+        const int head = hg * 4 + kg;
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const int c_even = 8 * j + slot_channel(2 * m);
+            const int c_odd = 8 * j + slot_channel(2 * m + 1);
+            o_s[(wave * NH + head) * kD + c_even] = o_acc[hg][m][0] + o_acc[hg][m][1];
+            o_s[(wave * NH + head) * kD + c_odd] = o_acc[hg][m][2] + o_acc[hg][m][3];
+        }
+        if (j == 0) {
+            ml_s[(wave * NH + head) * 2 + 0] = m_run[hg];
+            ml_s[(wave * NH + head) * 2 + 1] = lsum;
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < a.G * kD; i += 256) {
+        const int g = i / kD, c = i % kD;
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) M = fmaxf(M, ml_s[(w * NH + g) * 2]);
+        float acc = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const float mw = ml_s[(w * NH + g) * 2];
+            if (mw > -INFINITY) acc = fmaf(exp2f(mw - M), o_s[(w * NH + g) * kD + c], acc);
+        }
+        a.part_o[(((int64_t)b * a.H_q + h0 + g) * a.n_splits + split) * kD + c] = acc * (float)(1 << kShift);
+    }
+    if (tid < a.G) {
+        const int g = tid;
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) M = fmaxf(M, ml_s[(w * NH + g) * 2]);
+        float lsum = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const float mw = ml_s[(w * NH + g) * 2];
+            if (mw > -INFINITY) lsum = fmaf(exp2f(mw - M), ml_s[(w * NH + g) * 2 + 1], lsum);
+        }
+        float* ml = a.part_ml + (((int64_t)b * a.H_q + h0 + g) * a.n_splits + split) * 2;
+        ml[0] = M;
+        ml[1] = lsum;
+    }
+}
+
+// Which split pass serves blocks of 16 and 32: the LDS-staged pipeline or the register-staged one.
+constexpr bool kUseLdsPipeline = false;
+
 template <int HG>
 hipError_t launch_n(const DecodeArgs& a, int dt, int block, dim3 grid, hipStream_t s) {
     switch (block) {
-        case 16: decode_split_mfma_p4<16, HG><<<grid, 256, 0, s>>>(a, dt); break;
-        case 32: decode_split_mfma_p4<32, HG><<<grid, 256, 0, s>>>(a, dt); break;
+        case 16:
+            if (kUseLdsPipeline) decode_split_lds_p4<16, HG><<<grid, 256, 0, s>>>(a, dt);
+            else decode_split_mfma_p4<16, HG><<<grid, 256, 0, s>>>(a, dt);
+            break;
+        case 32:
+            if (kUseLdsPipeline) decode_split_lds_p4<32, HG><<<grid, 256, 0, s>>>(a, dt);
+            else decode_split_mfma_p4<32, HG><<<grid, 256, 0, s>>>(a, dt);
+            break;
         case 64: decode_split_mfma_p4<64, HG><<<grid, 256, 0, s>>>(a, dt); break;
         default: decode_split_mfma_p4<128, HG><<<grid, 256, 0, s>>>(a, dt); break;
     }
