@@ -175,6 +175,9 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="distinct layer caches in the ring (0 = enough for >= 1 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 1 GiB device copy a few times (known HBM bytes; used to scale "
+                         "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); --gpus %d is not "
@@ -184,6 +187,15 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     kvbfp.lib()     # fail loudly if the HIP library has not been built
+    if args.calibrate_copy:
+        n = 1 << 30
+        src = torch.full((n,), 7, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n, "launches": 5}))
+        return
 
     w = synth.WORKLOADS[args.workload]
     n_layers = args.layers or max(2, -(-1_100_000_000 // w.cache_bytes(w.seq + 1)))
