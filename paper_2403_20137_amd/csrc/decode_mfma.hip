@@ -29,6 +29,7 @@
 #include <cmath>
 #include <cstdint>
 #include <type_traits>
+#include <utility>
 
 #include "decode_args.h"
 #include "kvbfp_internal.h"
@@ -41,6 +42,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
 
 constexpr int kD = 128;
 constexpr int kWaves = 4;
@@ -408,6 +410,53 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
 #define KVBFP_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define KVBFP_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
 
+// Compile-time loop: f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N-1>{}).
+template <int... I, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F&& f) { (f(std::integral_constant<int, I>{}), ...); }
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) { static_for_impl(std::make_integer_sequence<int, N>{}, f); }
+
+// LDS byte address of a pointer into __shared__ memory.
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+    return (uint32_t)(unsigned long)(__attribute__((address_space(3))) const uint8_t*)p;
+}
+
+// Reads of DMA-staged data are written in assembly: the compiler's wait-count pass half-knows about
+// LDS DMA and would otherwise put a full vmcnt(0) in front of some of these loads, which serialises
+// the whole pipeline.  Each block waits for its own LDS results before returning.
+template <int OFF_M, int OFF_E, bool E16>
+__device__ __forceinline__ void lds_read_key_stage(uint32_t m_addr, uint32_t e_addr, u32x4& raw, uint32_t& e) {
+    if (E16)
+        asm volatile("ds_read_b128 %0, %2 offset:%4\n\tds_read_u16 %1, %3 offset:%5\n\ts_waitcnt lgkmcnt(0)"
+                     : "=&v"(raw), "=&v"(e) : "v"(m_addr), "v"(e_addr), "n"(OFF_M), "n"(OFF_E) : "memory");
+    else
+        asm volatile("ds_read_b128 %0, %2 offset:%4\n\tds_read_u8 %1, %3 offset:%5\n\ts_waitcnt lgkmcnt(0)"
+                     : "=&v"(raw), "=&v"(e) : "v"(m_addr), "v"(e_addr), "n"(OFF_M), "n"(OFF_E) : "memory");
+}
+template <int OFF>
+__device__ __forceinline__ uint2 lds_read_b64(uint32_t addr) {
+    uint64_t v;
+    asm volatile("ds_read_b64 %0, %1 offset:%2\n\ts_waitcnt lgkmcnt(0)" : "=&v"(v) : "v"(addr), "n"(OFF) : "memory");
+    return make_uint2((uint32_t)v, (uint32_t)(v >> 32));
+}
+// Value stage U: dwords at m_addr + 256*(4U+i), exponent bytes at e_addr + 256*U + NB*i, i = 0..3.
+template <int U, int NB>
+__device__ __forceinline__ void lds_read_val_stage(uint32_t m_addr, uint32_t e_addr, uint32_t (&w)[4], uint32_t (&e)[4]) {
+    uint64_t w01, w23;
+    asm volatile("ds_read2st64_b32 %0, %6 offset0:%8 offset1:%9\n\t"
+                 "ds_read2st64_b32 %1, %6 offset0:%10 offset1:%11\n\t"
+                 "ds_read_u8 %2, %7 offset:%12\n\t"
+                 "ds_read_u8 %3, %7 offset:%13\n\t"
+                 "ds_read_u8 %4, %7 offset:%14\n\t"
+                 "ds_read_u8 %5, %7 offset:%15\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(w01), "=&v"(w23), "=&v"(e[0]), "=&v"(e[1]), "=&v"(e[2]), "=&v"(e[3])
+                 : "v"(m_addr), "v"(e_addr), "n"(4 * U), "n"(4 * U + 1), "n"(4 * U + 2), "n"(4 * U + 3),
+                   "n"(256 * U), "n"(256 * U + NB), "n"(256 * U + 2 * NB), "n"(256 * U + 3 * NB)
+                 : "memory");
+    w[0] = (uint32_t)w01; w[1] = (uint32_t)(w01 >> 32); w[2] = (uint32_t)w23; w[3] = (uint32_t)(w23 >> 32);
+}
+
 constexpr int vmcnt_imm(int n) { return (n & 0xF) | (0x7 << 4) | (0xF << 8) | ((n >> 4) << 14); }
 
 template <int N, int HG>
@@ -421,16 +470,23 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
     constexpr int kKm = 0;                         // 4 stages x 1024 B key mantissas
     constexpr int kVm = kKm + 4096;                // 4 stages x 1024 B value mantissas
     constexpr int kKe = kVm + 4096;                // 4 stages x 64 lanes x 4 B key exponents (own dword per lane)
-    constexpr int kVe = kKe + 1024;                // 4 stages x 16 tokens x NB value exponents
-    constexpr int kPs = kVe + 4 * 16 * NB;         // probabilities: [HG][2 limbs][4 heads][64 tokens] bf16
-    constexpr int kWaveBytes = kPs + HG * 2 * 4 * kTileTok * 2;
-    constexpr int kQl = kWaves * kWaveBytes;       // query limbs: [NH*4 rows][128] bf16, slot order
-    constexpr int kTotal = kQl + NH * 4 * kD * 2;
+    constexpr int kVe = kKe + 1024;                // 4 stages x 256 B: 16 tokens x NB value exponent bytes (+ duplicates)
+    constexpr int kWaveBytes = kVe + 1024;
+    // Blocks of 32 are exactly the MX block of the scaled MFMA: keys then go in as raw FP4 nibbles.
+    constexpr bool kFp4Keys = (N == 32);
+    constexpr int kQl = kWaves * kWaveBytes;       // query operand staging (limbs in MFMA operand order)
+    constexpr int kQf = kQl;                       // fp4 path: q' as fp32 [NH][128]
+    constexpr int kQ8 = kQf + NH * kD * 4;         //           FP8 limbs [NH*4 rows][128], then scale bytes [NH*4][4]
+    constexpr int kTotal = kFp4Keys ? kQ8 + NH * 4 * kD + NH * 16 : kQl + NH * 4 * kD * 2;
     static_assert(kWaves * NH * kD * 4 + kWaves * NH * 8 <= kQl, "merge buffers alias the staging area");
     __shared__ __align__(16) uint8_t smem[kTotal];
+    // probabilities of the current tile, bf16 hi/lo limbs: [wave][HG][2 limbs][4 heads][64 tokens].  A separate
+    // LDS object, so the compiler can tell its reads apart from the DMA targets inside smem.
+    __shared__ __align__(16) uint16_t p_lds[kWaves][HG * 2 * 4 * kTileTok];
 
     const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS bases stay in scalar registers
+    const int lane = tid & 63;
     const int j = lane & 15, kg = lane >> 4;
     const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
     const int h0 = kvh * a.G;
@@ -468,40 +524,46 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
     const uint32_t k_src = (uint32_t)kd_row * 64u + (uint32_t)kd_chunk * 16u;
     const uint32_t v_src = (uint32_t)vrow_of_slot * 64u + (uint32_t)vp_c * 16u;
     const uint32_t ke_src = (uint32_t)j * NB + (N == 16 ? 4u * (uint32_t)(kg >> 1) : 0u);   // dword holding this lane's byte(s)
-    const uint32_t ve_src = (uint32_t)lane * 4u;                                           // linear, lanes < 4*NB
+    // value exponents: the stage needs 16*NB bytes = 4*NB dwords; all 64 lanes fetch (lanes beyond
+    // 4*NB repeat earlier dwords into the unused rest of the 256-byte stage area) so that no lane
+    // masking is needed
+    const uint32_t ve_src = (uint32_t)(lane & (4 * NB - 1)) * 4u;
 
-    // Fills stage u (keys or values) with the 16 tokens starting at token t of the split.
+    // Fills stage u (keys or values) with the 16 tokens starting at token t of the split.  `left` is
+    // wave-uniform, so the ragged case is a scalar branch; rows past the last cached token re-read
+    // that token (left - 1 may be negative: earlier rows of the split are cached too).
     auto fill_keys = [&](const int u, const int t) {
-        const int left = n_tok - t;                // may be <= 0 for stages past the end: clamp to the last token
-        const uint8_t* mp = k_mant + (int64_t)t * 64;
-        const uint8_t* ep = k_exp + (int64_t)t * NB;
-        uint32_t mo = k_src, eo = ke_src;
-        if (left < 16) {
-            // left - 1 may be negative: rows before t are cached too
-            mo = (uint32_t)(min(kd_row, left - 1) * 64 + kd_chunk * 16);
-            eo = (uint32_t)(min(j, left - 1) * NB + (N == 16 ? 4 * (kg >> 1) : 0));
+        const int left = n_tok - t;
+        const uint8_t* __restrict__ mp = k_mant + (int64_t)t * 64;
+        const uint8_t* __restrict__ ep = k_exp + (int64_t)t * NB;
+        uint8_t* const lm = wbase + kKm + u * 1024;
+        uint8_t* const le = wbase + kKe + u * 256;
+        if (left >= 16) {
+            __builtin_amdgcn_global_load_lds(KVBFP_GPTR(mp + k_src), KVBFP_LPTR(lm), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(KVBFP_GPTR(ep + ke_src), KVBFP_LPTR(le), 4, 0, 0);
+        } else {
+            const int mo = min(kd_row, left - 1) * 64 + kd_chunk * 16;
+            const int eo = min(j, left - 1) * NB + (N == 16 ? 4 * (kg >> 1) : 0);
+            __builtin_amdgcn_global_load_lds(KVBFP_GPTR(mp + mo), KVBFP_LPTR(lm), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(KVBFP_GPTR(ep + eo), KVBFP_LPTR(le), 4, 0, 0);
         }
-        __builtin_amdgcn_global_load_lds(KVBFP_GPTR(mp + (int32_t)mo), KVBFP_LPTR(wbase + kKm + u * 1024), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds(KVBFP_GPTR(ep + (int32_t)eo), KVBFP_LPTR(wbase + kKe + u * 256), 4, 0, 0);
     };
     auto fill_vals = [&](const int u, const int t) {
         const int left = n_tok - t;
-        const uint8_t* mp = v_mant + (int64_t)t * 64;
-        const uint8_t* ep = v_exp + (int64_t)t * NB;
-        uint32_t mo = v_src;
-        int eo = (int)ve_src;
-        if (left < 16) {
-            const int r = min(vrow_of_slot, left - 1);
-            mo = (uint32_t)(r * 64 + vp_c * 16);
-            // exponent bytes are fetched as linear dwords; past the last token re-read the last row's
+        const uint8_t* __restrict__ mp = v_mant + (int64_t)t * 64;
+        const uint8_t* __restrict__ ep = v_exp + (int64_t)t * NB;
+        uint8_t* const lm = wbase + kVm + u * 1024;
+        uint8_t* const le = wbase + kVe + u * 256;
+        if (left >= 16) {
+            __builtin_amdgcn_global_load_lds(KVBFP_GPTR(mp + v_src), KVBFP_LPTR(lm), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(KVBFP_GPTR(ep + ve_src), KVBFP_LPTR(le), 4, 0, 0);
+        } else {
+            const int mo = min(vrow_of_slot, left - 1) * 64 + vp_c * 16;
             const int tok = min((int)(ve_src / NB), left - 1);
-            eo = tok * NB + (int)(ve_src % NB);
+            const int eo = tok * NB + (int)(ve_src % NB);
+            __builtin_amdgcn_global_load_lds(KVBFP_GPTR(mp + mo), KVBFP_LPTR(lm), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(KVBFP_GPTR(ep + eo), KVBFP_LPTR(le), 4, 0, 0);
         }
-        __builtin_amdgcn_global_load_lds(KVBFP_GPTR(mp + (int32_t)mo), KVBFP_LPTR(wbase + kVm + u * 1024), 16, 0, 0);
-        // only the first 4*NB lanes carry exponent bytes (the stage holds 16*NB of them); the
-        // instruction is still issued once per wavefront, which is what the vmcnt bookkeeping counts
-        if (lane < 4 * NB)
-            __builtin_amdgcn_global_load_lds(KVBFP_GPTR(ep + eo), KVBFP_LPTR(wbase + kVe + u * 16 * NB), 4, 0, 0);
     };
 
     // ---- first tile of this wavefront goes out before anything else ------------------------------
@@ -514,9 +576,59 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
         for (int u = 0; u < 4; ++u) fill_vals(u, T_first + 16 * u);
     }
 
-    // ---- query limbs to LDS (whole workgroup), in MFMA slot order ---------------------------------
-    // row 4*head + limb; position 32*kg + 8*d + x holds channel 32*kg + 8*d + slot_channel(x)
-    {
+    // ---- query operand of the score product to LDS (whole workgroup) -------------------------------
+    bf16x8 aq[HG][4];      // bf16 path: row 4*head + limb (3 limbs), 4 MFMAs of 32 channels
+    v8i aq8[HG];           // fp4-key path: row 4*head + limb (4 FP8 limbs), one MFMA of 128 channels
+    int sa8[HG];           //               E8M0 scale of this lane's 32 query values
+    if (kFp4Keys) {
+        // FP8 operand layout (measured): byte i of lane-group g is channel 64*(i/16) + 16*g + i%16, while
+        // the E8M0 scale of channel block kb (32 consecutive channels) is taken from lane-group kb.
+        // Each block of 32 query values shares a power-of-two scale 2^sh chosen so that the largest
+        // lands in [128, 256); limb l holds the FP8 rounding of the residual at scale 2^(sh - 4l), so four
+        // limbs carry 16 bits relative to the block's maximum.
+        float* qf = (float*)(smem + kQf);
+        uint8_t* q8 = smem + kQ8;
+        uint8_t* qsc = q8 + NH * 4 * kD;
+        for (int i = tid; i < NH * kD; i += 256) {
+            const int g = i / kD, c = i % kD;
+            float f = 0.f;
+            if (g < a.G) {
+                const int src = a.perm_k ? a.perm_k[kvh * kD + c] : c;
+                f = load_as_float(a.q, dt, ((int64_t)b * a.H_q + h0 + g) * kD + src) * a.scale_log2e;
+            }
+            qf[i] = f;
+        }
+        __syncthreads();
+        for (int i = tid; i < NH * kD; i += 256) {
+            const int g = i / kD, pos = i % kD, ga = pos >> 5, ii = pos & 31;
+            const int c = ii < 16 ? 16 * ga + ii : 64 + 16 * ga + (ii - 16);
+            const int kb = c >> 5;
+            float mx = 0.f;
+            for (int t = 0; t < 32; ++t) mx = fmaxf(mx, fabsf(qf[g * kD + 32 * kb + t]));
+            int e = 0;
+            if (mx > 0.f) (void)frexpf(mx, &e);            // mx = f * 2^e, f in [0.5, 1)
+            int sh = mx > 0.f ? e - 8 : 0;                  // mx * 2^-sh in [128, 256)
+            sh = max(-110, min(110, sh));
+            float v = qf[g * kD + c];
+#pragma unroll
+            for (int limb = 0; limb < 4; ++limb) {
+                const int sl = sh - 4 * limb;
+                const uint32_t packed = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(ldexpf(v, -sl), 0.f, 0, false);
+                v -= ldexpf(__builtin_amdgcn_cvt_f32_fp8((int)packed, 0), sl);
+                q8[(4 * g + limb) * kD + pos] = (uint8_t)(packed & 0xFFu);
+                if ((c & 31) == 0) qsc[(4 * g + limb) * 4 + kb] = (uint8_t)(sl + 127);
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int hg = 0; hg < HG; ++hg) {
+            const u32x4 lo = *(const u32x4*)(q8 + (hg * 16 + j) * kD + kg * 32);
+            const u32x4 hi = *(const u32x4*)(q8 + (hg * 16 + j) * kD + kg * 32 + 16);
+            aq8[hg] = v8i{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+            sa8[hg] = qsc[(hg * 16 + j) * 4 + kg];
+        }
+    } else {
+        // row 4*head + limb; position 32*kg + 8*d + x holds channel 32*kg + 8*d + slot_channel(x)
         uint16_t* ql = (uint16_t*)(smem + kQl);
         for (int i = tid; i < NH * kD; i += 256) {
             const int g = i / kD, pos = i % kD;
@@ -535,14 +647,13 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
             ql[(4 * g + 2) * kD + pos] = __builtin_bit_cast(unsigned short, l2);
             ql[(4 * g + 3) * kD + pos] = 0;
         }
+        __syncthreads();
+#pragma unroll
+        for (int hg = 0; hg < HG; ++hg)
+#pragma unroll
+            for (int d = 0; d < 4; ++d)
+                aq[hg][d] = *(const bf16x8*)(smem + kQl + ((hg * 16 + j) * kD + 32 * kg + 8 * d) * 2);
     }
-    __syncthreads();
-    bf16x8 aq[HG][4];
-#pragma unroll
-    for (int hg = 0; hg < HG; ++hg)
-#pragma unroll
-        for (int d = 0; d < 4; ++d)
-            aq[hg][d] = *(const bf16x8*)(smem + kQl + ((hg * 16 + j) * kD + 32 * kg + 8 * d) * 2);
 
     const int a_head = j >> 2, a_par = (j >> 1) & 1, a_limb = j & 1;
     const uint32_t sel_even = a_par ? 0x01000c0cu : 0x0c0c0100u;
@@ -559,11 +670,12 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
     }
 
     // ---- LDS read offsets of this lane inside a stage --------------------------------------------
-    const uint8_t* const kq = wbase + kKm + (4 * j + (kg ^ ((j >> 2) & 3))) * 16;           // row j, chunk kg
-    const uint8_t* const keq = wbase + kKe + lane * 4 + (N == 32 ? kg : 2 * (kg & 1));     // own exponent byte(s)
-    const uint8_t* const vq = wbase + kVm + kg * 64 + j * 4;                               // + i*256: row 4kg+i sits at position 4i+kg
-    const uint8_t* const veq = wbase + kVe + (4 * kg) * NB + (8 * j) / N;                  // + i*NB
-    uint16_t* const ps = (uint16_t*)(wbase + kPs);
+    const uint32_t kq = lds_addr(wbase + kKm + (4 * j + (kg ^ ((j >> 2) & 3))) * 16);       // row j, chunk kg
+    const uint32_t keq = lds_addr(wbase + kKe + lane * 4 + (N == 32 ? kg : 2 * (kg & 1))); // own exponent byte(s)
+    const uint32_t vq = lds_addr(wbase + kVm + kg * 64 + j * 4);                           // + i*256: row 4kg+i sits at position 4i+kg
+    const uint32_t veq = lds_addr(wbase + kVe + (4 * kg) * NB + (8 * j) / N);              // + u*256 + i*NB
+    uint16_t* const ps = &p_lds[wave][0];
+    const uint32_t ps_rd = lds_addr(&p_lds[wave][(a_limb * 4 + a_head) * kTileTok + 4 * kg]);   // + head group and column tile
 
     if (has_work) {
         constexpr int kStep = kWaves * kTileTok;
@@ -574,37 +686,58 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
 
             // ---------------- scores
             f32x4 s_acc[HG][4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            static_for<4>([&](auto U) {
+                constexpr int u = decltype(U)::value;
                 __builtin_amdgcn_sched_barrier(0);
                 if (more) __builtin_amdgcn_s_waitcnt(vmcnt_imm(14)); else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
                 __builtin_amdgcn_sched_barrier(0);
-                const u32x4 raw = *(const u32x4*)(kq + u * 1024);
-                float sc0, sc1;
-                if (N == 16) {
-                    const uint32_t e2 = *(const uint16_t*)(keq + u * 256);
-                    sc0 = scale_operand(e2 & 0xFFu);
-                    sc1 = scale_operand(e2 >> 8);
-                } else {
-                    sc0 = sc1 = scale_operand(*(keq + u * 256));
-                }
+                u32x4 raw;
+                uint32_t kexp;
+                lds_read_key_stage<u * 1024, u * 256, N == 16>(kq, keq, raw, kexp);
 #pragma unroll
                 for (int hg = 0; hg < HG; ++hg) s_acc[hg][u] = f32x4{0.f, 0.f, 0.f, 0.f};
-                Unpacked kk[4];
+                if (kFp4Keys) {
+                    // magnitude/2 = FP4(s,0,m1,m0) + FP4(s,m2,0,0): two masked copies of the raw nibbles
+                    // are the B operands; the block's exponent byte (minus one for the halving) is
+                    // their E8M0 scale.
+                    const uint32_t E = kexp;
+                    const int sb = (int)__builtin_elementwise_sub_sat((unsigned short)E, (unsigned short)1);
+                    const v8i b1 = {(int)(raw[0] & 0xBBBBBBBBu), (int)(raw[1] & 0xBBBBBBBBu), (int)(raw[2] & 0xBBBBBBBBu),
+                                    (int)(raw[3] & 0xBBBBBBBBu), 0, 0, 0, 0};
+                    const v8i b2 = {(int)(raw[0] & 0xCCCCCCCCu), (int)(raw[1] & 0xCCCCCCCCu), (int)(raw[2] & 0xCCCCCCCCu),
+                                    (int)(raw[3] & 0xCCCCCCCCu), 0, 0, 0, 0};
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (more) fill_keys(u, T1 + 16 * u);
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int d = 0; d < 4; ++d) kk[d] = unpack8(raw[d], d < 2 ? sc0 : sc1);
-                // the stage has been read into registers: re-fill it for the next tile
-                __builtin_amdgcn_sched_barrier(0);
-                if (more) fill_keys(u, T1 + 16 * u);
-                __builtin_amdgcn_sched_barrier(0);
+                    for (int hg = 0; hg < HG; ++hg) {
+                        s_acc[hg][u] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aq8[hg], b1, s_acc[hg][u], 0, 4, 0, sa8[hg], 0, sb);
+                        s_acc[hg][u] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aq8[hg], b2, s_acc[hg][u], 0, 4, 0, sa8[hg], 0, sb);
+                    }
+                } else {
+                    float sc0, sc1;
+                    if (N == 16) {
+                        sc0 = scale_operand(kexp & 0xFFu);
+                        sc1 = scale_operand(kexp >> 8);
+                    } else {
+                        sc0 = sc1 = scale_operand(kexp);
+                    }
+                    Unpacked kk[4];
 #pragma unroll
-                for (int d = 0; d < 4; ++d) {
-                    const bf16x8 bk = join(kk[d].p[0], kk[d].p[1], kk[d].p[2], kk[d].p[3]);
+                    for (int d = 0; d < 4; ++d) kk[d] = unpack8(raw[d], d < 2 ? sc0 : sc1);
+                    // the stage has been read into registers: re-fill it for the next tile
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (more) fill_keys(u, T1 + 16 * u);
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int hg = 0; hg < HG; ++hg)
-                        s_acc[hg][u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aq[hg][d], bk, s_acc[hg][u], 0, 0, 0);
+                    for (int d = 0; d < 4; ++d) {
+                        const bf16x8 bk = join(kk[d].p[0], kk[d].p[1], kk[d].p[2], kk[d].p[3]);
+#pragma unroll
+                        for (int hg = 0; hg < HG; ++hg)
+                            s_acc[hg][u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aq[hg][d], bk, s_acc[hg][u], 0, 0, 0);
+                    }
                 }
-            }
+            });
 
             // ---------------- online softmax; lane (j, kg) owns head kg of each group, tokens 16u + j
 #pragma unroll
@@ -613,7 +746,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
                 float tmax = -INFINITY;
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    const float v = s_acc[hg][u][0] + s_acc[hg][u][1] + s_acc[hg][u][2];
+                    const float v = (s_acc[hg][u][0] + s_acc[hg][u][1]) + (s_acc[hg][u][2] + s_acc[hg][u][3]);   // the limb rows
                     s[u] = (16 * u + j < left) ? v : -INFINITY;
                     tmax = fmaxf(tmax, s[u]);
                 }
@@ -642,29 +775,29 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
             // ---------------- values
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            static_for<4>([&](auto U) {
+                constexpr int u = decltype(U)::value;
                 __builtin_amdgcn_sched_barrier(0);
                 if (more) __builtin_amdgcn_s_waitcnt(vmcnt_imm(14)); else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
                 __builtin_amdgcn_sched_barrier(0);
-                Unpacked vv[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const uint32_t w = *(const uint32_t*)(vq + u * 1024 + i * 256);
-                    const uint32_t E = *(veq + u * 16 * NB + i * NB);
-                    vv[i] = unpack8(w, scale_operand(E));
-                }
+                uint32_t vw[4], ve[4];
+                lds_read_val_stage<u, NB>(vq, veq, vw, ve);
+                uint2 pp[HG];
+                pp[0] = lds_read_b64<(16 * u) * 2>(ps_rd);
+                if (HG > 1) pp[HG - 1] = lds_read_b64<(2 * 4 * kTileTok + 16 * u) * 2>(ps_rd);
                 __builtin_amdgcn_sched_barrier(0);
                 if (more) fill_vals(u, T1 + 16 * u);
                 __builtin_amdgcn_sched_barrier(0);
+                Unpacked vv[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) vv[i] = unpack8(vw[i], scale_operand(ve[i]));
 #pragma unroll
                 for (int hg = 0; hg < HG; ++hg) {
-                    const uint2 pp = *(const uint2*)&ps[((hg * 2 + a_limb) * 4 + a_head) * kTileTok + 16 * u + 4 * kg];
                     uint32_t ar[4];
-                    ar[0] = __builtin_amdgcn_perm(pp.x, pp.x, sel_even);
-                    ar[1] = __builtin_amdgcn_perm(pp.x, pp.x, sel_odd);
-                    ar[2] = __builtin_amdgcn_perm(pp.y, pp.y, sel_even);
-                    ar[3] = __builtin_amdgcn_perm(pp.y, pp.y, sel_odd);
+                    ar[0] = __builtin_amdgcn_perm(pp[hg].x, pp[hg].x, sel_even);
+                    ar[1] = __builtin_amdgcn_perm(pp[hg].x, pp[hg].x, sel_odd);
+                    ar[2] = __builtin_amdgcn_perm(pp[hg].y, pp[hg].y, sel_even);
+                    ar[3] = __builtin_amdgcn_perm(pp[hg].y, pp[hg].y, sel_odd);
                     const bf16x8 ap = __builtin_bit_cast(bf16x8, u32x4{ar[0], ar[1], ar[2], ar[3]});
 #pragma unroll
                     for (int m = 0; m < 4; ++m) {
@@ -672,7 +805,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
                         o_acc[hg][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ap, bv, o_acc[hg][m], 0, 0, 0);
                     }
                 }
-            }
+            });
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -732,7 +865,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
 }
 
 // Which split pass serves blocks of 16 and 32: the LDS-staged pipeline or the register-staged one.
-constexpr bool kUseLdsPipeline = false;
+constexpr bool kUseLdsPipeline = true;
 
 template <int HG>
 hipError_t launch_n(const DecodeArgs& a, int dt, int block, dim3 grid, hipStream_t s) {

@@ -57,7 +57,7 @@ SplitPlan plan_splits(const kvbfp_layout* L, int32_t n_q_heads, int64_t max_len)
     (void)n_q_heads;
     const int64_t units = (int64_t)L->batch * L->n_kv_heads;
     const int64_t tiles = (max_len + kTokenTile - 1) / kTokenTile;
-    const int64_t target_wgs = 256 * 4;   // four resident workgroups per compute unit
+    const int64_t target_wgs = 256 * 3;   // three resident workgroups per compute unit
     int64_t want = (target_wgs + units - 1) / units;
     if (want < 1) want = 1;
     if (want > tiles) want = tiles;
