@@ -374,11 +374,12 @@ int kvbfp_decode_attention(const kvbfp_layout* L, const kvbfp_cache* cache, int3
         return fail(KVBFP_ERR_UNSUPPORTED, "decode_attention: too many heads for the grid");
     const dim3 grid1((unsigned)sp.n_splits, (unsigned)(a.H_kv * gg), (unsigned)L->batch);
     auto aligned16 = [](const void* p) { return ((uintptr_t)p & 15u) == 0; };
-    const bool fast = L->mant_bits == 4 && a.G <= 8 && dtype != KVBFP_F32 && aligned16(a.k_mant) &&
+    const bool fast = a.G <= 8 && dtype != KVBFP_F32 && aligned16(a.k_mant) &&
                       aligned16(a.v_mant) && aligned16(a.k_exp) && aligned16(a.v_exp);
     hipError_t err;
     if (fast) {
-        err = launch_decode_split_mfma(a, (int)dtype, L->block, L->batch, s);
+        err = L->mant_bits == 4 ? launch_decode_split_mfma(a, (int)dtype, L->block, L->batch, s)
+                                : launch_decode_split_mfma_p8(a, (int)dtype, L->block, L->batch, s);
     } else {
         if (L->mant_bits == 4) decode_split_generic<4><<<grid1, kTile, 0, s>>>(a, (int)dtype);
         else decode_split_generic<8><<<grid1, kTile, 0, s>>>(a, (int)dtype);

@@ -27,5 +27,7 @@ struct DecodeArgs {
 // Fast split pass for 4-bit mantissas and 16-bit I/O (decode_mfma.hip).  Returns hipSuccess after
 // enqueuing; the caller has already validated the arguments.  group size G <= 8.
 hipError_t launch_decode_split_mfma(const DecodeArgs& a, int dtype, int block, int batch, hipStream_t s);
+// The same for 8-bit mantissas (decode_mfma_p8.hip).
+hipError_t launch_decode_split_mfma_p8(const DecodeArgs& a, int dtype, int block, int batch, hipStream_t s);
 
 }  // namespace kvbfp

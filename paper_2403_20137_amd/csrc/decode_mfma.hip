@@ -32,51 +32,14 @@
 #include <utility>
 
 #include "decode_args.h"
+#include "decode_dev.h"
 #include "kvbfp_internal.h"
 
 namespace {
 
 using kvbfp::DecodeArgs;
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef int v8i __attribute__((ext_vector_type(8)));
-
-constexpr int kD = 128;
-constexpr int kWaves = 4;
-constexpr int kSuper = 64;   // tokens per wavefront iteration (4 MFMA column tiles of 16)
-// Cached values are produced as value * 2^-16 so that the conversion's scale exponent stays a
-// normal fp32 exponent for every stored exponent byte >= 10; the query carries the inverse factor.
-constexpr int kShift = 16;
-
-template <int CTRL>
-__device__ __forceinline__ float dpp_f(float v) {
-    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, 0xF, 0xF, false));
-}
-// all-reduce over the 16 lanes of a DPP row
-__device__ __forceinline__ float row_max(float v) {
-    v = fmaxf(v, dpp_f<0xB1>(v));
-    v = fmaxf(v, dpp_f<0x4E>(v));
-    v = fmaxf(v, dpp_f<0x141>(v));
-    v = fmaxf(v, dpp_f<0x140>(v));
-    return v;
-}
-__device__ __forceinline__ float row_sum(float v) {
-    v += dpp_f<0xB1>(v);
-    v += dpp_f<0x4E>(v);
-    v += dpp_f<0x141>(v);
-    v += dpp_f<0x140>(v);
-    return v;
-}
-
-__device__ __forceinline__ float load_as_float(const void* p, int dt, int64_t i) {
-    if (dt == KVBFP_F32) return ((const float*)p)[i];
-    const uint32_t h = ((const uint16_t*)p)[i];
-    if (dt == KVBFP_F16) return (float)__builtin_bit_cast(_Float16, (unsigned short)h);
-    return __uint_as_float(h << 16);
-}
+using namespace kvbfp::dev;
 
 // fp32 scale operand 2^(E - 129 + 9 - kShift): a code m, read as the FP8 subnormal m * 2^-9, times
 // it equals m * 2^(E - 127 - 2) * 2^-kShift.  Only the exponent field of the operand is used by the
@@ -98,12 +61,6 @@ __device__ __forceinline__ Unpacked unpack8(uint32_t w, float scale) {
     u.p[2] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, scale, false);      // (c1, c3)
     u.p[3] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, scale, true);       // (c5, c7)
     return u;
-}
-__device__ __forceinline__ bf16x8 join(bf16x2 a, bf16x2 b, bf16x2 c, bf16x2 d) {
-    bf16x8 r;
-    r[0] = a[0]; r[1] = a[1]; r[2] = b[0]; r[3] = b[1];
-    r[4] = c[0]; r[5] = c[1]; r[6] = d[0]; r[7] = d[1];
-    return r;
 }
 // channel offset inside a dword of MFMA slot x
 __device__ __forceinline__ int slot_channel(int x) { return (x < 4) ? 2 * x : 2 * (x - 4) + 1; }

@@ -42,7 +42,7 @@ def make_small(dtype, B, S, Hkv, G, seed):
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.float16, torch.bfloat16])
-@pytest.mark.parametrize("p,n", [(4, 16), (4, 32), (4, 64), (4, 128), (8, 16), (8, 32)])
+@pytest.mark.parametrize("p,n", [(4, 16), (4, 32), (4, 64), (4, 128), (8, 16), (8, 32), (8, 64), (8, 128)])
 @pytest.mark.parametrize("G", [1, 4])
 def test_decode_attention_matches_oracle(dtype, p, n, G):
     # 700 tokens: two full 256-token tiles and a ragged third; the second sequence stops mid-tile
@@ -51,10 +51,11 @@ def test_decode_attention_matches_oracle(dtype, p, n, G):
     assert_attention_close(got, want, dtype, "p=%d n=%d G=%d" % (p, n, G))
 
 
+@pytest.mark.parametrize("p", [4, 8])
 @pytest.mark.parametrize("G", [2, 3, 5, 8])
-def test_group_sizes_and_no_permutation(G):
+def test_group_sizes_and_no_permutation(G, p):
     k, v, q, _, _ = make_small(torch.bfloat16, B=1, S=300, Hkv=3, G=G, seed=40 + G)
-    got, want = run_both(k, v, q, 32, 4, [300], 0.11, None, None, use_seq_len=False)
+    got, want = run_both(k, v, q, 32, p, [300], 0.11, None, None, use_seq_len=False)
     assert_attention_close(got, want, torch.bfloat16)
 
 
