@@ -1,12 +1,18 @@
 // Cache write and read-back kernels for gfx950: casting key/value rows to Block Floating Point
 // (Sec. II-B, Eq. (1)) into the packed cache, and decoding them again.
 //
-// Work decomposition (wave64): a 128-channel row is handled by 16 adjacent lanes, 8 consecutive
-// cache positions per lane, so one wavefront carries 4 rows.  A lane loads its 8 inputs with one
-// or two 16-byte loads, a block of n = 16/32/64/128 positions spans 2/4/8/16 adjacent lanes of one
-// DPP row, so the per-block maximum is an all-reduce with 1..4 DPP steps and never leaves the row.
-// Each lane then rounds its 8 mantissas in registers and stores one packed dword (4-bit) or two
-// (8-bit); the 16 lanes of a row write one contiguous 64/128-byte segment.
+// Write path (wave64): a 128-channel row is handled by 8 adjacent lanes, 16 consecutive cache
+// positions per lane, so a lane never shares a block of 16 and a block of n = 32/64/128 spans
+// 2/4/8 adjacent lanes of one DPP row: the per-block maximum is an all-reduce with 0..3 DPP steps.
+// A workgroup of 256 threads takes 64 rows in two steps of 32 and issues the loads of both steps
+// before it computes, which keeps 32-64 bytes per lane in flight.  Each lane rounds its 16
+// mantissas in registers and stores them as one 8-byte (4-bit) or 16-byte (8-bit) word; the 8
+// lanes of a row write one contiguous 64/128-byte segment.
+//
+// Rounding without a division: with e the block's scale exponent, |x| + 2^(23+e) is rounded by the
+// adder to a multiple of 2^e (round to nearest, ties to even), and its low mantissa bits are the
+// integer |x| / 2^e rounded.  The constant's bit pattern is then removed from all packed codes at
+// once.  Blocks so large that 2^(23+e) overflows fp32 take a slower scaling path.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -15,9 +21,27 @@
 
 namespace {
 
-constexpr int kD = 128;          // channels per row (head_dim)
-constexpr int kLanesPerRow = 16; // 8 channels per lane
-constexpr int kRowsPerBlock = 16; // 256 threads
+constexpr int kD = 128;           // channels per row (head_dim)
+constexpr int kLanesPerRow = 8;   // 16 channels per lane
+constexpr int kRowsPerStep = 32;  // 256 threads
+constexpr int kSteps = 2;
+constexpr int kRowsPerWg = kRowsPerStep * kSteps;
+
+// How a lane obtains its 16 inputs.
+constexpr int kDirect = 0;        // aligned rows, cache order = memory order: 16-byte loads
+constexpr int kLdsGather = 1;     // aligned rows + permutation: 16-byte loads, permuted through LDS
+constexpr int kElementwise = 2;   // unaligned rows (with or without permutation): one load per element
+
+// Unsigned division of numerators below 2^31 by a fixed divisor: floor(n / d) = (n * mul) >> shift.
+struct FastDiv { uint32_t mul, shift; };
+FastDiv make_fastdiv(uint32_t d) {   // d >= 1
+    uint32_t l = 0;
+    while ((1ull << l) < d) ++l;
+    return FastDiv{(uint32_t)(((1ull << (31 + l)) / d) + 1), 31 + l};
+}
+__device__ __forceinline__ uint32_t fastdiv(uint32_t n, FastDiv d) {
+    return (uint32_t)(((uint64_t)n * d.mul) >> d.shift);
+}
 
 struct QuantTensor {
     const void* src;       // [B][n_new][H][D] strided
@@ -33,7 +57,8 @@ struct QuantArgs {
     const int32_t* pos_dev;
     int64_t max_seq;
     int32_t H, n_new;
-    int64_t n_rows;                          // B * H * n_new
+    uint32_t n_rows;                         // B * H * n_new, below 2^31
+    FastDiv div_n_new, div_H;
 };
 
 template <int CTRL>
@@ -41,16 +66,14 @@ __device__ __forceinline__ uint32_t dpp_mov(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xF, 0xF, false);
 }
 
-// All-reduce maximum over the LPB adjacent lanes that share a block (LPB = block / 8).
-// quad_perm[1,0,3,2], quad_perm[2,3,0,1], row_half_mirror, row_mirror: after the first two steps
-// every quad is uniform, so the mirrors (which map quad k to quad 1-k resp. 3-k) complete the
-// butterfly.
+// All-reduce maximum over the LPB adjacent lanes that share a block (LPB = block / 16).
+// quad_perm[1,0,3,2], quad_perm[2,3,0,1], row_half_mirror: after the first two steps every quad is
+// uniform, so the mirror (which swaps the two quads of a half row) completes the butterfly.
 template <int LPB>
 __device__ __forceinline__ uint32_t block_allmax(uint32_t a) {
-    a = max(a, dpp_mov<0xB1>(a));
+    if (LPB >= 2) a = max(a, dpp_mov<0xB1>(a));
     if (LPB >= 4) a = max(a, dpp_mov<0x4E>(a));
     if (LPB >= 8) a = max(a, dpp_mov<0x141>(a));
-    if (LPB >= 16) a = max(a, dpp_mov<0x140>(a));
     return a;
 }
 
@@ -59,106 +82,183 @@ __device__ __forceinline__ float widen_f16(uint32_t h) {
     return (float)__builtin_bit_cast(_Float16, (unsigned short)h);
 }
 
-// Loads the 8 inputs of this lane: cache positions c0..c0+7 of the row at `row`.
-template <int DT, bool GATHER>
-__device__ __forceinline__ void load8(const void* row, const int32_t* perm_row, int c0, float (&x)[8]) {
-    if (GATHER) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int c = perm_row ? perm_row[c0 + i] : (c0 + i);
-            if (DT == KVBFP_F32) x[i] = ((const float*)row)[c];
-            else if (DT == KVBFP_F16) x[i] = widen_f16(((const uint16_t*)row)[c]);
-            else x[i] = widen_bf16(((const uint16_t*)row)[c]);
-        }
-    } else if (DT == KVBFP_F32) {
-        const float4 a = *(const float4*)((const float*)row + c0);
-        const float4 b = *(const float4*)((const float*)row + c0 + 4);
-        x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
-        x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
-    } else {
-        const uint4 v = *(const uint4*)((const uint16_t*)row + c0);
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+template <int DT>
+struct RawRow { uint4 v[DT == KVBFP_F32 ? 4 : 2]; };   // this lane's 16 inputs as loaded
+
+template <int DT>
+__device__ __forceinline__ void widen16(const RawRow<DT>& raw, float (&x)[16]) {
+    if (DT == KVBFP_F32) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            if (DT == KVBFP_F16) {
-                x[2 * i] = widen_f16(w[i] & 0xFFFFu);
-                x[2 * i + 1] = widen_f16(w[i] >> 16);
-            } else {
-                x[2 * i] = widen_bf16(w[i] & 0xFFFFu);
-                x[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+            x[4 * i] = __uint_as_float(raw.v[i].x);
+            x[4 * i + 1] = __uint_as_float(raw.v[i].y);
+            x[4 * i + 2] = __uint_as_float(raw.v[i].z);
+            x[4 * i + 3] = __uint_as_float(raw.v[i].w);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const uint32_t w[4] = {raw.v[i].x, raw.v[i].y, raw.v[i].z, raw.v[i].w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                if (DT == KVBFP_F16) {
+                    x[8 * i + 2 * k] = widen_f16(w[k] & 0xFFFFu);
+                    x[8 * i + 2 * k + 1] = widen_f16(w[k] >> 16);
+                } else {
+                    x[8 * i + 2 * k] = widen_bf16(w[k] & 0xFFFFu);
+                    x[8 * i + 2 * k + 1] = __uint_as_float(w[k] & 0xFFFF0000u);
+                }
             }
         }
     }
 }
 
-// One row per 16 lanes.  P = mantissa bits, LPB = lanes per block.
-template <int DT, int P, int LPB, bool GATHER>
-__global__ __launch_bounds__(256) void quantize_rows_kernel(QuantArgs a) {
-    const QuantTensor T = a.t[blockIdx.y];
-    const int lane16 = threadIdx.x & (kLanesPerRow - 1);
-    const int64_t r = (int64_t)blockIdx.x * kRowsPerBlock + (threadIdx.x >> 4);
-    // Rows beyond the end keep their lanes active (DPP reads neighbours) but touch no memory.
-    const bool in_range = r < a.n_rows;
-    const int64_t rr = in_range ? r : 0;
-    const int32_t t = (int32_t)(rr % a.n_new);
-    const int32_t h = (int32_t)((rr / a.n_new) % a.H);
-    const int32_t b = (int32_t)(rr / ((int64_t)a.n_new * a.H));
-    const int64_t pos = (a.pos_dev ? (int64_t)a.pos_dev[b] : a.pos0) + t;
-    const bool live = in_range && pos >= 0 && pos < a.max_seq;
-
-    const int c0 = lane16 * 8;
-    float x[8];
-    if (live) {
-        const int64_t off = b * a.stride_b + t * a.stride_t + h * a.stride_h;
-        const void* row = (DT == KVBFP_F32) ? (const void*)((const float*)T.src + off)
-                                            : (const void*)((const uint16_t*)T.src + off);
-        load8<DT, GATHER>(row, T.perm ? T.perm + (int64_t)h * kD : nullptr, c0, x);
-    } else {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) x[i] = 0.f;
-    }
-
+// Casts the 16 values of this lane (cache positions c0..c0+15 of one row) and stores them.
+// Every lane of a row group calls this (the DPP steps read neighbours); only `live` rows store.
+template <int P, int N>
+__device__ __forceinline__ void encode_store(const float (&x)[16], int sub, bool live, const QuantTensor& T,
+                                             int64_t crow) {
+    constexpr int LPB = N / 16;
+    constexpr int NB = kD / N;
     // Largest magnitude of the block, compared on the bit patterns (monotone for finite values).
-    uint32_t amax = 0;
+    float am = 0.f;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) amax = max(amax, __float_as_uint(x[i]) & 0x7FFFFFFFu);
-    amax = block_allmax<LPB>(amax);
+    for (int i = 0; i < 16; ++i) am = fmaxf(am, fabsf(x[i]));
+    const uint32_t amax = block_allmax<LPB>(__float_as_uint(am));
 
     // Shared exponent byte: the fp32 exponent field of the maximum, one higher when rounding the
     // maximum to P-1 magnitude bits would carry (its top P-1 fraction bits are all ones); at least
     // 1 so that subnormal blocks use the scale of the smallest normal; 0 marks an all-zero block.
     const uint32_t bumped = (amax + (1u << (24 - P))) >> 23;
-    const int E = amax == 0 ? 0 : (int)max(bumped, 1u);
-    const int e = E - 127 - (P - 2);
+    const uint32_t E = amax == 0 ? 0u : max(bumped, 1u);
 
-    // Mantissas: scaling by a power of two is exact, adding 2^23 rounds to nearest-even integer.
-    uint32_t code[8];
+    // q[i]: a word whose low P-1 bits are the rounded magnitude; `bias` is what the other bits add
+    // up to once the words are packed at P-bit spacing.
+    constexpr int kPerWord = 32 / P;
+    constexpr uint32_t kOnes = P == 4 ? 0x11111111u : 0x01010101u;
+    uint32_t q[16];
+    uint32_t bias;
+    const uint32_t cfield = E + 25 - P;              // exponent field of 2^(23+e), e = E - 127 - (P-2)
+    if (cfield <= 254) {
+        const float C = __uint_as_float(cfield << 23);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const float scaled = ldexpf(x[i], -e);
-        const uint32_t mag = __float_as_uint(fabsf(scaled) + 8388608.0f) & 0xFFu;
-        const uint32_t sign = (__float_as_uint(x[i]) >> 31) << (P - 1);
-        code[i] = mag ? (mag | sign) : 0u;
+        for (int i = 0; i < 16; ++i) q[i] = __float_as_uint(fabsf(x[i]) + C);
+        bias = (cfield << 23) * kOnes;
+    } else {                                         // enormous block: scale down first (exact), then round
+        const int e = (int)E - 127 - (P - 2);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) q[i] = __float_as_uint(fabsf(ldexpf(x[i], -e)) + 8388608.0f) & 0xFFu;
+        bias = 0u;
+    }
+
+    uint32_t word[16 / kPerWord];
+#pragma unroll
+    for (int w = 0; w < 16 / kPerWord; ++w) {
+        uint32_t m = 0, sg = 0;
+#pragma unroll
+        for (int k = 0; k < kPerWord; ++k) {
+            const int i = w * kPerWord + k;
+            m += q[i] << (P * k);
+            sg |= (__float_as_uint(x[i]) >> 31) << (P * k + P - 1);
+        }
+        m -= bias;
+        // the sign bit only where the magnitude is non-zero: minus zero is stored as plus zero
+        const uint32_t nz = (m + (P == 4 ? 0x77777777u : 0x7F7F7F7Fu)) & (P == 4 ? 0x88888888u : 0x80808080u);
+        word[w] = m | (sg & nz);
     }
 
     if (!live) return;
-    const int64_t crow = ((int64_t)b * a.H + h) * a.max_seq + pos;
-    if (P == 4) {
-        uint32_t w = 0;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) w |= code[i] << (4 * i);
-        ((uint32_t*)(T.mant + crow * 64))[lane16] = w;
-    } else {
-        uint2 w = make_uint2(0u, 0u);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            w.x |= code[i] << (8 * i);
-            w.y |= code[4 + i] << (8 * i);
-        }
-        ((uint2*)(T.mant + crow * 128))[lane16] = w;
-    }
-    if ((lane16 & (LPB - 1)) == 0) T.exp[crow * (kLanesPerRow / LPB) + lane16 / LPB] = (uint8_t)E;
+    if (P == 4) *(uint2*)(T.mant + crow * 64 + sub * 8) = make_uint2(word[0], word[1]);
+    else *(uint4*)(T.mant + crow * 128 + sub * 16) = make_uint4(word[0], word[1], word[2], word[3]);
+    if ((sub & (LPB - 1)) == 0) T.exp[crow * NB + sub / LPB] = (uint8_t)E;
 }
+
+// One row per 8 lanes, 64 rows per workgroup.  P = mantissa bits, N = block size.
+template <int DT, int P, int N, int MODE>
+__global__ __launch_bounds__(256) void quantize_rows_kernel(QuantArgs a) {
+    constexpr int ESZ = DT == KVBFP_F32 ? 4 : 2;
+    constexpr int kRowBytes = kD * ESZ;
+    __shared__ __align__(16) uint8_t stage[MODE == kLdsGather ? kRowsPerWg * kRowBytes : 16];
+
+    const QuantTensor T = a.t[blockIdx.y];
+    const int sub = threadIdx.x & (kLanesPerRow - 1);
+    const int slot = threadIdx.x >> 3;
+    const int c0 = sub * 16;
+
+    bool live[kSteps];
+    int64_t crow[kSteps];
+    int32_t head[kSteps];
+    RawRow<DT> raw[kSteps];
+    const uint8_t* srow[kSteps];
+#pragma unroll
+    for (int k = 0; k < kSteps; ++k) {
+        // Rows beyond the end keep their lanes active (DPP reads neighbours) but touch no memory.
+        const uint32_t r = blockIdx.x * (uint32_t)kRowsPerWg + (uint32_t)(k * kRowsPerStep + slot);
+        const bool in_range = r < a.n_rows;
+        const uint32_t rr = in_range ? r : 0u;
+        const uint32_t bh = fastdiv(rr, a.div_n_new);
+        const uint32_t t = rr - bh * (uint32_t)a.n_new;
+        const uint32_t b = fastdiv(bh, a.div_H);
+        const uint32_t h = bh - b * (uint32_t)a.H;
+        const int64_t pos = (a.pos_dev ? (int64_t)a.pos_dev[b] : a.pos0) + t;
+        live[k] = in_range && pos >= 0 && pos < a.max_seq;
+        crow[k] = ((int64_t)b * a.H + h) * a.max_seq + pos;
+        head[k] = (int32_t)h;
+        srow[k] = (const uint8_t*)T.src + ((int64_t)b * a.stride_b + (int64_t)t * a.stride_t + (int64_t)h * a.stride_h) * ESZ;
+        if (MODE != kElementwise) {
+#pragma unroll
+            for (int i = 0; i < ESZ * 16 / 16; ++i)
+                raw[k].v[i] = live[k] ? ((const uint4*)(srow[k] + c0 * ESZ))[i] : make_uint4(0u, 0u, 0u, 0u);
+        }
+    }
+
+#pragma unroll
+    for (int k = 0; k < kSteps; ++k) {
+        float x[16];
+        if (MODE == kDirect || (MODE == kLdsGather && T.perm == nullptr)) {
+            widen16<DT>(raw[k], x);
+        } else if (MODE == kLdsGather) {
+            // The row goes to LDS in memory order and comes back in cache order: position j of the
+            // cache holds channel perm[j].  A row stays inside 8 lanes of one wavefront.
+            uint8_t* lrow = stage + (k * kRowsPerStep + slot) * kRowBytes;
+#pragma unroll
+            for (int i = 0; i < ESZ * 16 / 16; ++i) ((uint4*)(lrow + c0 * ESZ))[i] = raw[k].v[i];
+            int4 pi[4];
+            const int4* pp = (const int4*)(T.perm + (int64_t)head[k] * kD + c0);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) pi[i] = pp[i];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int c = (i & 3) == 0 ? pi[i >> 2].x : ((i & 3) == 1 ? pi[i >> 2].y : ((i & 3) == 2 ? pi[i >> 2].z : pi[i >> 2].w));
+                const int cc = c & (kD - 1);          // a valid permutation is unchanged; keeps LDS reads in range
+                if (DT == KVBFP_F32) x[i] = ((const float*)lrow)[cc];
+                else if (DT == KVBFP_F16) x[i] = widen_f16(((const uint16_t*)lrow)[cc]);
+                else x[i] = widen_bf16(((const uint16_t*)lrow)[cc]);
+            }
+        } else {
+            const int32_t* pr = T.perm ? T.perm + (int64_t)head[k] * kD : nullptr;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                float v = 0.f;
+                if (live[k]) {
+                    const int c = pr ? (pr[c0 + i] & (kD - 1)) : (c0 + i);
+                    if (DT == KVBFP_F32) v = ((const float*)srow[k])[c];
+                    else if (DT == KVBFP_F16) v = widen_f16(((const uint16_t*)srow[k])[c]);
+                    else v = widen_bf16(((const uint16_t*)srow[k])[c]);
+                }
+                x[i] = v;
+            }
+        }
+        encode_store<P, N>(x, sub, live[k], T, crow[k]);
+    }
+}
+
+// Read-back kernel: one row per 16 lanes, 8 cache positions per lane, 16 rows per workgroup.
+constexpr int kDqLanesPerRow = 16;
+constexpr int kDqRowsPerBlock = 16;
 
 struct DequantArgs {
     const uint8_t* mant;
@@ -178,14 +278,14 @@ __device__ __forceinline__ uint16_t narrow_bf16(float v) {
 
 template <int DT, int P, int LPB>
 __global__ __launch_bounds__(256) void dequantize_rows_kernel(DequantArgs a) {
-    const int lane16 = threadIdx.x & (kLanesPerRow - 1);
-    const int64_t r = (int64_t)blockIdx.x * kRowsPerBlock + (threadIdx.x >> 4);
+    const int lane16 = threadIdx.x & (kDqLanesPerRow - 1);
+    const int64_t r = (int64_t)blockIdx.x * kDqRowsPerBlock + (threadIdx.x >> 4);
     if (r >= a.n_rows) return;
     const int64_t t = r % a.n_tok;
     const int32_t h = (int32_t)((r / a.n_tok) % a.H);
     const int64_t b = r / (a.n_tok * a.H);
     const int64_t crow = (b * a.H + h) * a.max_seq + a.t0 + t;
-    const int E = a.exp[crow * (kLanesPerRow / LPB) + lane16 / LPB];
+    const int E = a.exp[crow * (kDqLanesPerRow / LPB) + lane16 / LPB];
     const int e = E - 127 - (P - 2);
     uint32_t code[8];
     if (P == 4) {
@@ -241,27 +341,26 @@ __global__ __launch_bounds__(256) void dequantize_rows_kernel(DequantArgs a) {
     }
 }
 
-template <int DT, int P, bool GATHER>
-hipError_t launch_quant_lpb(int block, const QuantArgs& a, dim3 grid, hipStream_t s) {
+template <int DT, int P, int MODE>
+hipError_t launch_quant_n(int block, const QuantArgs& a, dim3 grid, hipStream_t s) {
     switch (block) {
-        case 16: quantize_rows_kernel<DT, P, 2, GATHER><<<grid, 256, 0, s>>>(a); break;
-        case 32: quantize_rows_kernel<DT, P, 4, GATHER><<<grid, 256, 0, s>>>(a); break;
-        case 64: quantize_rows_kernel<DT, P, 8, GATHER><<<grid, 256, 0, s>>>(a); break;
-        default: quantize_rows_kernel<DT, P, 16, GATHER><<<grid, 256, 0, s>>>(a); break;
+        case 16: quantize_rows_kernel<DT, P, 16, MODE><<<grid, 256, 0, s>>>(a); break;
+        case 32: quantize_rows_kernel<DT, P, 32, MODE><<<grid, 256, 0, s>>>(a); break;
+        case 64: quantize_rows_kernel<DT, P, 64, MODE><<<grid, 256, 0, s>>>(a); break;
+        default: quantize_rows_kernel<DT, P, 128, MODE><<<grid, 256, 0, s>>>(a); break;
     }
     return hipGetLastError();
 }
-template <int DT, bool GATHER>
+template <int DT, int MODE>
 hipError_t launch_quant_p(int p, int block, const QuantArgs& a, dim3 grid, hipStream_t s) {
-    return p == 4 ? launch_quant_lpb<DT, 4, GATHER>(block, a, grid, s)
-                  : launch_quant_lpb<DT, 8, GATHER>(block, a, grid, s);
+    return p == 4 ? launch_quant_n<DT, 4, MODE>(block, a, grid, s) : launch_quant_n<DT, 8, MODE>(block, a, grid, s);
 }
-template <bool GATHER>
+template <int MODE>
 hipError_t launch_quant(int dt, int p, int block, const QuantArgs& a, dim3 grid, hipStream_t s) {
     switch (dt) {
-        case KVBFP_F32: return launch_quant_p<KVBFP_F32, GATHER>(p, block, a, grid, s);
-        case KVBFP_F16: return launch_quant_p<KVBFP_F16, GATHER>(p, block, a, grid, s);
-        default: return launch_quant_p<KVBFP_BF16, GATHER>(p, block, a, grid, s);
+        case KVBFP_F32: return launch_quant_p<KVBFP_F32, MODE>(p, block, a, grid, s);
+        case KVBFP_F16: return launch_quant_p<KVBFP_F16, MODE>(p, block, a, grid, s);
+        default: return launch_quant_p<KVBFP_BF16, MODE>(p, block, a, grid, s);
     }
 }
 
@@ -310,20 +409,27 @@ int kvbfp_quantize_append(const kvbfp_layout* L, const kvbfp_cache* cache, const
     a.stride_b = stride_b; a.stride_t = stride_t; a.stride_h = stride_h;
     a.pos0 = pos0; a.pos_dev = pos_dev; a.max_seq = L->max_seq;
     a.H = L->n_kv_heads; a.n_new = n_new;
-    a.n_rows = (int64_t)L->batch * L->n_kv_heads * n_new;
-    const int64_t blocks = (a.n_rows + kRowsPerBlock - 1) / kRowsPerBlock;
-    if (blocks > 0x7FFFFFFF) return fail(KVBFP_ERR_UNSUPPORTED, "quantize_append: too many rows");
-    const dim3 grid((unsigned)blocks, (unsigned)nt, 1);
+    const int64_t n_rows = (int64_t)L->batch * L->n_kv_heads * n_new;
+    if (n_rows > 0x7FFFFFFF) return fail(KVBFP_ERR_UNSUPPORTED, "quantize_append: too many rows");
+    a.n_rows = (uint32_t)n_rows;
+    a.div_n_new = make_fastdiv((uint32_t)n_new);
+    a.div_H = make_fastdiv((uint32_t)L->n_kv_heads);
+    const dim3 grid((unsigned)((n_rows + kRowsPerWg - 1) / kRowsPerWg), (unsigned)nt, 1);
 
-    // 16-byte vector loads need aligned rows; otherwise (or with a permutation) gather elementwise.
+    // 16-byte vector loads need aligned rows; a permutation is then applied through LDS.  Anything
+    // unaligned is gathered element by element.
     auto aligned = [&](const void* p) {
         return p == nullptr || (((uintptr_t)p % 16 == 0) && (stride_b * esz) % 16 == 0 &&
                                 (stride_t * esz) % 16 == 0 && (stride_h * esz) % 16 == 0);
     };
-    const bool gather = perm_k || perm_v || !aligned(k_new) || !aligned(v_new);
+    const bool rows_aligned = aligned(k_new) && aligned(v_new);
+    const bool perms_aligned = (uintptr_t)perm_k % 16 == 0 && (uintptr_t)perm_v % 16 == 0;
+    const bool any_perm = (k_new && perm_k) || (v_new && perm_v);
     hipStream_t s = (hipStream_t)hip_stream;
-    const hipError_t err = gather ? launch_quant<true>(dtype, L->mant_bits, L->block, a, grid, s)
-                                  : launch_quant<false>(dtype, L->mant_bits, L->block, a, grid, s);
+    hipError_t err;
+    if (!rows_aligned || (any_perm && !perms_aligned)) err = launch_quant<kElementwise>(dtype, L->mant_bits, L->block, a, grid, s);
+    else if (any_perm) err = launch_quant<kLdsGather>(dtype, L->mant_bits, L->block, a, grid, s);
+    else err = launch_quant<kDirect>(dtype, L->mant_bits, L->block, a, grid, s);
     if (err != hipSuccess) return fail(KVBFP_ERR_HIP, "quantize_append: %s", hipGetErrorString(err));
     return KVBFP_OK;
 }
@@ -349,7 +455,7 @@ int kvbfp_dequantize(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t wh
     a.perm = perm; a.out = out; a.t0 = t0; a.n_tok = n_tok; a.max_seq = L->max_seq;
     a.H = L->n_kv_heads;
     a.n_rows = (int64_t)L->batch * L->n_kv_heads * n_tok;
-    const int64_t blocks = (a.n_rows + kRowsPerBlock - 1) / kRowsPerBlock;
+    const int64_t blocks = (a.n_rows + kDqRowsPerBlock - 1) / kDqRowsPerBlock;
     if (blocks > 0x7FFFFFFF) return fail(KVBFP_ERR_UNSUPPORTED, "dequantize: too many rows");
     const dim3 grid((unsigned)blocks, 1, 1);
     hipStream_t s = (hipStream_t)hip_stream;
