@@ -150,20 +150,28 @@ def bulk_quantize_rate(device="cuda", reps=5):
     v = synth.kv_rows(w.batch, w.seq, w.n_kv_heads, w.head_dim, w.dtype, kg, synth.BASE_SEED, synth.TID_V, device)
     layout = kvbfp.make_layout(w.head_dim, w.block, w.mant_bits, w.n_kv_heads, w.batch, w.seq)
     cache = kvbfp.alloc_cache(layout, device)
-    kvbfp.quantize_append(cache, k, v)
-    torch.cuda.synchronize()
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-    for a, b in ev:
-        a.record()
-        kvbfp.quantize_append(cache, k, v)
-        b.record()
-    torch.cuda.synchronize()
-    us = np.array([a.elapsed_time(b) for a, b in ev]) * 1e3
+    def rate(perm):
+        kvbfp.quantize_append(cache, k, v, perm_k=perm, perm_v=perm)
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, b in ev:
+            a.record()
+            kvbfp.quantize_append(cache, k, v, perm_k=perm, perm_v=perm)
+            b.record()
+        torch.cuda.synchronize()
+        return np.array([a.elapsed_time(b) for a, b in ev]) * 1e3
+
+    us = rate(None)
+    # the same cast with the channel gather done at append time (a seeded permutation per KV head)
+    g = torch.Generator().manual_seed(synth.BASE_SEED)
+    perm = torch.stack([torch.randperm(w.head_dim, generator=g) for _ in range(w.n_kv_heads)]).to(torch.int32).to(device)
+    us_perm = rate(perm)
     elems = 2 * k.numel()
     bytes_ = elems * 2 + elems * w.mant_bits // 8 + elems // w.block
     return {"workload": w.name, "elements": elems, "us_median": float(np.median(us)), "us_min": float(us.min()),
             "gelem_s": elems / np.median(us) / 1e3, "hbm_gb_s": bytes_ / np.median(us) / 1e3,
-            "hbm_frac": bytes_ / np.median(us) / 1e3 / HBM_PEAK_GBS}
+            "hbm_frac": bytes_ / np.median(us) / 1e3 / HBM_PEAK_GBS,
+            "with_perm_us_median": float(np.median(us_perm)), "with_perm_gelem_s": elems / np.median(us_perm) / 1e3}
 
 
 def main():
