@@ -165,6 +165,23 @@ int kvbfp_decode_attention(const kvbfp_layout* layout, const kvbfp_cache* cache,
                            const int32_t* perm_v, void* out, void* workspace,
                            size_t workspace_bytes, void* hip_stream);
 
+/* DEVICE, asynchronous.  kvbfp_decode_attention with the query in Block Floating Point as well
+ * (Sec. III and Sec. IV: the activations entering the score product are BFP too, 8-bit mantissas in
+ * the paper's experiments).  The permuted query q' of every head is cast exactly like a cached row
+ * (Eq. (1); blocks of layout->block channels, q_mant_bits-bit sign-magnitude mantissas, shared
+ * exponent from the block's largest magnitude, round to nearest even) before softmax_scale is
+ * applied, so each block's contribution to a score is an integer dot product of mantissas times a
+ * power of two.  The cast happens inside the kernel; q in memory is not modified.
+ *   q_mant_bits : 8 or 4; 0 behaves exactly like kvbfp_decode_attention.
+ * All other arguments, the workspace size and the error behaviour are those of
+ * kvbfp_decode_attention; a q_mant_bits outside {0, 4, 8} is INVALID_ARG. */
+int kvbfp_decode_attention_qbfp(const kvbfp_layout* layout, const kvbfp_cache* cache,
+                                int32_t n_q_heads, const void* q, kvbfp_dtype dtype,
+                                const int32_t* seq_len_dev, int64_t max_len, float softmax_scale,
+                                const int32_t* perm_k, const int32_t* perm_v, int32_t q_mant_bits,
+                                void* out, void* workspace, size_t workspace_bytes,
+                                void* hip_stream);
+
 /* Message describing the last error on the calling thread ("" if none).  Static storage. */
 const char* kvbfp_last_error(void);
 

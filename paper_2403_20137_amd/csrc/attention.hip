@@ -16,6 +16,7 @@
 #include <cstdint>
 
 #include "decode_args.h"
+#include "decode_dev.h"
 #include "kvbfp_internal.h"
 
 using kvbfp::DecodeArgs;
@@ -93,17 +94,22 @@ __global__ __launch_bounds__(kTile) void decode_split_generic(DecodeArgs a, int 
         return;
     }
 
-    // q' = permuted query times softmax_scale*log2(e); unused head slots are zero
+    // q' = permuted query (optionally cast to BFP) times softmax_scale*log2(e); unused head slots are zero
     for (int i = tid; i < kHeadsPerWg * kD; i += kTile) {
         const int g = i / kD, j = i % kD;
         float v = 0.f;
         if (g < n_act) {
             const int c = a.perm_k ? a.perm_k[kvh * kD + j] : j;
-            v = load_as_float(a.q, dt, ((int64_t)b * a.H_q + h0 + g) * kD + c) * a.scale_log2e;
+            v = load_as_float(a.q, dt, ((int64_t)b * a.H_q + h0 + g) * kD + c);
         }
-        qs[g][j] = v;
+        qs[g][j] = a.q_mant_bits ? v : v * a.scale_log2e;
     }
     __syncthreads();
+    if (a.q_mant_bits) {
+        kvbfp::dev::bfp_round_queries(&qs[0][0], (uint32_t*)&sc[0][0], kHeadsPerWg, a.log2_block, a.q_mant_bits);
+        for (int i = tid; i < kHeadsPerWg * kD; i += kTile) (&qs[0][0])[i] *= a.scale_log2e;
+        __syncthreads();
+    }
 
     const int64_t base = ((int64_t)b * a.H_kv + kvh) * a.max_seq;
     float m_run = -INFINITY, l_run = 0.f;          // wave g owns head g0+g (uniform per wave)
@@ -330,12 +336,14 @@ size_t kvbfp_decode_workspace_bytes(const kvbfp_layout* L, int32_t n_q_heads, in
     return (size_t)L->batch * (size_t)n_q_heads * (size_t)sp.n_splits * (size_t)(kD + 2) * sizeof(float);
 }
 
-int kvbfp_decode_attention(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t n_q_heads,
-                           const void* q, kvbfp_dtype dtype, const int32_t* seq_len_dev,
-                           int64_t max_len, float softmax_scale, const int32_t* perm_k,
-                           const int32_t* perm_v, void* out, void* workspace,
-                           size_t workspace_bytes, void* hip_stream) {
+static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t n_q_heads,
+                       const void* q, kvbfp_dtype dtype, const int32_t* seq_len_dev,
+                       int64_t max_len, float softmax_scale, const int32_t* perm_k,
+                       const int32_t* perm_v, int32_t q_mant_bits, void* out, void* workspace,
+                       size_t workspace_bytes, void* hip_stream) {
     clear_error();
+    if (q_mant_bits != 0 && q_mant_bits != 4 && q_mant_bits != 8)
+        return fail(KVBFP_ERR_INVALID_ARG, "decode_attention: q_mant_bits = %d (0, 4 or 8)", q_mant_bits);
     if (int rc = check_device_layout(L)) return rc;
     if (int rc = check_cache(cache, true, true)) return rc;
     if (!q || !out) return fail(KVBFP_ERR_INVALID_ARG, "decode_attention: q/out is NULL");
@@ -366,6 +374,7 @@ int kvbfp_decode_attention(const kvbfp_layout* L, const kvbfp_cache* cache, int3
     a.max_seq = L->max_seq; a.max_len = max_len; a.split_len = sp.split_len;
     a.H_kv = L->n_kv_heads; a.H_q = n_q_heads; a.G = n_q_heads / L->n_kv_heads;
     a.n_splits = sp.n_splits; a.log2_block = log2_exact(L->block);
+    a.q_mant_bits = q_mant_bits;
     a.scale_log2e = softmax_scale * 1.4426950408889634f;
 
     hipStream_t s = (hipStream_t)hip_stream;
@@ -391,6 +400,24 @@ int kvbfp_decode_attention(const kvbfp_layout* L, const kvbfp_cache* cache, int3
     err = hipGetLastError();
     if (err != hipSuccess) return fail(KVBFP_ERR_HIP, "decode_attention (combine pass): %s", hipGetErrorString(err));
     return KVBFP_OK;
+}
+
+int kvbfp_decode_attention(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t n_q_heads,
+                           const void* q, kvbfp_dtype dtype, const int32_t* seq_len_dev,
+                           int64_t max_len, float softmax_scale, const int32_t* perm_k,
+                           const int32_t* perm_v, void* out, void* workspace,
+                           size_t workspace_bytes, void* hip_stream) {
+    return decode_impl(L, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v, 0, out,
+                       workspace, workspace_bytes, hip_stream);
+}
+
+int kvbfp_decode_attention_qbfp(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t n_q_heads,
+                                const void* q, kvbfp_dtype dtype, const int32_t* seq_len_dev,
+                                int64_t max_len, float softmax_scale, const int32_t* perm_k,
+                                const int32_t* perm_v, int32_t q_mant_bits, void* out, void* workspace,
+                                size_t workspace_bytes, void* hip_stream) {
+    return decode_impl(L, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v,
+                       q_mant_bits, out, workspace, workspace_bytes, hip_stream);
 }
 
 }  // extern "C"

@@ -21,6 +21,7 @@ struct DecodeArgs {
     float* part_o;            // [B][H_q][n_splits][D]
     int64_t max_seq, max_len, split_len;
     int32_t H_kv, H_q, G, n_splits, log2_block;
+    int32_t q_mant_bits;      // 0, or the mantissa bits the permuted query is cast to (block = cache block)
     float scale_log2e;
 };
 

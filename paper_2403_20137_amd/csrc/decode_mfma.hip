@@ -98,17 +98,25 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
         return;
     }
 
-    // q' = permuted query * softmax_scale*log2(e) * 2^kShift; head slots beyond G are zero
-    for (int i = tid; i < NH * kD; i += 256) {
-        const int g = i / kD, c = i % kD;
-        float v = 0.f;
-        if (g < a.G) {
-            const int src = a.perm_k ? a.perm_k[kvh * kD + c] : c;
-            v = load_as_float(a.q, dt, ((int64_t)b * a.H_q + h0 + g) * kD + src) * a.scale_log2e * (float)(1 << kShift);
+    // q' = permuted query (optionally cast to BFP) * softmax_scale*log2(e) * 2^kShift; head slots beyond G are zero
+    {
+        const float factor = a.scale_log2e * (float)(1 << kShift);
+        for (int i = tid; i < NH * kD; i += 256) {
+            const int g = i / kD, c = i % kD;
+            float v = 0.f;
+            if (g < a.G) {
+                const int src = a.perm_k ? a.perm_k[kvh * kD + c] : c;
+                v = load_as_float(a.q, dt, ((int64_t)b * a.H_q + h0 + g) * kD + src);
+            }
+            q_s[g][c] = a.q_mant_bits ? v : v * factor;
         }
-        q_s[g][c] = v;
+        __syncthreads();
+        if (a.q_mant_bits) {
+            bfp_round_queries(&q_s[0][0], (uint32_t*)&o_s[0][0][0], NH, a.log2_block, a.q_mant_bits);
+            for (int i = tid; i < NH * kD; i += 256) (&q_s[0][0])[i] *= factor;
+            __syncthreads();
+        }
     }
-    __syncthreads();
 
     // A operands of the score product: row r = lane%16 = 4*head + limb, k-slot (kg, x) of MFMA d
     // is channel 32*kg + 8*d + slot_channel(x).
@@ -537,6 +545,25 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
     bf16x8 aq[HG][4];      // bf16 path: row 4*head + limb (3 limbs), 4 MFMAs of 32 channels
     v8i aq8[HG];           // fp4-key path: row 4*head + limb (4 FP8 limbs), one MFMA of 128 channels
     int sa8[HG];           //               E8M0 scale of this lane's 32 query values
+    // With the BFP query option the permuted queries are first cast in LDS (the probability buffer is
+    // free until the main loop) and the operand builders below read them from there.
+    const float* qr = nullptr;
+    if (a.q_mant_bits) {
+        float* qr_s = (float*)&p_lds[0][0];
+        static_assert(sizeof(p_lds) >= NH * kD * 4 + NH * 8 * 4, "query cast scratch fits the probability buffer");
+        for (int i = tid; i < NH * kD; i += 256) {
+            const int g = i / kD, c = i % kD;
+            float f = 0.f;
+            if (g < a.G) {
+                const int src = a.perm_k ? a.perm_k[kvh * kD + c] : c;
+                f = load_as_float(a.q, dt, ((int64_t)b * a.H_q + h0 + g) * kD + src);
+            }
+            qr_s[i] = f;
+        }
+        __syncthreads();
+        bfp_round_queries(qr_s, (uint32_t*)(qr_s + NH * kD), NH, a.log2_block, a.q_mant_bits);
+        qr = qr_s;
+    }
     if (kFp4Keys) {
         // FP8 operand layout (measured): byte i of lane-group g is channel 64*(i/16) + 16*g + i%16, while
         // the E8M0 scale of channel block kb (32 consecutive channels) is taken from lane-group kb.
@@ -551,7 +578,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
             float f = 0.f;
             if (g < a.G) {
                 const int src = a.perm_k ? a.perm_k[kvh * kD + c] : c;
-                f = load_as_float(a.q, dt, ((int64_t)b * a.H_q + h0 + g) * kD + src) * a.scale_log2e;
+                f = (qr ? qr[i] : load_as_float(a.q, dt, ((int64_t)b * a.H_q + h0 + g) * kD + src)) * a.scale_log2e;
             }
             qf[i] = f;
         }
@@ -593,7 +620,8 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
             float f = 0.f;
             if (g < a.G) {
                 const int src = a.perm_k ? a.perm_k[kvh * kD + c] : c;
-                f = load_as_float(a.q, dt, ((int64_t)b * a.H_q + h0 + g) * kD + src) * a.scale_log2e * (float)(1 << kShift);
+                f = (qr ? qr[g * kD + c] : load_as_float(a.q, dt, ((int64_t)b * a.H_q + h0 + g) * kD + src)) *
+                    a.scale_log2e * (float)(1 << kShift);
             }
             const __bf16 l0 = (__bf16)f;
             const float r1 = f - (float)l0;

@@ -100,17 +100,25 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p8(DecodeArgs a, int dt
         return;
     }
 
-    // q' = permuted query * softmax_scale*log2(e) * 2^kShift; head slots beyond G are zero
-    for (int i = tid; i < NH * kD; i += 256) {
-        const int g = i / kD, c = i % kD;
-        float v = 0.f;
-        if (g < a.G) {
-            const int src = a.perm_k ? a.perm_k[kvh * kD + c] : c;
-            v = load_as_float(a.q, dt, ((int64_t)b * a.H_q + h0 + g) * kD + src) * a.scale_log2e * (float)(1 << kShift);
+    // q' = permuted query (optionally cast to BFP) * softmax_scale*log2(e) * 2^kShift; head slots beyond G are zero
+    {
+        const float factor = a.scale_log2e * (float)(1 << kShift);
+        for (int i = tid; i < NH * kD; i += 256) {
+            const int g = i / kD, c = i % kD;
+            float v = 0.f;
+            if (g < a.G) {
+                const int src = a.perm_k ? a.perm_k[kvh * kD + c] : c;
+                v = load_as_float(a.q, dt, ((int64_t)b * a.H_q + h0 + g) * kD + src);
+            }
+            q_s[g][c] = a.q_mant_bits ? v : v * factor;
         }
-        q_s[g][c] = v;
+        __syncthreads();
+        if (a.q_mant_bits) {
+            bfp_round_queries(&q_s[0][0], (uint32_t*)&o_s[0][0][0], NH, a.log2_block, a.q_mant_bits);
+            for (int i = tid; i < NH * kD; i += 256) (&q_s[0][0])[i] *= factor;
+            __syncthreads();
+        }
     }
-    __syncthreads();
 
     // A operands of the score product: row r = lane%16 = 4*head + limb; MFMA d (0..7) reduces over
     // the four channels 64*(d/4) + 16*kg + 4*(d%4) + (0..3), slots 0-3 against the hi pieces and

@@ -23,7 +23,7 @@ _NP_DT = {np.dtype(np.float32): F32, np.dtype(np.float16): F16}
 
 EXPORTS = ["kvbfp_cache_bytes", "kvbfp_calibrate_perm", "kvbfp_permute_weights",
            "kvbfp_quantize_append", "kvbfp_dequantize", "kvbfp_decode_workspace_bytes",
-           "kvbfp_decode_attention", "kvbfp_last_error", "kvbfp_version"]
+           "kvbfp_decode_attention", "kvbfp_decode_attention_qbfp", "kvbfp_last_error", "kvbfp_version"]
 
 
 class KvbfpError(RuntimeError):
@@ -71,6 +71,10 @@ def lib():
         l.kvbfp_decode_attention.argtypes = [C.POINTER(Layout), C.POINTER(CachePtrs), C.c_int32, C.c_void_p,
                                              C.c_int, C.c_void_p, C.c_int64, C.c_float, C.c_void_p,
                                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        l.kvbfp_decode_attention_qbfp.argtypes = [C.POINTER(Layout), C.POINTER(CachePtrs), C.c_int32, C.c_void_p,
+                                                  C.c_int, C.c_void_p, C.c_int64, C.c_float, C.c_void_p,
+                                                  C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t,
+                                                  C.c_void_p]
         _lib = l
     return _lib
 
@@ -237,9 +241,7 @@ def decode_workspace_bytes(layout: Layout, n_q_heads, max_len) -> int:
     return int(lib().kvbfp_decode_workspace_bytes(C.byref(layout), int(n_q_heads), int(max_len)))
 
 
-def decode_attention(cache: Cache, q, max_len, softmax_scale, seq_len_dev=None, perm_k=None,
-                     perm_v=None, out=None, workspace=None, stream=None):
-    """DEVICE, async.  q: [batch][n_q_heads][head_dim] contiguous device tensor; returns `out`."""
+def _decode_common(cache, q, max_len, out, workspace):
     L = cache.layout
     if q.dim() != 3 or not q.is_contiguous():
         raise ValueError("q must be a contiguous [batch][n_q_heads][head_dim] tensor")
@@ -249,8 +251,15 @@ def decode_attention(cache: Cache, q, max_len, softmax_scale, seq_len_dev=None, 
     if workspace is None:
         need = decode_workspace_bytes(L, n_q_heads, max_len)
         if need == 0:
-            _check(ERR_INVALID_ARG if not last_error() else ERR_INVALID_ARG)
+            _check(ERR_INVALID_ARG)
         workspace = torch.empty((need,), dtype=torch.uint8, device=q.device)
+    return L, n_q_heads, out, workspace
+
+
+def decode_attention(cache: Cache, q, max_len, softmax_scale, seq_len_dev=None, perm_k=None,
+                     perm_v=None, out=None, workspace=None, stream=None):
+    """DEVICE, async.  q: [batch][n_q_heads][head_dim] contiguous device tensor; returns `out`."""
+    L, n_q_heads, out, workspace = _decode_common(cache, q, max_len, out, workspace)
     ptrs = cache.ptrs
     _check(lib().kvbfp_decode_attention(C.byref(L), C.byref(ptrs), n_q_heads, _dev_ptr(q),
                                         _TORCH_DT[q.dtype], _dev_ptr(seq_len_dev, torch.int32),
@@ -258,4 +267,18 @@ def decode_attention(cache: Cache, q, max_len, softmax_scale, seq_len_dev=None, 
                                         _dev_ptr(perm_k, torch.int32), _dev_ptr(perm_v, torch.int32),
                                         _dev_ptr(out), _dev_ptr(workspace), workspace.numel(),
                                         _stream_ptr(stream)))
+    return out
+
+
+def decode_attention_qbfp(cache: Cache, q, max_len, softmax_scale, q_mant_bits, seq_len_dev=None, perm_k=None,
+                          perm_v=None, out=None, workspace=None, stream=None):
+    """DEVICE, async.  decode_attention with the permuted query cast to BFP (q_mant_bits 4 or 8) first."""
+    L, n_q_heads, out, workspace = _decode_common(cache, q, max_len, out, workspace)
+    ptrs = cache.ptrs
+    _check(lib().kvbfp_decode_attention_qbfp(C.byref(L), C.byref(ptrs), n_q_heads, _dev_ptr(q),
+                                             _TORCH_DT[q.dtype], _dev_ptr(seq_len_dev, torch.int32),
+                                             int(max_len), float(softmax_scale),
+                                             _dev_ptr(perm_k, torch.int32), _dev_ptr(perm_v, torch.int32),
+                                             int(q_mant_bits), _dev_ptr(out), _dev_ptr(workspace),
+                                             workspace.numel(), _stream_ptr(stream)))
     return out

@@ -11,18 +11,23 @@ from util import DT_NAME, assert_attention_close, assert_planes_equal, dev_i32, 
 pytestmark = pytest.mark.gpu
 
 
-def run_both(k, v, q, n, p, lens, scale, pk=None, pv=None, S_max=None, use_seq_len=True):
+def run_both(k, v, q, n, p, lens, scale, pk=None, pv=None, S_max=None, use_seq_len=True, q_mant_bits=0):
     """k, v: CPU tensors [B][S][Hkv][D]; q: CPU [B][Hq][D].  Returns (gpu_out, oracle_out)."""
     B, S, Hkv, D = k.shape
     S_max = S if S_max is None else S_max
     planes = oracle_cache(k, v, n, p, S_max, 0, pk, pv)
     cache = gpu_cache(k.cuda(), v.cuda(), n, p, S_max, perm_k=pk, perm_v=pv)
     assert_planes_equal(cache, planes, "cache before attention")
-    want = O.decode_attention(*planes, D, n, p, synth.to_f32_numpy(q), lens, float(np.float32(scale)), pk, pv)
+    want = O.decode_attention(*planes, D, n, p, synth.to_f32_numpy(q), lens, float(np.float32(scale)), pk, pv,
+                              q_mant_bits=q_mant_bits)
     max_len = int(np.max(lens))
     sl = dev_i32(np.broadcast_to(np.asarray(lens), (B,))) if use_seq_len else None
-    got = kvbfp.decode_attention(cache, q.cuda(), max_len, float(np.float32(scale)), seq_len_dev=sl,
-                                 perm_k=dev_i32(pk), perm_v=dev_i32(pv))
+    if q_mant_bits:
+        got = kvbfp.decode_attention_qbfp(cache, q.cuda(), max_len, float(np.float32(scale)), q_mant_bits,
+                                          seq_len_dev=sl, perm_k=dev_i32(pk), perm_v=dev_i32(pv))
+    else:
+        got = kvbfp.decode_attention(cache, q.cuda(), max_len, float(np.float32(scale)), seq_len_dev=sl,
+                                     perm_k=dev_i32(pk), perm_v=dev_i32(pv))
     torch.cuda.synchronize()
     return got, want
 
@@ -49,6 +54,24 @@ def test_decode_attention_matches_oracle(dtype, p, n, G):
     k, v, q, pk, pv = make_small(dtype, B=2, S=700, Hkv=2, G=G, seed=20 + G)
     got, want = run_both(k, v, q, n, p, [700, 259], 128 ** -0.5, pk, pv, S_max=720)
     assert_attention_close(got, want, dtype, "p=%d n=%d G=%d" % (p, n, G))
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("p,n", [(4, 16), (4, 32), (4, 64), (8, 16), (8, 128)])
+@pytest.mark.parametrize("G,qbits", [(1, 8), (4, 8), (4, 4), (6, 8)])
+def test_query_cast_to_bfp_matches_oracle(dtype, p, n, G, qbits):
+    # Sec. III / Sec. IV: the query enters the score product as BFP (8-bit mantissas in the paper's
+    # experiments); the cast is decided on exact fp32 values on both sides, so the tolerance is the
+    # one of the plain path.
+    k, v, q, pk, pv = make_small(dtype, B=2, S=600, Hkv=2, G=G, seed=70 + G)
+    got, want = run_both(k, v, q, n, p, [600, 77], 128 ** -0.5, pk, pv, q_mant_bits=qbits)
+    assert_attention_close(got, want, dtype, "qbits=%d p=%d n=%d G=%d" % (qbits, p, n, G))
+    # and the option is not a no-op: 4-bit queries move the result far beyond the tolerance
+    if qbits == 4:
+        plain = kvbfp.decode_attention(gpu_cache(k.cuda(), v.cuda(), n, p, 600, perm_k=pk, perm_v=pv), q.cuda(), 600,
+                                       float(np.float32(128 ** -0.5)), perm_k=dev_i32(pk), perm_v=dev_i32(pv))
+        torch.cuda.synchronize()
+        assert (plain.double().cpu() - got.double().cpu()).norm() > 1e-2 * got.double().cpu().norm()
 
 
 @pytest.mark.parametrize("p", [4, 8])

@@ -133,6 +133,14 @@ def test_device_calls_reject_bad_arguments_before_launching():
     assert da(max_len=0) == kvbfp.ERR_INVALID_ARG
     assert da(q=None) == kvbfp.ERR_INVALID_ARG
     assert da(scale=float("nan")) == kvbfp.ERR_INVALID_ARG
+
+    def daq(qbits, n_q=4):
+        return lib.kvbfp_decode_attention_qbfp(C.byref(good), C.byref(ptrs), n_q, fake, kvbfp.BF16, None, 64,
+                                               0.1, None, None, qbits, fake, fake, 1 << 30, None)
+
+    assert daq(5) == kvbfp.ERR_INVALID_ARG and "q_mant_bits" in kvbfp.last_error()
+    assert daq(-8) == kvbfp.ERR_INVALID_ARG
+    assert daq(8, n_q=3) == kvbfp.ERR_INVALID_ARG      # the other checks are those of the plain call
     assert da(ws=None) == kvbfp.ERR_WORKSPACE
     assert da(ws_bytes=16) == kvbfp.ERR_WORKSPACE and "workspace" in kvbfp.last_error()
     assert da(ws=C.c_void_p(0x1010)) == kvbfp.ERR_WORKSPACE
