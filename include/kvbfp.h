@@ -182,6 +182,20 @@ int kvbfp_decode_attention_qbfp(const kvbfp_layout* layout, const kvbfp_cache* c
                                 void* out, void* workspace, size_t workspace_bytes,
                                 void* hip_stream);
 
+/* DEVICE, SYNCHRONOUS, for measurement.  Enqueues exactly the launches of
+ * kvbfp_decode_attention_qbfp (Sec. III; same arguments, same result in `out`) with HIP events
+ * recorded on `hip_stream` before the split pass, between the two passes and after the combine
+ * pass, waits for the last one and returns the two durations in milliseconds:
+ *   kernel_ms : HOST float[2]; [0] = split pass (the kernel that streams the cache), [1] = combine.
+ * Creates and destroys three events per call; not meant for a serving loop.
+ * Errors: as kvbfp_decode_attention_qbfp, plus INVALID_ARG for a NULL kernel_ms. */
+int kvbfp_decode_attention_profile(const kvbfp_layout* layout, const kvbfp_cache* cache,
+                                   int32_t n_q_heads, const void* q, kvbfp_dtype dtype,
+                                   const int32_t* seq_len_dev, int64_t max_len, float softmax_scale,
+                                   const int32_t* perm_k, const int32_t* perm_v, int32_t q_mant_bits,
+                                   void* out, void* workspace, size_t workspace_bytes,
+                                   void* hip_stream, float* kernel_ms);
+
 /* Message describing the last error on the calling thread ("" if none).  Static storage. */
 const char* kvbfp_last_error(void);
 

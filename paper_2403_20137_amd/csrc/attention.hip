@@ -340,7 +340,7 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
                        const void* q, kvbfp_dtype dtype, const int32_t* seq_len_dev,
                        int64_t max_len, float softmax_scale, const int32_t* perm_k,
                        const int32_t* perm_v, int32_t q_mant_bits, void* out, void* workspace,
-                       size_t workspace_bytes, void* hip_stream) {
+                       size_t workspace_bytes, void* hip_stream, float* kernel_ms = nullptr) {
     clear_error();
     if (q_mant_bits != 0 && q_mant_bits != 4 && q_mant_bits != 8)
         return fail(KVBFP_ERR_INVALID_ARG, "decode_attention: q_mant_bits = %d (0, 4 or 8)", q_mant_bits);
@@ -385,6 +385,13 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
     auto aligned16 = [](const void* p) { return ((uintptr_t)p & 15u) == 0; };
     const bool fast = a.G <= 8 && dtype != KVBFP_F32 && aligned16(a.k_mant) &&
                       aligned16(a.v_mant) && aligned16(a.k_exp) && aligned16(a.v_exp);
+    // Optional timing of the two launches (kvbfp_decode_attention_profile): events on the same stream.
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+    if (kernel_ms) {
+        for (auto& e : ev)
+            if (hipEventCreate(&e) != hipSuccess) return fail(KVBFP_ERR_HIP, "decode_attention_profile: hipEventCreate failed");
+        (void)hipEventRecord(ev[0], s);
+    }
     hipError_t err;
     if (fast) {
         err = L->mant_bits == 4 ? launch_decode_split_mfma(a, (int)dtype, L->block, L->batch, s)
@@ -394,11 +401,21 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
         else decode_split_generic<8><<<grid1, kTile, 0, s>>>(a, (int)dtype);
         err = hipGetLastError();
     }
-    if (err != hipSuccess) return fail(KVBFP_ERR_HIP, "decode_attention (split pass): %s", hipGetErrorString(err));
-    const dim3 grid2((unsigned)n_q_heads, (unsigned)L->batch, 1);
-    decode_combine<<<grid2, kD, 0, s>>>(a, (int)dtype);
-    err = hipGetLastError();
-    if (err != hipSuccess) return fail(KVBFP_ERR_HIP, "decode_attention (combine pass): %s", hipGetErrorString(err));
+    if (kernel_ms) (void)hipEventRecord(ev[1], s);
+    if (err == hipSuccess) {
+        const dim3 grid2((unsigned)n_q_heads, (unsigned)L->batch, 1);
+        decode_combine<<<grid2, kD, 0, s>>>(a, (int)dtype);
+        err = hipGetLastError();
+    }
+    if (kernel_ms) {
+        (void)hipEventRecord(ev[2], s);
+        hipError_t e2 = hipEventSynchronize(ev[2]);
+        if (e2 == hipSuccess) e2 = hipEventElapsedTime(&kernel_ms[0], ev[0], ev[1]);
+        if (e2 == hipSuccess) e2 = hipEventElapsedTime(&kernel_ms[1], ev[1], ev[2]);
+        for (auto& e : ev) (void)hipEventDestroy(e);
+        if (err == hipSuccess) err = e2;
+    }
+    if (err != hipSuccess) return fail(KVBFP_ERR_HIP, "decode_attention: %s", hipGetErrorString(err));
     return KVBFP_OK;
 }
 
@@ -418,6 +435,19 @@ int kvbfp_decode_attention_qbfp(const kvbfp_layout* L, const kvbfp_cache* cache,
                                 size_t workspace_bytes, void* hip_stream) {
     return decode_impl(L, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v,
                        q_mant_bits, out, workspace, workspace_bytes, hip_stream);
+}
+
+int kvbfp_decode_attention_profile(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t n_q_heads,
+                                   const void* q, kvbfp_dtype dtype, const int32_t* seq_len_dev,
+                                   int64_t max_len, float softmax_scale, const int32_t* perm_k,
+                                   const int32_t* perm_v, int32_t q_mant_bits, void* out, void* workspace,
+                                   size_t workspace_bytes, void* hip_stream, float* kernel_ms) {
+    if (!kernel_ms) {
+        clear_error();
+        return fail(KVBFP_ERR_INVALID_ARG, "decode_attention_profile: kernel_ms is NULL");
+    }
+    return decode_impl(L, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v,
+                       q_mant_bits, out, workspace, workspace_bytes, hip_stream, kernel_ms);
 }
 
 }  // extern "C"

@@ -23,7 +23,8 @@ _NP_DT = {np.dtype(np.float32): F32, np.dtype(np.float16): F16}
 
 EXPORTS = ["kvbfp_cache_bytes", "kvbfp_calibrate_perm", "kvbfp_permute_weights",
            "kvbfp_quantize_append", "kvbfp_dequantize", "kvbfp_decode_workspace_bytes",
-           "kvbfp_decode_attention", "kvbfp_decode_attention_qbfp", "kvbfp_last_error", "kvbfp_version"]
+           "kvbfp_decode_attention", "kvbfp_decode_attention_qbfp", "kvbfp_decode_attention_profile",
+           "kvbfp_last_error", "kvbfp_version"]
 
 
 class KvbfpError(RuntimeError):
@@ -75,6 +76,7 @@ def lib():
                                                   C.c_int, C.c_void_p, C.c_int64, C.c_float, C.c_void_p,
                                                   C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t,
                                                   C.c_void_p]
+        l.kvbfp_decode_attention_profile.argtypes = l.kvbfp_decode_attention_qbfp.argtypes + [C.POINTER(C.c_float)]
         _lib = l
     return _lib
 
@@ -282,3 +284,18 @@ def decode_attention_qbfp(cache: Cache, q, max_len, softmax_scale, q_mant_bits, 
                                              int(q_mant_bits), _dev_ptr(out), _dev_ptr(workspace),
                                              workspace.numel(), _stream_ptr(stream)))
     return out
+
+
+def decode_attention_profile(cache: Cache, q, max_len, softmax_scale, q_mant_bits=0, seq_len_dev=None, perm_k=None,
+                             perm_v=None, out=None, workspace=None, stream=None):
+    """DEVICE, synchronous.  Same launches as decode_attention_qbfp; returns (out, split_ms, combine_ms)."""
+    L, n_q_heads, out, workspace = _decode_common(cache, q, max_len, out, workspace)
+    ptrs = cache.ptrs
+    ms = (C.c_float * 2)()
+    _check(lib().kvbfp_decode_attention_profile(C.byref(L), C.byref(ptrs), n_q_heads, _dev_ptr(q),
+                                                _TORCH_DT[q.dtype], _dev_ptr(seq_len_dev, torch.int32),
+                                                int(max_len), float(softmax_scale),
+                                                _dev_ptr(perm_k, torch.int32), _dev_ptr(perm_v, torch.int32),
+                                                int(q_mant_bits), _dev_ptr(out), _dev_ptr(workspace),
+                                                workspace.numel(), _stream_ptr(stream), ms))
+    return out, float(ms[0]), float(ms[1])
