@@ -249,59 +249,87 @@ __device__ __forceinline__ uint16_t narrow_bf16(float v) {
     return (uint16_t)(u >> 16);
 }
 
-// Pass 2: merge the splits of one (batch, query head).  grid = (H_q, B), block = 128 (one channel
-// per thread).  The (m, l) pairs go through LDS once; the partial outputs are read with eight
-// independent loads in flight per thread, so the pass costs a couple of memory round trips
-// rather than one per split.
-__global__ __launch_bounds__(kD) void decode_combine(DecodeArgs a, int dt) {
+// Pass 2: merge the splits of one (batch, query head).  grid = (H_q, B), block = 512: four slices of
+// the splits times 128 channels.  A round trip to memory costs far more than anything computed here,
+// so every thread first puts up to 8 or 32 partial-output loads in flight (enough for 32 or 128
+// splits in one go), then the (m, l) pairs go through LDS, and the four slices are added through LDS at the end.
+constexpr int kCombineSlices = 4;
+// kCombineBatch: loads in flight per thread, 8 (up to 32 splits without a second round) or 32.
+template <int kCombineBatch>
+__global__ __launch_bounds__(kD * kCombineSlices) void decode_combine(DecodeArgs a, int dt) {
     constexpr int kMaxLds = 1024;
-    __shared__ float w_s[kMaxLds];          // m_i, then the weight 2^(m_i - M)
+    __shared__ float m_s[kMaxLds];
     __shared__ float l_s[kMaxLds];
-    const int j = threadIdx.x;
+    __shared__ float red[kCombineSlices][2][kD];
+    __shared__ float red_m[kCombineSlices];
+    const int j = threadIdx.x % kD, sl = threadIdx.x / kD;
     const int h = blockIdx.x, b = blockIdx.y;
     const int64_t bh = (int64_t)b * a.H_q + h;
     const float* ml = a.part_ml + bh * a.n_splits * 2;
     const float* po = a.part_o + bh * a.n_splits * kD;
     const int n = a.n_splits;
+    const bool staged = n <= kMaxLds;           // otherwise (m, l) are read from global memory each time
+
+    float v[kCombineBatch];                     // first batch of this thread's partial outputs: splits sl + 4k
+#pragma unroll
+    for (int k = 0; k < kCombineBatch; ++k) {
+        const int i = sl + k * kCombineSlices;
+        v[k] = i < n ? po[(int64_t)i * kD + j] : 0.f;
+    }
+    if (staged) {
+        for (int i = threadIdx.x; i < n; i += kD * kCombineSlices) {
+            const float2 t = *(const float2*)(ml + 2 * i);
+            m_s[i] = t.x;
+            l_s[i] = t.y;
+        }
+        __syncthreads();
+    }
+    auto m_of = [&](int i) { return staged ? m_s[i] : ml[2 * i]; };
+    auto l_of = [&](int i) { return staged ? l_s[i] : ml[2 * i + 1]; };
+    // Each slice works relative to the maximum of its own splits (a short, unrolled scan instead of
+    // one long serial loop over all of them); the slices are brought to the common maximum at the end.
+    float mk[kCombineBatch];
+    float Ms = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < kCombineBatch; ++k) {
+        const int i = sl + k * kCombineSlices;
+        mk[k] = i < n ? m_of(i) : -INFINITY;
+        Ms = fmaxf(Ms, mk[k]);
+    }
+    for (int i = sl + kCombineBatch * kCombineSlices; i < n; i += kCombineSlices) Ms = fmaxf(Ms, m_of(i));
     float num = 0.f, den = 0.f;
-    if (n <= kMaxLds) {
-        for (int i = j; i < n; i += kD) {
-            const float2 v = *(const float2*)(ml + 2 * i);
-            w_s[i] = v.x;
-            l_s[i] = v.y;
-        }
-        __syncthreads();
-        float M = -INFINITY;
-        for (int i = 0; i < n; ++i) M = fmaxf(M, w_s[i]);
-        __syncthreads();
-        if (M > -INFINITY) {
-            for (int i = j; i < n; i += kD) w_s[i] = exp2f(w_s[i] - M);   // empty splits carry m = -inf -> weight 0
-            __syncthreads();
-            int i = 0;
-            for (; i + 8 <= n; i += 8) {
-                float v[8];
+    if (Ms > -INFINITY) {                       // empty splits carry m = -inf -> weight 0
 #pragma unroll
-                for (int k = 0; k < 8; ++k) v[k] = po[(int64_t)(i + k) * kD + j];
-#pragma unroll
-                for (int k = 0; k < 8; ++k) {
-                    num = fmaf(w_s[i + k], v[k], num);
-                    den = fmaf(w_s[i + k], l_s[i + k], den);
-                }
-            }
-            for (; i < n; ++i) {
-                num = fmaf(w_s[i], po[(int64_t)i * kD + j], num);
-                den = fmaf(w_s[i], l_s[i], den);
+        for (int k = 0; k < kCombineBatch; ++k) {
+            const int i = sl + k * kCombineSlices;
+            if (i < n) {
+                const float w = exp2f(mk[k] - Ms);
+                num = fmaf(w, v[k], num);
+                den = fmaf(w, l_of(i), den);
             }
         }
-    } else {   // very many splits: plain two-pass loop
-        float M = -INFINITY;
-        for (int i = 0; i < n; ++i) M = fmaxf(M, ml[2 * i]);
-        if (M > -INFINITY) {
-            for (int i = 0; i < n; ++i) {
-                const float w = exp2f(ml[2 * i] - M);
-                num = fmaf(w, po[(int64_t)i * kD + j], num);
-                den = fmaf(w, ml[2 * i + 1], den);
-            }
+        for (int i = sl + kCombineBatch * kCombineSlices; i < n; i += kCombineSlices) {
+            const float w = exp2f(m_of(i) - Ms);
+            num = fmaf(w, po[(int64_t)i * kD + j], num);
+            den = fmaf(w, l_of(i), den);
+        }
+    }
+    red[sl][0][j] = num;
+    red[sl][1][j] = den;
+    if (j == 0) red_m[sl] = Ms;
+    __syncthreads();
+    if (sl != 0) return;
+    float M = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < kCombineSlices; ++k) M = fmaxf(M, red_m[k]);
+    num = 0.f;
+    den = 0.f;
+    if (M > -INFINITY) {
+#pragma unroll
+        for (int k = 0; k < kCombineSlices; ++k) {
+            const float w = exp2f(red_m[k] - M);        // 0 for a slice without cached tokens
+            num = fmaf(w, red[k][0][j], num);
+            den = fmaf(w, red[k][1][j], den);
         }
     }
     const float r = den > 0.f ? num / den : 0.f;
@@ -404,7 +432,8 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
     if (kernel_ms) (void)hipEventRecord(ev[1], s);
     if (err == hipSuccess) {
         const dim3 grid2((unsigned)n_q_heads, (unsigned)L->batch, 1);
-        decode_combine<<<grid2, kD, 0, s>>>(a, (int)dtype);
+        if (sp.n_splits <= 8 * kCombineSlices) decode_combine<8><<<grid2, kD * kCombineSlices, 0, s>>>(a, (int)dtype);
+        else decode_combine<32><<<grid2, kD * kCombineSlices, 0, s>>>(a, (int)dtype);
         err = hipGetLastError();
     }
     if (kernel_ms) {
