@@ -58,19 +58,24 @@ __device__ __forceinline__ bf16x8 join(bf16x2 a, bf16x2 b, bf16x2 c, bf16x2 d) {
     return r;
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding
+// vector-memory operation of the wavefront, which a kernel with cache rows in flight cannot afford
+// during its set-up.
+__device__ __forceinline__ void lds_only_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 // Casts the queries in q_s[n_heads][128] (cache channel order, fp32, unscaled) to Block Floating Point
 // in place: blocks of 2^log2_block channels, `bits`-bit sign-magnitude mantissas, the shared exponent
 // chosen by the same rule as for cached rows (Sec. II-B, Eq. (1); Sec. III: the activations of the
 // score product are BFP as well).  The decoded values are written back, so what follows is a product
 // of exact small integers per block.  amax_s: n_heads * 8 words of LDS scratch.  Called by every
-// thread of the workgroup after q_s is complete (barrier before); ends with a barrier.
+// thread of the workgroup after q_s is complete (barrier before); ends with a barrier (LDS only).
 __device__ __forceinline__ void bfp_round_queries(float* q_s, uint32_t* amax_s, int n_heads, int log2_block, int bits) {
     const int tid = threadIdx.x, nt = blockDim.x;
     for (int i = tid; i < n_heads * 8; i += nt) amax_s[i] = 0u;
-    __syncthreads();
+    lds_only_barrier();
     for (int i = tid; i < n_heads * kD; i += nt)
         atomicMax(&amax_s[(i / kD) * 8 + ((i % kD) >> log2_block)], __float_as_uint(q_s[i]) & 0x7FFFFFFFu);
-    __syncthreads();
+    lds_only_barrier();
     for (int i = tid; i < n_heads * kD; i += nt) {
         const uint32_t amax = amax_s[(i / kD) * 8 + ((i % kD) >> log2_block)];
         const uint32_t bumped = (amax + (1u << (24 - bits))) >> 23;
@@ -78,7 +83,7 @@ __device__ __forceinline__ void bfp_round_queries(float* q_s, uint32_t* amax_s, 
         const int e = E - 127 - (bits - 2);
         q_s[i] = ldexpf(rintf(ldexpf(q_s[i], -e)), e);     // both scalings exact; rintf rounds to nearest even
     }
-    __syncthreads();
+    lds_only_barrier();
 }
 
 }  // namespace dev

@@ -444,7 +444,11 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
     constexpr int kQ8 = kQf + NH * kD * 4;         //           FP8 limbs [NH*4 rows][128], then scale bytes [NH*4][4]
     constexpr int kTotal = kFp4Keys ? kQ8 + NH * 4 * kD + NH * 16 : kQl + NH * 4 * kD * 2;
     static_assert(kWaves * NH * kD * 4 + kWaves * NH * 8 <= kQl, "merge buffers alias the staging area");
-    __shared__ __align__(16) uint8_t smem[kTotal];
+    // The DMA rings and the query staging are separate LDS objects: the compiler waits for every
+    // outstanding DMA before it touches an object that a DMA may write, and the set-up must not wait
+    // for the first tile.
+    __shared__ __align__(16) uint8_t smem[kQl];
+    __shared__ __align__(16) uint8_t q_lds[kTotal - kQl];
     // probabilities of the current tile, bf16 hi/lo limbs: [wave][HG][2 limbs][4 heads][64 tokens].  A separate
     // LDS object, so the compiler can tell its reads apart from the DMA targets inside smem.
     __shared__ __align__(16) uint16_t p_lds[kWaves][HG * 2 * 4 * kTileTok];
@@ -531,7 +535,41 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
         }
     };
 
-    // ---- first tile of this wavefront goes out before anything else ------------------------------
+    // ---- the query and its permutation are requested first, the first tile of this wavefront right
+    // after them, and only then does anybody wait: issued later, these small loads would queue
+    // behind the first tiles of every workgroup of the grid (tens of megabytes).
+    // (Loaded as raw bits and widened later: a conversion right here would make the compiler wait for
+    // each load in turn.  For the same reason the set-up below synchronises with LDS-only barriers:
+    // __syncthreads() also waits for every vector-memory operation, i.e. for the whole first tile.)
+    constexpr int kQPerThread = NH * kD / 256;
+    uint32_t q_bits[kQPerThread];
+#pragma unroll
+    for (int k = 0; k < kQPerThread; ++k) {
+        const int i = tid + 256 * k, g = i / kD, c = i % kD;
+        const int64_t idx = ((int64_t)b * a.H_q + h0 + min(g, a.G - 1)) * kD + c;      // clamped: rows beyond G are zeroed below
+        q_bits[k] = dt == KVBFP_F32 ? ((const uint32_t*)a.q)[idx] : (uint32_t)((const uint16_t*)a.q)[idx];
+    }
+    int perm_c = 0;
+    if (a.perm_k && tid < kD) perm_c = a.perm_k[kvh * kD + tid];
+    auto lds_barrier = [] { lds_only_barrier(); };
+    // The permuted (and, on request, BFP-cast) queries wait in the probability buffer, which is free
+    // until the main loop; the operand builders below read them from there.  The raw values go to LDS
+    // before the first tile is requested (the sequence length, needed for that request, was loaded
+    // after them, so they have arrived by now); everything after works on LDS only.
+    float* const qr = (float*)&p_lds[0][0];                 // [NH][kD], unscaled
+    int* const scratch = (int*)(qr + NH * kD);              // permutation, then block maxima of the cast
+    static_assert(sizeof(p_lds) >= NH * kD * 4 + kD * 4, "query staging fits the probability buffer");
+#pragma unroll
+    for (int k = 0; k < kQPerThread; ++k) {
+        const int g = (tid + 256 * k) / kD;
+        float f;
+        if (dt == KVBFP_F32) f = __uint_as_float(q_bits[k]);
+        else if (dt == KVBFP_F16) f = (float)__builtin_bit_cast(_Float16, (unsigned short)q_bits[k]);
+        else f = __uint_as_float(q_bits[k] << 16);
+        qr[tid + 256 * k] = g < a.G ? f : 0.f;
+    }
+    if (a.perm_k && tid < kD) scratch[tid] = perm_c & (kD - 1);   // a valid permutation is unchanged; keeps LDS reads in range
+
     const int T_first = wave * kTileTok;
     const bool has_work = T_first < n_tok;
     if (has_work) {
@@ -545,44 +583,33 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
     bf16x8 aq[HG][4];      // bf16 path: row 4*head + limb (3 limbs), 4 MFMAs of 32 channels
     v8i aq8[HG];           // fp4-key path: row 4*head + limb (4 FP8 limbs), one MFMA of 128 channels
     int sa8[HG];           //               E8M0 scale of this lane's 32 query values
-    // With the BFP query option the permuted queries are first cast in LDS (the probability buffer is
-    // free until the main loop) and the operand builders below read them from there.
-    const float* qr = nullptr;
-    if (a.q_mant_bits) {
-        float* qr_s = (float*)&p_lds[0][0];
-        static_assert(sizeof(p_lds) >= NH * kD * 4 + NH * 8 * 4, "query cast scratch fits the probability buffer");
-        for (int i = tid; i < NH * kD; i += 256) {
-            const int g = i / kD, c = i % kD;
-            float f = 0.f;
-            if (g < a.G) {
-                const int src = a.perm_k ? a.perm_k[kvh * kD + c] : c;
-                f = load_as_float(a.q, dt, ((int64_t)b * a.H_q + h0 + g) * kD + src);
-            }
-            qr_s[i] = f;
+    if (a.perm_k) {
+        float q_perm[kQPerThread];
+        lds_barrier();
+#pragma unroll
+        for (int k = 0; k < kQPerThread; ++k) {
+            const int i = tid + 256 * k;
+            q_perm[k] = qr[(i / kD) * kD + scratch[i % kD]];
         }
-        __syncthreads();
-        bfp_round_queries(qr_s, (uint32_t*)(qr_s + NH * kD), NH, a.log2_block, a.q_mant_bits);
-        qr = qr_s;
+        lds_barrier();
+#pragma unroll
+        for (int k = 0; k < kQPerThread; ++k) qr[tid + 256 * k] = q_perm[k];
     }
+    lds_barrier();
+    if (a.q_mant_bits) bfp_round_queries(qr, (uint32_t*)scratch, NH, a.log2_block, a.q_mant_bits);
     if (kFp4Keys) {
         // FP8 operand layout (measured): byte i of lane-group g is channel 64*(i/16) + 16*g + i%16, while
         // the E8M0 scale of channel block kb (32 consecutive channels) is taken from lane-group kb.
         // Each block of 32 query values shares a power-of-two scale 2^sh chosen so that the largest
         // lands in [128, 256); limb l holds the FP8 rounding of the residual at scale 2^(sh - 4l), so four
         // limbs carry 16 bits relative to the block's maximum.
-        float* qf = (float*)(smem + kQf);
-        uint8_t* q8 = smem + kQ8;
+        float* qf = (float*)(q_lds + (kQf - kQl));
+        uint8_t* q8 = q_lds + (kQ8 - kQl);
         uint8_t* qsc = q8 + NH * 4 * kD;
         for (int i = tid; i < NH * kD; i += 256) {
-            const int g = i / kD, c = i % kD;
-            float f = 0.f;
-            if (g < a.G) {
-                const int src = a.perm_k ? a.perm_k[kvh * kD + c] : c;
-                f = (qr ? qr[i] : load_as_float(a.q, dt, ((int64_t)b * a.H_q + h0 + g) * kD + src)) * a.scale_log2e;
-            }
-            qf[i] = f;
+            qf[i] = qr[i] * a.scale_log2e;
         }
-        __syncthreads();
+        lds_barrier();
         for (int i = tid; i < NH * kD; i += 256) {
             const int g = i / kD, pos = i % kD, ga = pos >> 5, ii = pos & 31;
             const int c = ii < 16 ? 16 * ga + ii : 64 + 16 * ga + (ii - 16);
@@ -603,7 +630,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
                 if ((c & 31) == 0) qsc[(4 * g + limb) * 4 + kb] = (uint8_t)(sl + 127);
             }
         }
-        __syncthreads();
+        lds_barrier();
 #pragma unroll
         for (int hg = 0; hg < HG; ++hg) {
             const u32x4 lo = *(const u32x4*)(q8 + (hg * 16 + j) * kD + kg * 32);
@@ -613,16 +640,11 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
         }
     } else {
         // row 4*head + limb; position 32*kg + 8*d + x holds channel 32*kg + 8*d + slot_channel(x)
-        uint16_t* ql = (uint16_t*)(smem + kQl);
+        uint16_t* ql = (uint16_t*)q_lds;
         for (int i = tid; i < NH * kD; i += 256) {
             const int g = i / kD, pos = i % kD;
             const int c = (pos & ~7) + slot_channel(pos & 7);
-            float f = 0.f;
-            if (g < a.G) {
-                const int src = a.perm_k ? a.perm_k[kvh * kD + c] : c;
-                f = (qr ? qr[g * kD + c] : load_as_float(a.q, dt, ((int64_t)b * a.H_q + h0 + g) * kD + src)) *
-                    a.scale_log2e * (float)(1 << kShift);
-            }
+            const float f = qr[g * kD + c] * a.scale_log2e * (float)(1 << kShift);
             const __bf16 l0 = (__bf16)f;
             const float r1 = f - (float)l0;
             const __bf16 l1 = (__bf16)r1;
@@ -632,12 +654,12 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
             ql[(4 * g + 2) * kD + pos] = __builtin_bit_cast(unsigned short, l2);
             ql[(4 * g + 3) * kD + pos] = 0;
         }
-        __syncthreads();
+        lds_barrier();
 #pragma unroll
         for (int hg = 0; hg < HG; ++hg)
 #pragma unroll
             for (int d = 0; d < 4; ++d)
-                aq[hg][d] = *(const bf16x8*)(smem + kQl + ((hg * 16 + j) * kD + 32 * kg + 8 * d) * 2);
+                aq[hg][d] = *(const bf16x8*)(q_lds + ((hg * 16 + j) * kD + 32 * kg + 8 * d) * 2);
     }
 
     const int a_head = j >> 2, a_par = (j >> 1) & 1, a_limb = j & 1;
