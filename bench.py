@@ -72,6 +72,8 @@ class LayerRing:
         self.k_new = synth.kv_rows(w.batch, 1, w.n_kv_heads, w.head_dim, w.dtype, kg, synth.BASE_SEED, synth.TID_K_NEW, device)
         self.v_new = synth.kv_rows(w.batch, 1, w.n_kv_heads, w.head_dim, w.dtype, vg, synth.BASE_SEED, synth.TID_V_NEW, device)
         self.pos = torch.full((w.batch,), w.seq, dtype=torch.int32, device=device)
+        self.seq_len = torch.full((w.batch,), w.seq + 1, dtype=torch.int32, device=device)
+        self.fused = True
         self.out = torch.empty_like(self.q)
         need = kvbfp.decode_workspace_bytes(self.layout, w.n_q_heads, self.S_max)
         self.workspace = torch.empty((need,), dtype=torch.uint8, device=device)
@@ -86,8 +88,14 @@ class LayerRing:
                                perm_k=self.perm_k, perm_v=self.perm_v, out=self.out, workspace=self.workspace)
 
     def step(self, i):
-        self.append(i)
-        self.decode(i)
+        """One decode step of a layer: the current token is cast and appended, then attention."""
+        if self.fused:
+            kvbfp.append_decode_attention(self.caches[i % len(self.caches)], self.k_new, self.v_new, self.q, self.S_max,
+                                          self.scale, seq_len_dev=self.seq_len, perm_k=self.perm_k, perm_v=self.perm_v,
+                                          out=self.out, workspace=self.workspace)
+        else:
+            self.append(i)
+            self.decode(i)
 
     def decode_kernels(self, i, q_mant_bits=0):
         """The same decode call with HIP events around each of its two kernels: (split us, combine us)."""
@@ -123,8 +131,10 @@ def time_graph_steps(ring: LayerRing, graphs, steps: int, warmup: int):
 
 
 def time_steps(ring: LayerRing, steps: int, warmup: int):
+    """Eager launches of the two separate calls, each bracketed by HIP events."""
     for i in range(warmup):
-        ring.step(i)
+        ring.append(i)
+        ring.decode(i)
     torch.cuda.synchronize()
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
     t0 = time.perf_counter()
@@ -216,6 +226,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of graph replays")
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="a step = quantize_append + decode_attention as two calls instead of append_decode_attention")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy a few times (known HBM bytes; used to scale "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -243,9 +255,18 @@ def main():
     n_layers = min(n_layers, 64)
     ring = LayerRing(w, n_layers)
     dec_bytes, app_bytes = algorithmic_bytes(w, w.seq + 1)
+    ring.fused = not args.separate_calls
     eager_sec_per_step, app_us, dec_us = time_steps(ring, args.steps, args.warmup)
-    sec_per_step = eager_sec_per_step
-    if not args.no_graph:
+    if args.no_graph:
+        for i in range(args.warmup):
+            ring.step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            ring.step(args.warmup + i)
+        torch.cuda.synchronize()
+        sec_per_step = (time.perf_counter() - t0) / args.steps
+    else:
         # the same steps replayed from captured graphs: the timed region of `value`
         sec_per_step = time_graph_steps(ring, capture_step_graphs(ring), args.steps, args.warmup)
     value = (dec_bytes + app_bytes) / sec_per_step / 1e9
@@ -277,10 +298,11 @@ def main():
         "config": {"workload": w.name, "batch": w.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "seq": w.seq + 1, "block": w.block, "mant_bits": w.mant_bits,
                    "layer_caches_in_ring": n_layers, "ring_bytes": n_layers * w.cache_bytes(w.seq + 1),
-                   "step": "quantize_append(1 token/sequence) + decode_attention",
+                   "step": ("quantize_append(1 token/sequence) + decode_attention, two calls" if args.separate_calls else
+                            "append_decode_attention: 1 token/sequence cast and appended, then attention, one call"),
                    "launch": "eager" if args.no_graph else "one captured graph per layer cache, replayed"},
         "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
-        "eager_ms_per_step": eager_sec_per_step * 1e3,
+        "two_calls_eager_ms_per_step": eager_sec_per_step * 1e3,
         "append_us_median": float(np.median(app_us)), "decode_us_median": float(np.median(dec_us)),
         "roofline": roofline,
     }

@@ -182,6 +182,28 @@ int kvbfp_decode_attention_qbfp(const kvbfp_layout* layout, const kvbfp_cache* c
                                 void* out, void* workspace, size_t workspace_bytes,
                                 void* hip_stream);
 
+/* DEVICE, asynchronous.  One decode step in one call: the current token's key and value rows are
+ * cast to BFP and stored (Sec. II-B, Eq. (1), exactly as kvbfp_quantize_append does for one row per
+ * sequence), then attention runs over the cache including that token (Sec. III), exactly as
+ * kvbfp_decode_attention_qbfp does.  Same cache bytes and same output as the two calls one after the
+ * other; where the fast split pass applies the cast happens inside it and a launch is saved.
+ *   k_new, v_new : DEVICE, row of (batch b, kv-head h) at base + b*new_stride_b + h*new_stride_h
+ *                  (strides in elements of `dtype`, >= 0), head_dim contiguous elements, original
+ *                  channel order if perm_k/perm_v are given, cache order if they are NULL.
+ *   seq_len_dev  : DEVICE int32 [batch], cached tokens per sequence INCLUDING the current one
+ *                  (clamped to [0, max_len]); the current token is stored at position seq_len - 1.
+ *                  NULL = max_len for all.  A sequence with seq_len 0 stores nothing and yields zeros.
+ *   perm_k/perm_v: as in kvbfp_decode_attention; the same permutations order the new rows.
+ * Everything else as kvbfp_decode_attention_qbfp (q_mant_bits 0 = query left as it is).
+ * Errors: those of kvbfp_decode_attention_qbfp and kvbfp_quantize_append. */
+int kvbfp_append_decode_attention(const kvbfp_layout* layout, const kvbfp_cache* cache,
+                                  int32_t n_q_heads, const void* k_new, const void* v_new,
+                                  int64_t new_stride_b, int64_t new_stride_h, const void* q,
+                                  kvbfp_dtype dtype, const int32_t* seq_len_dev, int64_t max_len,
+                                  float softmax_scale, const int32_t* perm_k, const int32_t* perm_v,
+                                  int32_t q_mant_bits, void* out, void* workspace,
+                                  size_t workspace_bytes, void* hip_stream);
+
 /* DEVICE, SYNCHRONOUS, for measurement.  Enqueues exactly the launches of
  * kvbfp_decode_attention_qbfp (Sec. III; same arguments, same result in `out`) with HIP events
  * recorded on `hip_stream` before the split pass, between the two passes and after the combine

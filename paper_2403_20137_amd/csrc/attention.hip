@@ -368,7 +368,9 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
                        const void* q, kvbfp_dtype dtype, const int32_t* seq_len_dev,
                        int64_t max_len, float softmax_scale, const int32_t* perm_k,
                        const int32_t* perm_v, int32_t q_mant_bits, void* out, void* workspace,
-                       size_t workspace_bytes, void* hip_stream, float* kernel_ms = nullptr) {
+                       size_t workspace_bytes, void* hip_stream, float* kernel_ms = nullptr,
+                       const void* k_new = nullptr, const void* v_new = nullptr, int64_t new_stride_b = 0,
+                       int64_t new_stride_h = 0) {
     clear_error();
     if (q_mant_bits != 0 && q_mant_bits != 4 && q_mant_bits != 8)
         return fail(KVBFP_ERR_INVALID_ARG, "decode_attention: q_mant_bits = %d (0, 4 or 8)", q_mant_bits);
@@ -413,6 +415,27 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
     auto aligned16 = [](const void* p) { return ((uintptr_t)p & 15u) == 0; };
     const bool fast = a.G <= 8 && dtype != KVBFP_F32 && aligned16(a.k_mant) &&
                       aligned16(a.v_mant) && aligned16(a.k_exp) && aligned16(a.v_exp);
+    // The current token (kvbfp_append_decode_attention): cast inside the LDS split pass, else by the
+    // cache-write kernel ahead of the split pass.  Either way it lands at position seq_len - 1.
+    if (k_new || v_new) {
+        if (!k_new || !v_new) return fail(KVBFP_ERR_INVALID_ARG, "append_decode_attention: k_new and v_new are both needed");
+        if (new_stride_b < 0 || new_stride_h < 0)
+            return fail(KVBFP_ERR_INVALID_ARG, "append_decode_attention: negative stride");
+        // Inside the split pass the cast delays the workgroup that holds the last token by a few
+        // microseconds; that is free only if its split is at least two 256-token tiles shorter than
+        // the others (otherwise the cache-write kernel goes first, as in the two separate calls).
+        const int64_t tiles = (max_len + kTokenTile - 1) / kTokenTile, tiles_per_split = sp.split_len / kTokenTile;
+        const int64_t last_tiles = tiles - (int64_t)(sp.n_splits - 1) * tiles_per_split;
+        const bool in_kernel = fast && L->mant_bits == 4 && (L->block == 16 || L->block == 32) &&
+                               tiles_per_split - last_tiles >= 2;
+        if (in_kernel) {
+            a.k_new = k_new; a.v_new = v_new; a.new_stride_b = new_stride_b; a.new_stride_h = new_stride_h;
+        } else {
+            if (int rc = kvbfp::quantize_append_impl(L, cache, k_new, v_new, dtype, 1, new_stride_b, 0, new_stride_h,
+                                                     max_len - 1, seq_len_dev, -1, max_len, perm_k, perm_v, hip_stream))
+                return rc;
+        }
+    }
     // Optional timing of the two launches (kvbfp_decode_attention_profile): events on the same stream.
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
     if (kernel_ms) {
@@ -464,6 +487,21 @@ int kvbfp_decode_attention_qbfp(const kvbfp_layout* L, const kvbfp_cache* cache,
                                 size_t workspace_bytes, void* hip_stream) {
     return decode_impl(L, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v,
                        q_mant_bits, out, workspace, workspace_bytes, hip_stream);
+}
+
+int kvbfp_append_decode_attention(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t n_q_heads,
+                                  const void* k_new, const void* v_new, int64_t new_stride_b,
+                                  int64_t new_stride_h, const void* q, kvbfp_dtype dtype,
+                                  const int32_t* seq_len_dev, int64_t max_len, float softmax_scale,
+                                  const int32_t* perm_k, const int32_t* perm_v, int32_t q_mant_bits,
+                                  void* out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!k_new || !v_new) {
+        clear_error();
+        return fail(KVBFP_ERR_INVALID_ARG, "append_decode_attention: k_new/v_new is NULL");
+    }
+    return decode_impl(L, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v,
+                       q_mant_bits, out, workspace, workspace_bytes, hip_stream, nullptr, k_new, v_new,
+                       new_stride_b, new_stride_h);
 }
 
 int kvbfp_decode_attention_profile(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t n_q_heads,

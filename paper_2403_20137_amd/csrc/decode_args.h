@@ -21,6 +21,12 @@ struct DecodeArgs {
     float* part_o;            // [B][H_q][n_splits][D]
     int64_t max_seq, max_len, split_len;
     int32_t H_kv, H_q, G, n_splits, log2_block;
+    // Appending the current token inside the split pass (kvbfp_append_decode_attention): the new key
+    // and value row of (batch b, kv-head h) at k_new/v_new + b * new_stride_b + h * new_stride_h
+    // (elements of the call's dtype); nullptr = nothing to append.
+    const void* k_new;
+    const void* v_new;
+    int64_t new_stride_b, new_stride_h;
     int32_t q_mant_bits;      // 0, or the mantissa bits the permuted query is cast to (block = cache block)
     float scale_log2e;
 };

@@ -34,6 +34,7 @@
 #include "decode_args.h"
 #include "decode_dev.h"
 #include "kvbfp_internal.h"
+#include "quantize_dev.h"
 
 namespace {
 
@@ -474,6 +475,31 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
             ml[1] = 0.f;
         }
         return;
+    }
+
+    // ---- kvbfp_append_decode_attention: the current token, position L - 1, is cast and stored by the
+    // workgroup whose split holds that position, before that workgroup requests any cache bytes (its
+    // requests would otherwise pick up what was there before).  Lanes 0-7 of wavefront 0 take the key
+    // row, lanes 8-15 the value row; the rest of the wavefront runs along with zeros (the block maximum
+    // is a cross-lane reduction) and stores nothing.  __syncthreads() also waits for the stores.
+    if (a.k_new != nullptr && L - 1 >= t_begin && L - 1 < t_end) {
+        if (wave == 0) {
+            const int sub = lane & 7, which = (lane >> 3) & 1;
+            const bool live = lane < 16;
+            const void* src = which ? a.v_new : a.k_new;
+            const int32_t* pr = which ? a.perm_v : a.perm_k;
+            const int64_t off = (int64_t)b * a.new_stride_b + (int64_t)kvh * a.new_stride_h;
+            float x[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int c = pr ? (pr[kvh * kD + sub * 16 + i] & (kD - 1)) : (sub * 16 + i);
+                x[i] = live ? load_as_float(src, dt, off + c) : 0.f;
+            }
+            kvbfp::cast::encode_store<4, N>(x, sub, live, const_cast<uint8_t*>(which ? a.v_mant : a.k_mant),
+                                            const_cast<uint8_t*>(which ? a.v_exp : a.k_exp),
+                                            ((int64_t)b * a.H_kv + kvh) * a.max_seq + (L - 1));
+        }
+        __syncthreads();
     }
 
     const int64_t base = ((int64_t)b * a.H_kv + kvh) * a.max_seq + t_begin;

@@ -18,10 +18,10 @@
 #include <cstdint>
 
 #include "kvbfp_internal.h"
+#include "quantize_dev.h"
 
 namespace {
 
-constexpr int kD = 128;           // channels per row (head_dim)
 constexpr int kLanesPerRow = 8;   // 16 channels per lane
 constexpr int kRowsPerStep = 32;  // 256 threads
 constexpr int kSteps = 2;
@@ -55,123 +55,14 @@ struct QuantArgs {
     int64_t stride_b, stride_t, stride_h;   // in elements
     int64_t pos0;
     const int32_t* pos_dev;
+    int64_t pos_bias, pos_cap;               // device positions: min(max(pos_dev[b], 0), pos_cap) + pos_bias
     int64_t max_seq;
     int32_t H, n_new;
     uint32_t n_rows;                         // B * H * n_new, below 2^31
     FastDiv div_n_new, div_H;
 };
 
-template <int CTRL>
-__device__ __forceinline__ uint32_t dpp_mov(uint32_t v) {
-    return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xF, 0xF, false);
-}
-
-// All-reduce maximum over the LPB adjacent lanes that share a block (LPB = block / 16).
-// quad_perm[1,0,3,2], quad_perm[2,3,0,1], row_half_mirror: after the first two steps every quad is
-// uniform, so the mirror (which swaps the two quads of a half row) completes the butterfly.
-template <int LPB>
-__device__ __forceinline__ uint32_t block_allmax(uint32_t a) {
-    if (LPB >= 2) a = max(a, dpp_mov<0xB1>(a));
-    if (LPB >= 4) a = max(a, dpp_mov<0x4E>(a));
-    if (LPB >= 8) a = max(a, dpp_mov<0x141>(a));
-    return a;
-}
-
-__device__ __forceinline__ float widen_bf16(uint32_t h) { return __uint_as_float(h << 16); }
-__device__ __forceinline__ float widen_f16(uint32_t h) {
-    return (float)__builtin_bit_cast(_Float16, (unsigned short)h);
-}
-
-template <int DT>
-struct RawRow { uint4 v[DT == KVBFP_F32 ? 4 : 2]; };   // this lane's 16 inputs as loaded
-
-template <int DT>
-__device__ __forceinline__ void widen16(const RawRow<DT>& raw, float (&x)[16]) {
-    if (DT == KVBFP_F32) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            x[4 * i] = __uint_as_float(raw.v[i].x);
-            x[4 * i + 1] = __uint_as_float(raw.v[i].y);
-            x[4 * i + 2] = __uint_as_float(raw.v[i].z);
-            x[4 * i + 3] = __uint_as_float(raw.v[i].w);
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const uint32_t w[4] = {raw.v[i].x, raw.v[i].y, raw.v[i].z, raw.v[i].w};
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                if (DT == KVBFP_F16) {
-                    x[8 * i + 2 * k] = widen_f16(w[k] & 0xFFFFu);
-                    x[8 * i + 2 * k + 1] = widen_f16(w[k] >> 16);
-                } else {
-                    x[8 * i + 2 * k] = widen_bf16(w[k] & 0xFFFFu);
-                    x[8 * i + 2 * k + 1] = __uint_as_float(w[k] & 0xFFFF0000u);
-                }
-            }
-        }
-    }
-}
-
-// Casts the 16 values of this lane (cache positions c0..c0+15 of one row) and stores them.
-// Every lane of a row group calls this (the DPP steps read neighbours); only `live` rows store.
-template <int P, int N>
-__device__ __forceinline__ void encode_store(const float (&x)[16], int sub, bool live, const QuantTensor& T,
-                                             int64_t crow) {
-    constexpr int LPB = N / 16;
-    constexpr int NB = kD / N;
-    // Largest magnitude of the block, compared on the bit patterns (monotone for finite values).
-    float am = 0.f;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) am = fmaxf(am, fabsf(x[i]));
-    const uint32_t amax = block_allmax<LPB>(__float_as_uint(am));
-
-    // Shared exponent byte: the fp32 exponent field of the maximum, one higher when rounding the
-    // maximum to P-1 magnitude bits would carry (its top P-1 fraction bits are all ones); at least
-    // 1 so that subnormal blocks use the scale of the smallest normal; 0 marks an all-zero block.
-    const uint32_t bumped = (amax + (1u << (24 - P))) >> 23;
-    const uint32_t E = amax == 0 ? 0u : max(bumped, 1u);
-
-    // q[i]: a word whose low P-1 bits are the rounded magnitude; `bias` is what the other bits add
-    // up to once the words are packed at P-bit spacing.
-    constexpr int kPerWord = 32 / P;
-    constexpr uint32_t kOnes = P == 4 ? 0x11111111u : 0x01010101u;
-    uint32_t q[16];
-    uint32_t bias;
-    const uint32_t cfield = E + 25 - P;              // exponent field of 2^(23+e), e = E - 127 - (P-2)
-    if (cfield <= 254) {
-        const float C = __uint_as_float(cfield << 23);
-#pragma unroll
-        for (int i = 0; i < 16; ++i) q[i] = __float_as_uint(fabsf(x[i]) + C);
-        bias = (cfield << 23) * kOnes;
-    } else {                                         // enormous block: scale down first (exact), then round
-        const int e = (int)E - 127 - (P - 2);
-#pragma unroll
-        for (int i = 0; i < 16; ++i) q[i] = __float_as_uint(fabsf(ldexpf(x[i], -e)) + 8388608.0f) & 0xFFu;
-        bias = 0u;
-    }
-
-    uint32_t word[16 / kPerWord];
-#pragma unroll
-    for (int w = 0; w < 16 / kPerWord; ++w) {
-        uint32_t m = 0, sg = 0;
-#pragma unroll
-        for (int k = 0; k < kPerWord; ++k) {
-            const int i = w * kPerWord + k;
-            m += q[i] << (P * k);
-            sg |= (__float_as_uint(x[i]) >> 31) << (P * k + P - 1);
-        }
-        m -= bias;
-        // the sign bit only where the magnitude is non-zero: minus zero is stored as plus zero
-        const uint32_t nz = (m + (P == 4 ? 0x77777777u : 0x7F7F7F7Fu)) & (P == 4 ? 0x88888888u : 0x80808080u);
-        word[w] = m | (sg & nz);
-    }
-
-    if (!live) return;
-    if (P == 4) *(uint2*)(T.mant + crow * 64 + sub * 8) = make_uint2(word[0], word[1]);
-    else *(uint4*)(T.mant + crow * 128 + sub * 16) = make_uint4(word[0], word[1], word[2], word[3]);
-    if ((sub & (LPB - 1)) == 0) T.exp[crow * NB + sub / LPB] = (uint8_t)E;
-}
+using namespace kvbfp::cast;
 
 // One row per 8 lanes, 64 rows per workgroup.  P = mantissa bits, N = block size.
 template <int DT, int P, int N, int MODE>
@@ -200,7 +91,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(QuantArgs a) {
         const uint32_t t = rr - bh * (uint32_t)a.n_new;
         const uint32_t b = fastdiv(bh, a.div_H);
         const uint32_t h = bh - b * (uint32_t)a.H;
-        const int64_t pos = (a.pos_dev ? (int64_t)a.pos_dev[b] : a.pos0) + t;
+        const int64_t pos = (a.pos_dev ? min(max((int64_t)a.pos_dev[b], (int64_t)0), a.pos_cap) + a.pos_bias : a.pos0) + t;
         live[k] = in_range && pos >= 0 && pos < a.max_seq;
         crow[k] = ((int64_t)b * a.H + h) * a.max_seq + pos;
         head[k] = (int32_t)h;
@@ -252,7 +143,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(QuantArgs a) {
                 x[i] = v;
             }
         }
-        encode_store<P, N>(x, sub, live[k], T, crow[k]);
+        encode_store<P, N>(x, sub, live[k], T.mant, T.exp, crow[k]);
     }
 }
 
@@ -390,6 +281,18 @@ int kvbfp_quantize_append(const kvbfp_layout* L, const kvbfp_cache* cache, const
                           int64_t stride_t, int64_t stride_h, int64_t pos0, const int32_t* pos_dev,
                           const int32_t* perm_k, const int32_t* perm_v, void* hip_stream) {
     clear_error();
+    return kvbfp::quantize_append_impl(L, cache, k_new, v_new, dtype, n_new, stride_b, stride_t, stride_h, pos0,
+                                       pos_dev, 0, L ? L->max_seq : 0, perm_k, perm_v, hip_stream);
+}
+
+}  // extern "C"
+
+// pos_dev given: row i of sequence b goes to min(max(pos_dev[b], 0), pos_cap) + pos_bias + i.
+int kvbfp::quantize_append_impl(const kvbfp_layout* L, const kvbfp_cache* cache, const void* k_new,
+                                const void* v_new, kvbfp_dtype dtype, int32_t n_new, int64_t stride_b,
+                                int64_t stride_t, int64_t stride_h, int64_t pos0, const int32_t* pos_dev,
+                                int64_t pos_bias, int64_t pos_cap, const int32_t* perm_k,
+                                const int32_t* perm_v, void* hip_stream) {
     if (int rc = check_device_layout(L)) return rc;
     if (int rc = check_cache(cache, k_new != nullptr, v_new != nullptr)) return rc;
     const int esz = dtype_size(dtype);
@@ -407,7 +310,7 @@ int kvbfp_quantize_append(const kvbfp_layout* L, const kvbfp_cache* cache, const
     if (k_new) a.t[nt++] = QuantTensor{k_new, perm_k, cache->k_mant, cache->k_exp};
     if (v_new) a.t[nt++] = QuantTensor{v_new, perm_v, cache->v_mant, cache->v_exp};
     a.stride_b = stride_b; a.stride_t = stride_t; a.stride_h = stride_h;
-    a.pos0 = pos0; a.pos_dev = pos_dev; a.max_seq = L->max_seq;
+    a.pos0 = pos0; a.pos_dev = pos_dev; a.pos_bias = pos_bias; a.pos_cap = pos_cap; a.max_seq = L->max_seq;
     a.H = L->n_kv_heads; a.n_new = n_new;
     const int64_t n_rows = (int64_t)L->batch * L->n_kv_heads * n_new;
     if (n_rows > 0x7FFFFFFF) return fail(KVBFP_ERR_UNSUPPORTED, "quantize_append: too many rows");
@@ -433,6 +336,8 @@ int kvbfp_quantize_append(const kvbfp_layout* L, const kvbfp_cache* cache, const
     if (err != hipSuccess) return fail(KVBFP_ERR_HIP, "quantize_append: %s", hipGetErrorString(err));
     return KVBFP_OK;
 }
+
+extern "C" {
 
 int kvbfp_dequantize(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t which, int64_t t0,
                      int64_t n_tok, const int32_t* perm, void* out, kvbfp_dtype dtype,

@@ -23,7 +23,7 @@ _NP_DT = {np.dtype(np.float32): F32, np.dtype(np.float16): F16}
 
 EXPORTS = ["kvbfp_cache_bytes", "kvbfp_calibrate_perm", "kvbfp_permute_weights",
            "kvbfp_quantize_append", "kvbfp_dequantize", "kvbfp_decode_workspace_bytes",
-           "kvbfp_decode_attention", "kvbfp_decode_attention_qbfp", "kvbfp_decode_attention_profile",
+           "kvbfp_decode_attention", "kvbfp_decode_attention_qbfp", "kvbfp_append_decode_attention", "kvbfp_decode_attention_profile",
            "kvbfp_last_error", "kvbfp_version"]
 
 
@@ -76,6 +76,10 @@ def lib():
                                                   C.c_int, C.c_void_p, C.c_int64, C.c_float, C.c_void_p,
                                                   C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t,
                                                   C.c_void_p]
+        l.kvbfp_append_decode_attention.argtypes = [C.POINTER(Layout), C.POINTER(CachePtrs), C.c_int32, C.c_void_p,
+                                                    C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int,
+                                                    C.c_void_p, C.c_int64, C.c_float, C.c_void_p, C.c_void_p,
+                                                    C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         l.kvbfp_decode_attention_profile.argtypes = l.kvbfp_decode_attention_qbfp.argtypes + [C.POINTER(C.c_float)]
         _lib = l
     return _lib
@@ -299,3 +303,25 @@ def decode_attention_profile(cache: Cache, q, max_len, softmax_scale, q_mant_bit
                                                 int(q_mant_bits), _dev_ptr(out), _dev_ptr(workspace),
                                                 workspace.numel(), _stream_ptr(stream), ms))
     return out, float(ms[0]), float(ms[1])
+
+
+def append_decode_attention(cache: Cache, k_new, v_new, q, max_len, softmax_scale, seq_len_dev=None, perm_k=None,
+                            perm_v=None, q_mant_bits=0, out=None, workspace=None, stream=None):
+    """DEVICE, async.  k_new / v_new: [batch][1][n_kv_heads][head_dim] (or [batch][n_kv_heads][head_dim]), the
+    current token; stored at position seq_len - 1 (max_len - 1 without seq_len_dev), then attention."""
+    L, n_q_heads, out, workspace = _decode_common(cache, q, max_len, out, workspace)
+    if k_new.dim() == 4:
+        k_new, v_new = k_new[:, 0], v_new[:, 0]
+    if k_new.dim() != 3 or k_new.stride(2) != 1 or k_new.shape != v_new.shape or k_new.stride() != v_new.stride() \
+            or k_new.dtype != q.dtype or v_new.dtype != q.dtype:
+        raise ValueError("k_new/v_new must be [batch][n_kv_heads][head_dim], channel-contiguous, same strides, q's dtype")
+    if k_new.shape != (L.batch, L.n_kv_heads, L.head_dim):
+        raise ValueError("k_new/v_new shape does not match the layout")
+    ptrs = cache.ptrs
+    _check(lib().kvbfp_append_decode_attention(C.byref(L), C.byref(ptrs), n_q_heads, _dev_ptr(k_new), _dev_ptr(v_new),
+                                               k_new.stride(0), k_new.stride(1), _dev_ptr(q), _TORCH_DT[q.dtype],
+                                               _dev_ptr(seq_len_dev, torch.int32), int(max_len), float(softmax_scale),
+                                               _dev_ptr(perm_k, torch.int32), _dev_ptr(perm_v, torch.int32),
+                                               int(q_mant_bits), _dev_ptr(out), _dev_ptr(workspace), workspace.numel(),
+                                               _stream_ptr(stream)))
+    return out

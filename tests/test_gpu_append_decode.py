@@ -1,0 +1,104 @@
+"""kvbfp_append_decode_attention = kvbfp_quantize_append of the current token + kvbfp_decode_attention:
+same cache bytes, same output bits, whether the cast happens inside the split pass or ahead of it."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2403_20137_amd import kvbfp, synth
+from util import dev_i32
+
+pytestmark = pytest.mark.gpu
+D = 128
+DT = {torch.float32: "f32", torch.float16: "f16", torch.bfloat16: "bf16"}
+
+
+def _case(dtype, n, p, G, lens, S_max, use_perm, seed, qbits=0, Hkv=2):
+    B = len(lens)
+    S = max(max(lens), 1)
+    gains = synth.outlier_gains(seed, 0, Hkv, D)
+    k = synth.kv_rows(B, S, Hkv, D, DT[dtype], gains, seed, 2, "cuda")
+    v = synth.kv_rows(B, S, Hkv, D, DT[dtype], gains, seed, 3, "cuda")
+    q = synth.queries(B, Hkv * G, D, DT[dtype], seed, 4, "cuda")
+    pk = pv = None
+    if use_perm:
+        g = torch.Generator().manual_seed(seed)
+        pk = torch.stack([torch.randperm(D, generator=g) for _ in range(Hkv)]).to(torch.int32).cuda()
+        pv = torch.stack([torch.randperm(D, generator=g) for _ in range(Hkv)]).to(torch.int32).cuda()
+    layout = kvbfp.make_layout(D, n, p, Hkv, B, S_max)
+    lens_t = dev_i32(np.asarray(lens))
+    # the current token of sequence b is row lens[b] - 1 of k / v
+    idx = torch.tensor([max(l - 1, 0) for l in lens], device="cuda")
+    k_new = k[torch.arange(B, device="cuda"), idx].contiguous()      # [B][Hkv][D]
+    v_new = v[torch.arange(B, device="cuda"), idx].contiguous()
+    caches = []
+    for _ in range(2):
+        c = kvbfp.alloc_cache(layout, "cuda", fill=0xAB)
+        kvbfp.quantize_append(c, k, v, perm_k=pk, perm_v=pv)             # history (the current token's slot too,
+        caches.append(c)                                                  # overwritten below by both variants)
+        for plane in (c.k_mant, c.k_exp, c.v_mant, c.v_exp):             # make the slot differ from the result
+            for b, l in enumerate(lens):
+                if l > 0:
+                    plane[b, :, l - 1] = 0x5A
+    a, f = caches
+    scale = 0.1
+    kvbfp.quantize_append(a, k_new.unsqueeze(1), v_new.unsqueeze(1), pos_dev=lens_t - 1, perm_k=pk, perm_v=pv)
+    if qbits:
+        want = kvbfp.decode_attention_qbfp(a, q, max(lens), scale, qbits, seq_len_dev=lens_t, perm_k=pk, perm_v=pv)
+    else:
+        want = kvbfp.decode_attention(a, q, max(lens), scale, seq_len_dev=lens_t, perm_k=pk, perm_v=pv)
+    got = kvbfp.append_decode_attention(f, k_new, v_new, q, max(lens), scale, seq_len_dev=lens_t, perm_k=pk, perm_v=pv,
+                                        q_mant_bits=qbits)
+    torch.cuda.synchronize()
+    for name in ("k_mant", "k_exp", "v_mant", "v_exp"):
+        assert torch.equal(getattr(a, name), getattr(f, name)), name
+    assert torch.equal(got, want)
+
+
+@pytest.mark.parametrize("n", [16, 32])
+@pytest.mark.parametrize("G", [1, 4, 8])
+@pytest.mark.parametrize("use_perm", [False, True])
+def test_small_caches_equal_two_calls(n, G, use_perm):
+    # lengths: full tiles + 1, mid-tile, a single token, an empty sequence
+    _case(torch.bfloat16, n, 4, G, [1025, 700, 1, 0], 1100, use_perm, seed=30 + n + G)
+
+
+@pytest.mark.parametrize("n", [16, 32])
+@pytest.mark.parametrize("G,use_perm,qbits", [(1, False, 0), (2, True, 0), (2, True, 8)])
+def test_cast_inside_the_split_pass_equals_two_calls(n, G, use_perm, qbits):
+    # The cast moves into the split pass when the split that holds the last token is at least two
+    # 256-token tiles shorter than the others.  4 x 64 = 256 (batch, kv-head) units ask for 3 splits;
+    # 7 tiles then split 3 + 3 + 1.  The current tokens fall into the last, the first and the middle
+    # split, and one sequence is empty.
+    _case(torch.bfloat16, n, 4, G, [1792, 700, 1300, 0], 1792, use_perm, seed=60 + n + G, qbits=qbits, Hkv=64)
+
+
+def test_cast_inside_the_split_pass_fp16():
+    _case(torch.float16, 32, 4, 1, [1700, 1792, 1537, 1], 1792, True, seed=77, Hkv=64)
+
+
+@pytest.mark.parametrize("dtype,n,p", [(torch.bfloat16, 16, 8), (torch.bfloat16, 64, 4), (torch.float32, 32, 4),
+                                       (torch.float16, 128, 8)])
+def test_append_ahead_of_the_split_pass_equals_two_calls(dtype, n, p):
+    _case(dtype, n, p, 2, [600, 259, 0], 640, True, seed=50 + n + p)
+
+
+def test_without_sequence_lengths_the_token_goes_to_the_last_position():
+    B, Hkv, G, S = 2, 2, 4, 515
+    gains = synth.outlier_gains(3, 0, Hkv, D)
+    k = synth.kv_rows(B, S, Hkv, D, "bf16", gains, 3, 2, "cuda")
+    v = synth.kv_rows(B, S, Hkv, D, "bf16", gains, 3, 3, "cuda")
+    q = synth.queries(B, Hkv * G, D, "bf16", 3, 4, "cuda")
+    layout = kvbfp.make_layout(D, 32, 4, Hkv, B, S)
+    a, f = kvbfp.alloc_cache(layout, "cuda", fill=0), kvbfp.alloc_cache(layout, "cuda", fill=0)
+    kvbfp.quantize_append(a, k, v)
+    kvbfp.quantize_append(f, k[:, :-1], v[:, :-1])
+    want = kvbfp.decode_attention(a, q, S, 0.1)
+    got = kvbfp.append_decode_attention(f, k[:, -1:], v[:, -1:], q, S, 0.1)
+    torch.cuda.synchronize()
+    assert torch.equal(a.k_mant, f.k_mant) and torch.equal(a.v_exp, f.v_exp) and torch.equal(got, want)
+
+
+def test_headline_configuration_in_the_launch_shape_of_the_benchmark():
+    # 8 sequences x 8 kv-heads x 32769 tokens, 4 query heads per kv-head, block 32: 12 splits of 11 tiles,
+    # the last one 8 tiles long -> the cast runs inside the split pass
+    _case(torch.bfloat16, 32, 4, 4, [32769, 32769, 32700, 32769, 30000, 32769, 32769, 28161], 32769, True, seed=99, Hkv=8)
