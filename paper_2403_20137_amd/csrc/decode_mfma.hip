@@ -897,20 +897,12 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
     }
 }
 
-// Which split pass serves blocks of 16 and 32: the LDS-staged pipeline or the register-staged one.
-constexpr bool kUseLdsPipeline = true;
-
+// Blocks of 16 and 32 go through the LDS pipeline, blocks of 64 and 128 through the register-staged pass.
 template <int HG>
 hipError_t launch_n(const DecodeArgs& a, int dt, int block, dim3 grid, hipStream_t s) {
     switch (block) {
-        case 16:
-            if (kUseLdsPipeline) decode_split_lds_p4<16, HG><<<grid, 256, 0, s>>>(a, dt);
-            else decode_split_mfma_p4<16, HG><<<grid, 256, 0, s>>>(a, dt);
-            break;
-        case 32:
-            if (kUseLdsPipeline) decode_split_lds_p4<32, HG><<<grid, 256, 0, s>>>(a, dt);
-            else decode_split_mfma_p4<32, HG><<<grid, 256, 0, s>>>(a, dt);
-            break;
+        case 16: decode_split_lds_p4<16, HG><<<grid, 256, 0, s>>>(a, dt); break;
+        case 32: decode_split_lds_p4<32, HG><<<grid, 256, 0, s>>>(a, dt); break;
         case 64: decode_split_mfma_p4<64, HG><<<grid, 256, 0, s>>>(a, dt); break;
         default: decode_split_mfma_p4<128, HG><<<grid, 256, 0, s>>>(a, dt); break;
     }
