@@ -432,7 +432,7 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
             a.k_new = k_new; a.v_new = v_new; a.new_stride_b = new_stride_b; a.new_stride_h = new_stride_h;
         } else {
             if (int rc = kvbfp::quantize_append_impl(L, cache, k_new, v_new, dtype, 1, new_stride_b, 0, new_stride_h,
-                                                     max_len - 1, seq_len_dev, -1, max_len, perm_k, perm_v, hip_stream))
+                                                     max_len - 1, seq_len_dev, max_len, perm_k, perm_v, hip_stream))
                 return rc;
         }
     }

@@ -34,12 +34,11 @@ struct SplitPlan {
 constexpr int kTokenTile = 256;
 SplitPlan plan_splits(const kvbfp_layout* L, int32_t n_q_heads, int64_t max_len);
 
-// kvbfp_quantize_append with the device positions biased and capped (see quantize.hip); does not clear
-// the error state.
+// kvbfp_quantize_append, optionally with sequence lengths in place of positions (len_cap >= 0, see
+// quantize.hip); does not clear the error state.
 int quantize_append_impl(const kvbfp_layout* L, const kvbfp_cache* cache, const void* k_new,
                          const void* v_new, kvbfp_dtype dtype, int32_t n_new, int64_t stride_b,
                          int64_t stride_t, int64_t stride_h, int64_t pos0, const int32_t* pos_dev,
-                         int64_t pos_bias, int64_t pos_cap, const int32_t* perm_k,
-                         const int32_t* perm_v, void* hip_stream);
+                         int64_t len_cap, const int32_t* perm_k, const int32_t* perm_v, void* hip_stream);
 
 }  // namespace kvbfp

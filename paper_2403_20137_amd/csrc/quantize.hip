@@ -55,7 +55,7 @@ struct QuantArgs {
     int64_t stride_b, stride_t, stride_h;   // in elements
     int64_t pos0;
     const int32_t* pos_dev;
-    int64_t pos_bias, pos_cap;               // device positions: min(max(pos_dev[b], 0), pos_cap) + pos_bias
+    int64_t len_cap;                         // >= 0: pos_dev holds sequence lengths, the row goes to min(max(len, 0), len_cap) - 1
     int64_t max_seq;
     int32_t H, n_new;
     uint32_t n_rows;                         // B * H * n_new, below 2^31
@@ -91,7 +91,9 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(QuantArgs a) {
         const uint32_t t = rr - bh * (uint32_t)a.n_new;
         const uint32_t b = fastdiv(bh, a.div_H);
         const uint32_t h = bh - b * (uint32_t)a.H;
-        const int64_t pos = (a.pos_dev ? min(max((int64_t)a.pos_dev[b], (int64_t)0), a.pos_cap) + a.pos_bias : a.pos0) + t;
+        int64_t pos = a.pos0;
+        if (a.pos_dev) pos = a.len_cap >= 0 ? min(max((int64_t)a.pos_dev[b], (int64_t)0), a.len_cap) - 1 : (int64_t)a.pos_dev[b];
+        pos += t;
         live[k] = in_range && pos >= 0 && pos < a.max_seq;
         crow[k] = ((int64_t)b * a.H + h) * a.max_seq + pos;
         head[k] = (int32_t)h;
@@ -282,17 +284,18 @@ int kvbfp_quantize_append(const kvbfp_layout* L, const kvbfp_cache* cache, const
                           const int32_t* perm_k, const int32_t* perm_v, void* hip_stream) {
     clear_error();
     return kvbfp::quantize_append_impl(L, cache, k_new, v_new, dtype, n_new, stride_b, stride_t, stride_h, pos0,
-                                       pos_dev, 0, L ? L->max_seq : 0, perm_k, perm_v, hip_stream);
+                                       pos_dev, -1, perm_k, perm_v, hip_stream);
 }
 
 }  // extern "C"
 
-// pos_dev given: row i of sequence b goes to min(max(pos_dev[b], 0), pos_cap) + pos_bias + i.
+// len_cap >= 0: pos_dev holds sequence lengths (clamped to [0, len_cap]) and row i of sequence b goes
+// to position length - 1 + i; len_cap < 0: pos_dev holds positions, as in the public call.
 int kvbfp::quantize_append_impl(const kvbfp_layout* L, const kvbfp_cache* cache, const void* k_new,
                                 const void* v_new, kvbfp_dtype dtype, int32_t n_new, int64_t stride_b,
                                 int64_t stride_t, int64_t stride_h, int64_t pos0, const int32_t* pos_dev,
-                                int64_t pos_bias, int64_t pos_cap, const int32_t* perm_k,
-                                const int32_t* perm_v, void* hip_stream) {
+                                int64_t len_cap, const int32_t* perm_k, const int32_t* perm_v,
+                                void* hip_stream) {
     if (int rc = check_device_layout(L)) return rc;
     if (int rc = check_cache(cache, k_new != nullptr, v_new != nullptr)) return rc;
     const int esz = dtype_size(dtype);
@@ -310,7 +313,7 @@ int kvbfp::quantize_append_impl(const kvbfp_layout* L, const kvbfp_cache* cache,
     if (k_new) a.t[nt++] = QuantTensor{k_new, perm_k, cache->k_mant, cache->k_exp};
     if (v_new) a.t[nt++] = QuantTensor{v_new, perm_v, cache->v_mant, cache->v_exp};
     a.stride_b = stride_b; a.stride_t = stride_t; a.stride_h = stride_h;
-    a.pos0 = pos0; a.pos_dev = pos_dev; a.pos_bias = pos_bias; a.pos_cap = pos_cap; a.max_seq = L->max_seq;
+    a.pos0 = pos0; a.pos_dev = pos_dev; a.len_cap = len_cap; a.max_seq = L->max_seq;
     a.H = L->n_kv_heads; a.n_new = n_new;
     const int64_t n_rows = (int64_t)L->batch * L->n_kv_heads * n_new;
     if (n_rows > 0x7FFFFFFF) return fail(KVBFP_ERR_UNSUPPORTED, "quantize_append: too many rows");
