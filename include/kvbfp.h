@@ -204,6 +204,25 @@ int kvbfp_append_decode_attention(const kvbfp_layout* layout, const kvbfp_cache*
                                   int32_t q_mant_bits, void* out, void* workspace,
                                   size_t workspace_bytes, void* hip_stream);
 
+/* DEVICE, asynchronous.  Attention for the last n_q_tokens tokens of every sequence at once
+ * (verification of speculated tokens, a chunk of a prompt): the same products as in
+ * kvbfp_decode_attention_qbfp (Sec. III), every cached row still read once.  The tokens are already in
+ * the cache; query token i (0-based) of a sequence with seq_len cached tokens attends to the first
+ * seq_len - (n_q_tokens - 1 - i) of them (causal order among the new tokens); a query token that
+ * sees no cached token yields zeros.
+ *   q, out      : DEVICE [batch][n_q_tokens][n_q_heads][head_dim] of `dtype`, contiguous.
+ *   workspace   : at least kvbfp_decode_workspace_bytes(layout, n_q_heads * n_q_tokens, max_len) bytes.
+ *   n_q_tokens  : 1..64.  The matrix-core passes take n_q_tokens * (n_q_heads / n_kv_heads) <= 8
+ *                 (their spare rows hold the extra tokens, so the cost is that of one token); more
+ *                 go through the general pass.
+ * Everything else as kvbfp_decode_attention_qbfp.  n_q_tokens = 1 is that call. */
+int kvbfp_decode_attention_multi(const kvbfp_layout* layout, const kvbfp_cache* cache,
+                                 int32_t n_q_heads, int32_t n_q_tokens, const void* q,
+                                 kvbfp_dtype dtype, const int32_t* seq_len_dev, int64_t max_len,
+                                 float softmax_scale, const int32_t* perm_k, const int32_t* perm_v,
+                                 int32_t q_mant_bits, void* out, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream);
+
 /* DEVICE, SYNCHRONOUS, for measurement.  Enqueues exactly the launches of
  * kvbfp_decode_attention_qbfp (Sec. III; same arguments, same result in `out`) with HIP events
  * recorded on `hip_stream` before the split pass, between the two passes and after the combine

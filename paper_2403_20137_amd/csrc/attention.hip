@@ -100,7 +100,7 @@ __global__ __launch_bounds__(kTile) void decode_split_generic(DecodeArgs a, int 
         float v = 0.f;
         if (g < n_act) {
             const int c = a.perm_k ? a.perm_k[kvh * kD + j] : j;
-            v = load_as_float(a.q, dt, ((int64_t)b * a.H_q + h0 + g) * kD + c);
+            v = load_as_float(a.q, dt, kvbfp::query_row(a, b, kvh, g0 + g) * kD + c);
         }
         qs[g][j] = a.q_mant_bits ? v : v * a.scale_log2e;
     }
@@ -161,7 +161,8 @@ __global__ __launch_bounds__(kTile) void decode_split_generic(DecodeArgs a, int 
             }
         }
 #pragma unroll
-        for (int g = 0; g < kHeadsPerWg; ++g) sc[g][tid] = s[g];
+        for (int g = 0; g < kHeadsPerWg; ++g)        // several query tokens: head slot g0+g does not see the last few tokens
+            sc[g][tid] = t < L - kvbfp::hidden_tokens(a, g0 + g) ? s[g] : -INFINITY;
         __syncthreads();
 
         // ---- online softmax: wave g updates head g
@@ -174,17 +175,18 @@ __global__ __launch_bounds__(kTile) void decode_split_generic(DecodeArgs a, int 
                 sv[k] = sc[g][lane + 64 * k];
                 tmax = fmaxf(tmax, sv[k]);
             }
-            tmax = wave_max(tmax);                  // finite: every tile holds a cached token
+            tmax = wave_max(tmax);                  // -inf only if this head sees none of the tile (several query tokens)
             const float m_new = fmaxf(m_run, tmax);
+            const float m_ref = m_new == -INFINITY ? 0.f : m_new;
             float tsum = 0.f;
 #pragma unroll
             for (int k = 0; k < kTile / 64; ++k) {
-                const float pw = exp2f(sv[k] - m_new);   // 2^-inf = 0 for padding
+                const float pw = exp2f(sv[k] - m_ref);   // 2^-inf = 0 for padding
                 sc[g][lane + 64 * k] = pw;
                 tsum += pw;
             }
             tsum = wave_sum(tsum);
-            const float al = exp2f(m_run - m_new);       // 0 on the first tile
+            const float al = exp2f(m_run - m_ref);       // 0 on the first tile
             l_run = l_run * al + tsum;
             m_run = m_new;
             if (lane == 0) alpha_s[g] = al;
@@ -335,7 +337,7 @@ __global__ __launch_bounds__(kD * kCombineSlices) void decode_combine(DecodeArgs
     const float r = den > 0.f ? num / den : 0.f;
     const int kvh = h / a.G;
     const int c = a.perm_v ? a.perm_v[kvh * kD + j] : j;
-    const int64_t oi = bh * kD + c;
+    const int64_t oi = kvbfp::query_row(a, b, kvh, h % a.G) * kD + c;
     if (dt == KVBFP_F32) ((float*)a.out)[oi] = r;
     else if (dt == KVBFP_F16) ((uint16_t*)a.out)[oi] = __builtin_bit_cast(unsigned short, (_Float16)r);
     else ((uint16_t*)a.out)[oi] = narrow_bf16(r);
@@ -370,8 +372,10 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
                        const int32_t* perm_v, int32_t q_mant_bits, void* out, void* workspace,
                        size_t workspace_bytes, void* hip_stream, float* kernel_ms = nullptr,
                        const void* k_new = nullptr, const void* v_new = nullptr, int64_t new_stride_b = 0,
-                       int64_t new_stride_h = 0) {
+                       int64_t new_stride_h = 0, int32_t n_q_tokens = 1) {
     clear_error();
+    if (n_q_tokens < 1 || n_q_tokens > 64)
+        return fail(KVBFP_ERR_INVALID_ARG, "decode_attention: n_q_tokens = %d (1..64)", n_q_tokens);
     if (q_mant_bits != 0 && q_mant_bits != 4 && q_mant_bits != 8)
         return fail(KVBFP_ERR_INVALID_ARG, "decode_attention: q_mant_bits = %d (0, 4 or 8)", q_mant_bits);
     if (int rc = check_device_layout(L)) return rc;
@@ -386,6 +390,9 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
                     (long long)max_len, (long long)L->max_seq);
     if (!std::isfinite(softmax_scale))
         return fail(KVBFP_ERR_INVALID_ARG, "decode_attention: softmax_scale is not finite");
+    // from here on "heads" are virtual heads: every query token brings its own set (see DecodeArgs)
+    const int32_t real_heads = n_q_heads;
+    n_q_heads *= n_q_tokens;
     const size_t need = kvbfp_decode_workspace_bytes(L, n_q_heads, max_len);
     if (!workspace || workspace_bytes < need)
         return fail(KVBFP_ERR_WORKSPACE, "decode_attention: workspace of %zu bytes needed, %zu given", need,
@@ -404,6 +411,7 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
     a.max_seq = L->max_seq; a.max_len = max_len; a.split_len = sp.split_len;
     a.H_kv = L->n_kv_heads; a.H_q = n_q_heads; a.G = n_q_heads / L->n_kv_heads;
     a.n_splits = sp.n_splits; a.log2_block = log2_exact(L->block);
+    a.n_q_tokens = n_q_tokens; a.real_Hq = real_heads; a.real_G = real_heads / L->n_kv_heads;
     a.q_mant_bits = q_mant_bits;
     a.scale_log2e = softmax_scale * 1.4426950408889634f;
 
@@ -419,6 +427,7 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
     // cache-write kernel ahead of the split pass.  Either way it lands at position seq_len - 1.
     if (k_new || v_new) {
         if (!k_new || !v_new) return fail(KVBFP_ERR_INVALID_ARG, "append_decode_attention: k_new and v_new are both needed");
+        if (n_q_tokens != 1) return fail(KVBFP_ERR_UNSUPPORTED, "append_decode_attention: one query token only");
         if (new_stride_b < 0 || new_stride_h < 0)
             return fail(KVBFP_ERR_INVALID_ARG, "append_decode_attention: negative stride");
         // Inside the split pass the cast delays the workgroup that holds the last token by a few
@@ -502,6 +511,16 @@ int kvbfp_append_decode_attention(const kvbfp_layout* L, const kvbfp_cache* cach
     return decode_impl(L, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v,
                        q_mant_bits, out, workspace, workspace_bytes, hip_stream, nullptr, k_new, v_new,
                        new_stride_b, new_stride_h);
+}
+
+int kvbfp_decode_attention_multi(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t n_q_heads,
+                                 int32_t n_q_tokens, const void* q, kvbfp_dtype dtype,
+                                 const int32_t* seq_len_dev, int64_t max_len, float softmax_scale,
+                                 const int32_t* perm_k, const int32_t* perm_v, int32_t q_mant_bits, void* out,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return decode_impl(L, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v,
+                       q_mant_bits, out, workspace, workspace_bytes, hip_stream, nullptr, nullptr, nullptr, 0, 0,
+                       n_q_tokens);
 }
 
 int kvbfp_decode_attention_profile(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t n_q_heads,

@@ -20,7 +20,12 @@ struct DecodeArgs {
     float* part_ml;           // [B][H_q][n_splits][2]  (m in base-2 units, l)
     float* part_o;            // [B][H_q][n_splits][D]
     int64_t max_seq, max_len, split_len;
+    // With several query tokens per sequence (kvbfp_decode_attention_multi) the kernels see "virtual
+    // heads": H_q = n_q_tokens * real_Hq per batch and G = n_q_tokens * real_G per kv-head; virtual head
+    // s of a kv-head is query token s / real_G, real head kvh * real_G + s % real_G, and may attend
+    // to n_q_tokens - 1 - s / real_G tokens fewer than the sequence holds (causal order of the new tokens).
     int32_t H_kv, H_q, G, n_splits, log2_block;
+    int32_t n_q_tokens, real_Hq, real_G;
     // Appending the current token inside the split pass (kvbfp_append_decode_attention): the new key
     // and value row of (batch b, kv-head h) at k_new/v_new + b * new_stride_b + h * new_stride_h
     // (elements of the call's dtype); nullptr = nothing to append.
@@ -30,6 +35,16 @@ struct DecodeArgs {
     int32_t q_mant_bits;      // 0, or the mantissa bits the permuted query is cast to (block = cache block)
     float scale_log2e;
 };
+
+// Row of q / out, in units of head_dim elements, of virtual head s of kv-head kvh in batch b.
+__host__ __device__ inline int64_t query_row(const DecodeArgs& a, int b, int kvh, int s) {
+    return ((int64_t)b * a.n_q_tokens + s / a.real_G) * a.real_Hq + (int64_t)kvh * a.real_G + s % a.real_G;
+}
+// Tokens at the end of the sequence that virtual head s must not see.
+__host__ __device__ inline int hidden_tokens(const DecodeArgs& a, int s) {
+    const int o = a.n_q_tokens - 1 - s / a.real_G;
+    return o > 0 ? o : 0;
+}
 
 // Fast split pass for 4-bit mantissas and 16-bit I/O (decode_mfma.hip).  Returns hipSuccess after
 // enqueuing; the caller has already validated the arguments.  group size G <= 8.

@@ -107,7 +107,7 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
             float v = 0.f;
             if (g < a.G) {
                 const int src = a.perm_k ? a.perm_k[kvh * kD + c] : c;
-                v = load_as_float(a.q, dt, ((int64_t)b * a.H_q + h0 + g) * kD + src);
+                v = load_as_float(a.q, dt, kvbfp::query_row(a, b, kvh, g) * kD + src);
             }
             q_s[g][c] = a.q_mant_bits ? v : v * factor;
         }
@@ -154,6 +154,13 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
     const uint8_t* __restrict__ k_exp = a.k_exp + base * NB;
     const uint8_t* __restrict__ v_exp = a.v_exp + base * NB;
     const int n_tok = (int)(t_end - t_begin);       // tokens of this split, <= split_len
+    // several query tokens: head slot s sees tokens below lim[.] only (split-relative), and a tile counts
+    // as full only if every head sees all of it
+    const int n_vis = (int)(L - t_begin);
+    const int n_full = min(n_tok, n_vis - (a.n_q_tokens - 1));
+    int lim[HG];
+#pragma unroll
+    for (int hg = 0; hg < HG; ++hg) lim[hg] = n_vis - kvbfp::hidden_tokens(a, hg * 4 + kg);
 
     float m_run[HG], l_run[HG];
     f32x4 o_acc[HG][4];
@@ -224,16 +231,17 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const float v = s_acc[hg][u][0] + s_acc[hg][u][1] + s_acc[hg][u][2];   // the three limbs
-                s[u] = (FULL || 16 * u + j < left) ? v : -INFINITY;
+                s[u] = (FULL || 16 * u + j < min(left, lim[hg] - T0)) ? v : -INFINITY;
                 tmax = fmaxf(tmax, s[u]);
             }
-            tmax = row_max(tmax);                                   // finite: the tile holds a cached token
+            tmax = row_max(tmax);           // -inf only if this head sees none of the tile (several query tokens)
             const float m_new = fmaxf(m_run[hg], tmax);
-            const float alpha = exp2f(m_run[hg] - m_new);           // 0 on the first tile, 1 when the maximum stays
+            const float m_ref = m_new == -INFINITY ? 0.f : m_new;   // keeps the differences below well defined
+            const float alpha = exp2f(m_run[hg] - m_ref);           // 0 on the first tile, 1 when the maximum stays
             float psum = 0.f;
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const float pw = exp2f(s[u] - m_new);
+                const float pw = exp2f(s[u] - m_ref);
                 const __bf16 ph = (__bf16)pw;
                 const __bf16 pl = (__bf16)(pw - (float)ph);
                 psum += (float)ph + (float)pl;
@@ -299,7 +307,7 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
 
     {
         int T0 = wave * kSuper;
-        for (; T0 + kSuper <= n_tok; T0 += kWaves * kSuper) tile(T0, std::true_type{});
+        for (; T0 + kSuper <= n_full; T0 += kWaves * kSuper) tile(T0, std::true_type{});
         if (T0 < n_tok) tile(T0, std::false_type{});     // at most one ragged tile per wavefront
     }
 
@@ -508,6 +516,10 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
     const uint8_t* __restrict__ k_exp = a.k_exp + base * NB;
     const uint8_t* __restrict__ v_exp = a.v_exp + base * NB;
     const int n_tok = (int)(t_end - t_begin);
+    // several query tokens: head slot s sees tokens below lim[.] only (split-relative)
+    int lim[HG];
+#pragma unroll
+    for (int hg = 0; hg < HG; ++hg) lim[hg] = (int)(L - t_begin) - kvbfp::hidden_tokens(a, hg * 4 + (lane >> 4));
 
     uint8_t* const wbase = smem + wave * kWaveBytes;
 
@@ -572,7 +584,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
 #pragma unroll
     for (int k = 0; k < kQPerThread; ++k) {
         const int i = tid + 256 * k, g = i / kD, c = i % kD;
-        const int64_t idx = ((int64_t)b * a.H_q + h0 + min(g, a.G - 1)) * kD + c;      // clamped: rows beyond G are zeroed below
+        const int64_t idx = kvbfp::query_row(a, b, kvh, min(g, a.G - 1)) * kD + c;     // clamped: rows beyond G are zeroed below
         q_bits[k] = dt == KVBFP_F32 ? ((const uint32_t*)a.q)[idx] : (uint32_t)((const uint16_t*)a.q)[idx];
     }
     int perm_c = 0;
@@ -780,16 +792,17 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const float v = (s_acc[hg][u][0] + s_acc[hg][u][1]) + (s_acc[hg][u][2] + s_acc[hg][u][3]);   // the limb rows
-                    s[u] = (16 * u + j < left) ? v : -INFINITY;
+                    s[u] = (16 * u + j < min(left, lim[hg] - T0)) ? v : -INFINITY;
                     tmax = fmaxf(tmax, s[u]);
                 }
-                tmax = row_max(tmax);
+                tmax = row_max(tmax);       // -inf only if this head sees none of the tile (several query tokens)
                 const float m_new = fmaxf(m_run[hg], tmax);
-                const float alpha = exp2f(m_run[hg] - m_new);
+                const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+                const float alpha = exp2f(m_run[hg] - m_ref);
                 float psum = 0.f;
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    const float pw = exp2f(s[u] - m_new);
+                    const float pw = exp2f(s[u] - m_ref);
                     const __bf16 ph = (__bf16)pw;
                     const __bf16 pl = (__bf16)(pw - (float)ph);
                     psum += (float)ph + (float)pl;

@@ -23,7 +23,7 @@ _NP_DT = {np.dtype(np.float32): F32, np.dtype(np.float16): F16}
 
 EXPORTS = ["kvbfp_cache_bytes", "kvbfp_calibrate_perm", "kvbfp_permute_weights",
            "kvbfp_quantize_append", "kvbfp_dequantize", "kvbfp_decode_workspace_bytes",
-           "kvbfp_decode_attention", "kvbfp_decode_attention_qbfp", "kvbfp_append_decode_attention", "kvbfp_decode_attention_profile",
+           "kvbfp_decode_attention", "kvbfp_decode_attention_qbfp", "kvbfp_append_decode_attention", "kvbfp_decode_attention_multi", "kvbfp_decode_attention_profile",
            "kvbfp_last_error", "kvbfp_version"]
 
 
@@ -80,6 +80,10 @@ def lib():
                                                     C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int,
                                                     C.c_void_p, C.c_int64, C.c_float, C.c_void_p, C.c_void_p,
                                                     C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        l.kvbfp_decode_attention_multi.argtypes = [C.POINTER(Layout), C.POINTER(CachePtrs), C.c_int32, C.c_int32,
+                                                   C.c_void_p, C.c_int, C.c_void_p, C.c_int64, C.c_float,
+                                                   C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
+                                                   C.c_size_t, C.c_void_p]
         l.kvbfp_decode_attention_profile.argtypes = l.kvbfp_decode_attention_qbfp.argtypes + [C.POINTER(C.c_float)]
         _lib = l
     return _lib
@@ -324,4 +328,28 @@ def append_decode_attention(cache: Cache, k_new, v_new, q, max_len, softmax_scal
                                                _dev_ptr(perm_k, torch.int32), _dev_ptr(perm_v, torch.int32),
                                                int(q_mant_bits), _dev_ptr(out), _dev_ptr(workspace), workspace.numel(),
                                                _stream_ptr(stream)))
+    return out
+
+
+def decode_attention_multi(cache: Cache, q, max_len, softmax_scale, seq_len_dev=None, perm_k=None, perm_v=None,
+                           q_mant_bits=0, out=None, workspace=None, stream=None):
+    """DEVICE, async.  q: [batch][n_q_tokens][n_q_heads][head_dim] contiguous: the last n_q_tokens tokens of every
+    sequence (already cached), causal among themselves.  Returns out of the same shape."""
+    L = cache.layout
+    if q.dim() != 4 or not q.is_contiguous():
+        raise ValueError("q must be a contiguous [batch][n_q_tokens][n_q_heads][head_dim] tensor")
+    n_tok, n_q_heads = q.shape[1], q.shape[2]
+    if out is None:
+        out = torch.empty_like(q)
+    if workspace is None:
+        need = decode_workspace_bytes(L, n_q_heads * n_tok, max_len)
+        if need == 0:
+            _check(ERR_INVALID_ARG)
+        workspace = torch.empty((need,), dtype=torch.uint8, device=q.device)
+    ptrs = cache.ptrs
+    _check(lib().kvbfp_decode_attention_multi(C.byref(L), C.byref(ptrs), n_q_heads, n_tok, _dev_ptr(q), _TORCH_DT[q.dtype],
+                                              _dev_ptr(seq_len_dev, torch.int32), int(max_len), float(softmax_scale),
+                                              _dev_ptr(perm_k, torch.int32), _dev_ptr(perm_v, torch.int32),
+                                              int(q_mant_bits), _dev_ptr(out), _dev_ptr(workspace), workspace.numel(),
+                                              _stream_ptr(stream)))
     return out
