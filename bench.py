@@ -310,6 +310,19 @@ def main():
         try:
             q8 = np.array([ring.decode_kernels(i, q_mant_bits=8)[0] for i in range(min(args.steps, 20))])
             result["decode_split_us_median_query_bfp8"] = float(np.median(q8))
+            # four query tokens per sequence (G * 4 virtual heads per kv-head) over the same caches
+            q4 = torch.stack([ring.q] * 4, dim=1).contiguous()
+            ws4 = torch.empty((kvbfp.decode_workspace_bytes(ring.layout, w.n_q_heads * 4, ring.S_max),), dtype=torch.uint8,
+                              device=ring.q.device)
+            out4 = torch.empty_like(q4)
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(12)]
+            for i, (e0, e1) in enumerate(ev):
+                e0.record()
+                kvbfp.decode_attention_multi(ring.caches[i % len(ring.caches)], q4, ring.S_max, ring.scale, perm_k=ring.perm_k,
+                                             perm_v=ring.perm_v, out=out4, workspace=ws4)
+                e1.record()
+            torch.cuda.synchronize()
+            result["decode_4_query_tokens_us_median"] = float(np.median([a.elapsed_time(b) for a, b in ev][2:]) * 1e3)
             result["quantize_append_bulk"] = bulk_quantize_rate()
         except Exception as e:      # reported, never hidden
             result["quantize_append_bulk"] = {"error": repr(e)}

@@ -212,9 +212,9 @@ int kvbfp_append_decode_attention(const kvbfp_layout* layout, const kvbfp_cache*
  * sees no cached token yields zeros.
  *   q, out      : DEVICE [batch][n_q_tokens][n_q_heads][head_dim] of `dtype`, contiguous.
  *   workspace   : at least kvbfp_decode_workspace_bytes(layout, n_q_heads * n_q_tokens, max_len) bytes.
- *   n_q_tokens  : 1..64.  The matrix-core passes take n_q_tokens * (n_q_heads / n_kv_heads) <= 8
- *                 (their spare rows hold the extra tokens, so the cost is that of one token); more
- *                 go through the general pass.
+ *   n_q_tokens  : 1..64.  With n_q_tokens * (n_q_heads / n_kv_heads) <= 8 the spare rows of the
+ *                 matrix-core passes hold the extra tokens and the cost is that of one token; up to
+ *                 32 the cache is read once per 8; more go through the general pass.
  * Everything else as kvbfp_decode_attention_qbfp.  n_q_tokens = 1 is that call. */
 int kvbfp_decode_attention_multi(const kvbfp_layout* layout, const kvbfp_cache* cache,
                                  int32_t n_q_heads, int32_t n_q_tokens, const void* q,

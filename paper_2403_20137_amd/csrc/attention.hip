@@ -421,8 +421,12 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
         return fail(KVBFP_ERR_UNSUPPORTED, "decode_attention: too many heads for the grid");
     const dim3 grid1((unsigned)sp.n_splits, (unsigned)(a.H_kv * gg), (unsigned)L->batch);
     auto aligned16 = [](const void* p) { return ((uintptr_t)p & 15u) == 0; };
-    const bool fast = a.G <= 8 && dtype != KVBFP_F32 && aligned16(a.k_mant) &&
+    // Matrix-core passes: 16-bit I/O, up to 8 (virtual) heads of a kv-head per launch; larger groups take
+    // several launches over head subsets (the cache is then read once per subset), up to 4 of them.
+    const bool fast = a.G <= 32 && dtype != KVBFP_F32 && aligned16(a.k_mant) &&
                       aligned16(a.v_mant) && aligned16(a.k_exp) && aligned16(a.v_exp);
+    a.g_base = 0;
+    a.g_cnt = a.G < 8 ? a.G : 8;
     // The current token (kvbfp_append_decode_attention): cast inside the LDS split pass, else by the
     // cache-write kernel ahead of the split pass.  Either way it lands at position seq_len - 1.
     if (k_new || v_new) {
@@ -454,8 +458,14 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
     }
     hipError_t err;
     if (fast) {
-        err = L->mant_bits == 4 ? launch_decode_split_mfma(a, (int)dtype, L->block, L->batch, s)
-                                : launch_decode_split_mfma_p8(a, (int)dtype, L->block, L->batch, s);
+        err = hipSuccess;
+        for (int g0 = 0; g0 < a.G && err == hipSuccess; g0 += 8) {
+            a.g_base = g0;
+            a.g_cnt = a.G - g0 < 8 ? a.G - g0 : 8;
+            err = L->mant_bits == 4 ? launch_decode_split_mfma(a, (int)dtype, L->block, L->batch, s)
+                                    : launch_decode_split_mfma_p8(a, (int)dtype, L->block, L->batch, s);
+            a.k_new = a.v_new = nullptr;       // the current token is cast by the first launch only
+        }
     } else {
         if (L->mant_bits == 4) decode_split_generic<4><<<grid1, kTile, 0, s>>>(a, (int)dtype);
         else decode_split_generic<8><<<grid1, kTile, 0, s>>>(a, (int)dtype);

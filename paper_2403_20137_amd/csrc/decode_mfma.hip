@@ -81,7 +81,7 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
     const int wave = tid >> 6, lane = tid & 63;
     const int j = lane & 15, kg = lane >> 4;
     const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
-    const int h0 = kvh * a.G;
+    const int h0 = kvh * a.G + a.g_base;      // first (virtual) head of this launch
 
     int64_t L = a.seq_len ? (int64_t)a.seq_len[b] : a.max_len;
     L = L < 0 ? 0 : (L > a.max_len ? a.max_len : L);
@@ -89,9 +89,9 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
     const int64_t t_end = min(t_begin + a.split_len, L);
 
     if (t_begin >= t_end) {   // nothing cached in this split
-        for (int i = tid; i < a.G * kD; i += 256)
+        for (int i = tid; i < a.g_cnt * kD; i += 256)
             a.part_o[(((int64_t)b * a.H_q + h0 + i / kD) * a.n_splits + split) * kD + (i % kD)] = 0.f;
-        if (tid < a.G) {
+        if (tid < a.g_cnt) {
             float* ml = a.part_ml + (((int64_t)b * a.H_q + h0 + tid) * a.n_splits + split) * 2;
             ml[0] = -INFINITY;
             ml[1] = 0.f;
@@ -105,9 +105,9 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
         for (int i = tid; i < NH * kD; i += 256) {
             const int g = i / kD, c = i % kD;
             float v = 0.f;
-            if (g < a.G) {
+            if (g < a.g_cnt) {
                 const int src = a.perm_k ? a.perm_k[kvh * kD + c] : c;
-                v = load_as_float(a.q, dt, kvbfp::query_row(a, b, kvh, g) * kD + src);
+                v = load_as_float(a.q, dt, kvbfp::query_row(a, b, kvh, a.g_base + g) * kD + src);
             }
             q_s[g][c] = a.q_mant_bits ? v : v * factor;
         }
@@ -160,7 +160,7 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
     const int n_full = min(n_tok, n_vis - (a.n_q_tokens - 1));
     int lim[HG];
 #pragma unroll
-    for (int hg = 0; hg < HG; ++hg) lim[hg] = n_vis - kvbfp::hidden_tokens(a, hg * 4 + kg);
+    for (int hg = 0; hg < HG; ++hg) lim[hg] = n_vis - kvbfp::hidden_tokens(a, a.g_base + hg * 4 + kg);
 
     float m_run[HG], l_run[HG];
     f32x4 o_acc[HG][4];
@@ -332,7 +332,7 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
     __syncthreads();
 
     // ---------------- merge the four wavefronts, write this split's partial result
-    for (int i = tid; i < a.G * kD; i += 256) {
+    for (int i = tid; i < a.g_cnt * kD; i += 256) {
         const int g = i / kD, c = i % kD;
         float M = -INFINITY;
 #pragma unroll
@@ -345,7 +345,7 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
         }
         a.part_o[(((int64_t)b * a.H_q + h0 + g) * a.n_splits + split) * kD + c] = acc * (float)(1 << kShift);
     }
-    if (tid < a.G) {
+    if (tid < a.g_cnt) {
         const int g = tid;
         float M = -INFINITY;
 #pragma unroll
@@ -467,7 +467,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
     const int lane = tid & 63;
     const int j = lane & 15, kg = lane >> 4;
     const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
-    const int h0 = kvh * a.G;
+    const int h0 = kvh * a.G + a.g_base;      // first (virtual) head of this launch
 
     int64_t L = a.seq_len ? (int64_t)a.seq_len[b] : a.max_len;
     L = L < 0 ? 0 : (L > a.max_len ? a.max_len : L);
@@ -475,9 +475,9 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
     const int64_t t_end = min(t_begin + a.split_len, L);
 
     if (t_begin >= t_end) {   // nothing cached in this split
-        for (int i = tid; i < a.G * kD; i += 256)
+        for (int i = tid; i < a.g_cnt * kD; i += 256)
             a.part_o[(((int64_t)b * a.H_q + h0 + i / kD) * a.n_splits + split) * kD + (i % kD)] = 0.f;
-        if (tid < a.G) {
+        if (tid < a.g_cnt) {
             float* ml = a.part_ml + (((int64_t)b * a.H_q + h0 + tid) * a.n_splits + split) * 2;
             ml[0] = -INFINITY;
             ml[1] = 0.f;
@@ -519,7 +519,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
     // several query tokens: head slot s sees tokens below lim[.] only (split-relative)
     int lim[HG];
 #pragma unroll
-    for (int hg = 0; hg < HG; ++hg) lim[hg] = (int)(L - t_begin) - kvbfp::hidden_tokens(a, hg * 4 + (lane >> 4));
+    for (int hg = 0; hg < HG; ++hg) lim[hg] = (int)(L - t_begin) - kvbfp::hidden_tokens(a, a.g_base + hg * 4 + (lane >> 4));
 
     uint8_t* const wbase = smem + wave * kWaveBytes;
 
@@ -584,7 +584,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
 #pragma unroll
     for (int k = 0; k < kQPerThread; ++k) {
         const int i = tid + 256 * k, g = i / kD, c = i % kD;
-        const int64_t idx = kvbfp::query_row(a, b, kvh, min(g, a.G - 1)) * kD + c;     // clamped: rows beyond G are zeroed below
+        const int64_t idx = kvbfp::query_row(a, b, kvh, a.g_base + min(g, a.g_cnt - 1)) * kD + c;   // clamped: rows beyond the count are zeroed below
         q_bits[k] = dt == KVBFP_F32 ? ((const uint32_t*)a.q)[idx] : (uint32_t)((const uint16_t*)a.q)[idx];
     }
     int perm_c = 0;
@@ -604,7 +604,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
         if (dt == KVBFP_F32) f = __uint_as_float(q_bits[k]);
         else if (dt == KVBFP_F16) f = (float)__builtin_bit_cast(_Float16, (unsigned short)q_bits[k]);
         else f = __uint_as_float(q_bits[k] << 16);
-        qr[tid + 256 * k] = g < a.G ? f : 0.f;
+        qr[tid + 256 * k] = g < a.g_cnt ? f : 0.f;
     }
     if (a.perm_k && tid < kD) scratch[tid] = perm_c & (kD - 1);   // a valid permutation is unchanged; keeps LDS reads in range
 
@@ -880,7 +880,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
         }
     }
     __syncthreads();
-    for (int i = tid; i < a.G * kD; i += 256) {
+    for (int i = tid; i < a.g_cnt * kD; i += 256) {
         const int g = i / kD, c = i % kD;
         float M = -INFINITY;
 #pragma unroll
@@ -893,7 +893,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
         }
         a.part_o[(((int64_t)b * a.H_q + h0 + g) * a.n_splits + split) * kD + c] = acc * (float)(1 << kShift);
     }
-    if (tid < a.G) {
+    if (tid < a.g_cnt) {
         const int g = tid;
         float M = -INFINITY;
 #pragma unroll
@@ -928,7 +928,7 @@ namespace kvbfp {
 
 hipError_t launch_decode_split_mfma(const DecodeArgs& a, int dtype, int block, int batch, hipStream_t s) {
     const dim3 grid((unsigned)a.n_splits, (unsigned)a.H_kv, (unsigned)batch);
-    if (a.G <= 4) return launch_n<1>(a, dtype, block, grid, s);
+    if (a.g_cnt <= 4) return launch_n<1>(a, dtype, block, grid, s);
     return launch_n<2>(a, dtype, block, grid, s);
 }
 

@@ -82,7 +82,7 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p8(DecodeArgs a, int dt
     const int wave = tid >> 6, lane = tid & 63;
     const int j = lane & 15, kg = lane >> 4;
     const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
-    const int h0 = kvh * a.G;
+    const int h0 = kvh * a.G + a.g_base;      // first (virtual) head of this launch
 
     int64_t L = a.seq_len ? (int64_t)a.seq_len[b] : a.max_len;
     L = L < 0 ? 0 : (L > a.max_len ? a.max_len : L);
@@ -90,9 +90,9 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p8(DecodeArgs a, int dt
     const int64_t t_end = min(t_begin + a.split_len, L);
 
     if (t_begin >= t_end) {   // nothing cached in this split
-        for (int i = tid; i < a.G * kD; i += 256)
+        for (int i = tid; i < a.g_cnt * kD; i += 256)
             a.part_o[(((int64_t)b * a.H_q + h0 + i / kD) * a.n_splits + split) * kD + (i % kD)] = 0.f;
-        if (tid < a.G) {
+        if (tid < a.g_cnt) {
             float* ml = a.part_ml + (((int64_t)b * a.H_q + h0 + tid) * a.n_splits + split) * 2;
             ml[0] = -INFINITY;
             ml[1] = 0.f;
@@ -106,9 +106,9 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p8(DecodeArgs a, int dt
         for (int i = tid; i < NH * kD; i += 256) {
             const int g = i / kD, c = i % kD;
             float v = 0.f;
-            if (g < a.G) {
+            if (g < a.g_cnt) {
                 const int src = a.perm_k ? a.perm_k[kvh * kD + c] : c;
-                v = load_as_float(a.q, dt, kvbfp::query_row(a, b, kvh, g) * kD + src);
+                v = load_as_float(a.q, dt, kvbfp::query_row(a, b, kvh, a.g_base + g) * kD + src);
             }
             q_s[g][c] = a.q_mant_bits ? v : v * factor;
         }
@@ -164,7 +164,7 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p8(DecodeArgs a, int dt
     const int n_full = min(n_tok, n_vis - (a.n_q_tokens - 1));
     int lim[HG];
 #pragma unroll
-    for (int hg = 0; hg < HG; ++hg) lim[hg] = n_vis - kvbfp::hidden_tokens(a, hg * 4 + kg);
+    for (int hg = 0; hg < HG; ++hg) lim[hg] = n_vis - kvbfp::hidden_tokens(a, a.g_base + hg * 4 + kg);
 
     float m_run[HG], l_run[HG];
     f32x4 o_acc[HG][4];
@@ -318,7 +318,7 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p8(DecodeArgs a, int dt
     __syncthreads();
 
     // ---------------- merge the four wavefronts, write this split's partial result
-    for (int i = tid; i < a.G * kD; i += 256) {
+    for (int i = tid; i < a.g_cnt * kD; i += 256) {
         const int g = i / kD, c = i % kD;
         float M = -INFINITY;
 #pragma unroll
@@ -331,7 +331,7 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p8(DecodeArgs a, int dt
         }
         a.part_o[(((int64_t)b * a.H_q + h0 + g) * a.n_splits + split) * kD + c] = acc * (float)(1 << kShift);
     }
-    if (tid < a.G) {
+    if (tid < a.g_cnt) {
         const int g = tid;
         float M = -INFINITY;
 #pragma unroll
@@ -365,7 +365,7 @@ namespace kvbfp {
 
 hipError_t launch_decode_split_mfma_p8(const DecodeArgs& a, int dtype, int block, int batch, hipStream_t s) {
     const dim3 grid((unsigned)a.n_splits, (unsigned)a.H_kv, (unsigned)batch);
-    if (a.G <= 4) return launch_n<1>(a, dtype, block, grid, s);
+    if (a.g_cnt <= 4) return launch_n<1>(a, dtype, block, grid, s);
     return launch_n<2>(a, dtype, block, grid, s);
 }
 

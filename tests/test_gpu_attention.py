@@ -75,7 +75,7 @@ def test_query_cast_to_bfp_matches_oracle(dtype, p, n, G, qbits):
 
 
 @pytest.mark.parametrize("p", [4, 8])
-@pytest.mark.parametrize("G", [2, 3, 5, 8])
+@pytest.mark.parametrize("G", [2, 3, 5, 8, 9, 16, 24, 32, 40])
 def test_group_sizes_and_no_permutation(G, p):
     k, v, q, _, _ = make_small(torch.bfloat16, B=1, S=300, Hkv=3, G=G, seed=40 + G)
     got, want = run_both(k, v, q, 32, p, [300], 0.11, None, None, use_seq_len=False)

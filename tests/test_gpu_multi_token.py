@@ -20,7 +20,10 @@ DT = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
     ("bf16", 4, 64, 1, 8),     # register-staged pass
     ("bf16", 8, 16, 1, 8),     # 8-bit mantissas
     ("bf16", 8, 32, 2, 3),     # 6 virtual heads
-    ("bf16", 4, 32, 4, 4),     # 16 virtual heads: general pass
+    ("bf16", 4, 32, 4, 4),     # 16 virtual heads: two launches over head subsets
+    ("bf16", 4, 16, 4, 8),     # 32 virtual heads: four launches
+    ("bf16", 8, 32, 3, 7),     # 21 virtual heads: 8 + 8 + 5
+    ("f16", 4, 32, 4, 9),      # 36 virtual heads: general pass
     ("f32", 4, 32, 2, 5),      # fp32 I/O: general pass
 ])
 def test_each_query_token_matches_single_token_attention(dt, p, n, G, Tq):
