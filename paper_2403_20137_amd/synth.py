@@ -57,6 +57,8 @@ WORKLOADS = {
     "batched_8k_p8": Workload("batched_8k_p8", 16, 32, 32, 128, 8192, "bf16", 16, 8, (2, 6), (10.0, 50.0)),
     "llama3_8b_gqa_32k": Workload("llama3_8b_gqa_32k", 8, 32, 8, 128, 32768, "bf16", 32, 4, (2, 6), (20.0, 20.0)),
     "long_128k": Workload("long_128k", 1, 32, 8, 128, 131072, "bf16", 16, 4, (2, 6), (20.0, 20.0)),
+    # not one of the contract's configurations: 8 query heads per kv-head (two MFMA row groups per pass)
+    "gqa8_32k": Workload("gqa8_32k", 8, 64, 8, 128, 32768, "bf16", 32, 4, (2, 6), (20.0, 20.0)),
     "prefill_bulk": Workload("prefill_bulk", 32, 8, 8, 128, 4096, "bf16", 16, 4, (2, 6), (10.0, 50.0),
                              extra={"note": "32 layers x 8 KV heads x 4096 tokens, layer index plays the batch role"}),
 }
