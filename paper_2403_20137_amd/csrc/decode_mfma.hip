@@ -364,9 +364,12 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
 
 
 // ------------------------------------------------------------------------------------------------
-// LDS-staged variant (block 16 or 32): the same arithmetic, but the packed rows travel
+// LDS-staged pass (blocks of 16 and 32, the default for them): the packed rows travel
 // global -> LDS by DMA (global_load_lds) instead of through registers, so every wavefront keeps
-// most of a 64-token tile in flight without holding registers for it.
+// most of a 64-token tile in flight without holding registers for it.  Values are unpacked as
+// above; keys are not unpacked at all: the raw nibbles are the FP4 operand of the scaled
+// FP8 x FP4 MFMA (v_mfma_scale_f32_16x16x128_f8f6f4), the block exponent byte is its E8M0 scale,
+// and the query is four FP8 limbs with a power-of-two scale per 32 channels.
 //
 // Each wavefront owns a private staging area of four 16-token stages for keys and four for values
 // (mantissas 1 KB + exponent bytes per stage).  A stage is re-filled for the wavefront's next tile
@@ -446,12 +449,12 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
     constexpr int kKe = kVm + 4096;                // 4 stages x 64 lanes x 4 B key exponents (own dword per lane)
     constexpr int kVe = kKe + 1024;                // 4 stages x 256 B: 16 tokens x NB value exponent bytes (+ duplicates)
     constexpr int kWaveBytes = kVe + 1024;
-    // Blocks of 32 are exactly the MX block of the scaled MFMA: keys then go in as raw FP4 nibbles.
-    constexpr bool kFp4Keys = (N == 32);
-    constexpr int kQl = kWaves * kWaveBytes;       // query operand staging (limbs in MFMA operand order)
-    constexpr int kQf = kQl;                       // fp4 path: q' as fp32 [NH][128]
-    constexpr int kQ8 = kQf + NH * kD * 4;         //           FP8 limbs [NH*4 rows][128], then scale bytes [NH*4][4]
-    constexpr int kTotal = kFp4Keys ? kQ8 + NH * 4 * kD + NH * 16 : kQl + NH * 4 * kD * 2;
+    // Keys go to the scaled FP8 x FP4 MFMA as raw nibbles: a block of 32 is exactly its MX block; a
+    // block of 16 takes two products per 32 channels, each with the other block's nibbles zeroed.
+    constexpr int kQl = kWaves * kWaveBytes;       // query operand staging, an LDS object of its own:
+    constexpr int kQf = kQl;                       //   q' as fp32 [NH][128]
+    constexpr int kQ8 = kQf + NH * kD * 4;         //   FP8 limbs [NH*4 rows][128], then scale bytes [NH*4][4]
+    constexpr int kTotal = kQ8 + NH * 4 * kD + NH * 16;
     static_assert(kWaves * NH * kD * 4 + kWaves * NH * 8 <= kQl, "merge buffers alias the staging area");
     // The DMA rings and the query staging are separate LDS objects: the compiler waits for every
     // outstanding DMA before it touches an object that a DMA may write, and the set-up must not wait
@@ -618,9 +621,8 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
     }
 
     // ---- query operand of the score product to LDS (whole workgroup) -------------------------------
-    bf16x8 aq[HG][4];      // bf16 path: row 4*head + limb (3 limbs), 4 MFMAs of 32 channels
-    v8i aq8[HG];           // fp4-key path: row 4*head + limb (4 FP8 limbs), one MFMA of 128 channels
-    int sa8[HG];           //               E8M0 scale of this lane's 32 query values
+    v8i aq8[HG];           // row 4*head + limb (4 FP8 limbs), one MFMA of 128 channels
+    int sa8[HG];           // E8M0 scale of this lane's 32 query values
     if (a.perm_k) {
         float q_perm[kQPerThread];
         lds_barrier();
@@ -635,7 +637,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
     }
     lds_barrier();
     if (a.q_mant_bits) bfp_round_queries(qr, (uint32_t*)scratch, NH, a.log2_block, a.q_mant_bits);
-    if (kFp4Keys) {
+    {
         // FP8 operand layout (measured): byte i of lane-group g is channel 64*(i/16) + 16*g + i%16, while
         // the E8M0 scale of channel block kb (32 consecutive channels) is taken from lane-group kb.
         // Each block of 32 query values shares a power-of-two scale 2^sh chosen so that the largest
@@ -659,7 +661,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
             int sh = mx > 0.f ? e - 8 : 0;                  // mx * 2^-sh in [128, 256)
             sh = max(-110, min(110, sh));
             float v = qf[g * kD + c];
-#pragma unroll
+    #pragma unroll
             for (int limb = 0; limb < 4; ++limb) {
                 const int sl = sh - 4 * limb;
                 const uint32_t packed = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(ldexpf(v, -sl), 0.f, 0, false);
@@ -669,35 +671,13 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
             }
         }
         lds_barrier();
-#pragma unroll
+    #pragma unroll
         for (int hg = 0; hg < HG; ++hg) {
             const u32x4 lo = *(const u32x4*)(q8 + (hg * 16 + j) * kD + kg * 32);
             const u32x4 hi = *(const u32x4*)(q8 + (hg * 16 + j) * kD + kg * 32 + 16);
             aq8[hg] = v8i{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
             sa8[hg] = qsc[(hg * 16 + j) * 4 + kg];
         }
-    } else {
-        // row 4*head + limb; position 32*kg + 8*d + x holds channel 32*kg + 8*d + slot_channel(x)
-        uint16_t* ql = (uint16_t*)q_lds;
-        for (int i = tid; i < NH * kD; i += 256) {
-            const int g = i / kD, pos = i % kD;
-            const int c = (pos & ~7) + slot_channel(pos & 7);
-            const float f = qr[g * kD + c] * a.scale_log2e * (float)(1 << kShift);
-            const __bf16 l0 = (__bf16)f;
-            const float r1 = f - (float)l0;
-            const __bf16 l1 = (__bf16)r1;
-            const __bf16 l2 = (__bf16)(r1 - (float)l1);
-            ql[(4 * g + 0) * kD + pos] = __builtin_bit_cast(unsigned short, l0);
-            ql[(4 * g + 1) * kD + pos] = __builtin_bit_cast(unsigned short, l1);
-            ql[(4 * g + 2) * kD + pos] = __builtin_bit_cast(unsigned short, l2);
-            ql[(4 * g + 3) * kD + pos] = 0;
-        }
-        lds_barrier();
-#pragma unroll
-        for (int hg = 0; hg < HG; ++hg)
-#pragma unroll
-            for (int d = 0; d < 4; ++d)
-                aq[hg][d] = *(const bf16x8*)(q_lds + ((hg * 16 + j) * kD + 32 * kg + 8 * d) * 2);
     }
 
     const int a_head = j >> 2, a_par = (j >> 1) & 1, a_limb = j & 1;
@@ -741,45 +721,42 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
                 lds_read_key_stage<u * 1024, u * 256, N == 16>(kq, keq, raw, kexp);
 #pragma unroll
                 for (int hg = 0; hg < HG; ++hg) s_acc[hg][u] = f32x4{0.f, 0.f, 0.f, 0.f};
-                if (kFp4Keys) {
+                {
                     // magnitude/2 = FP4(s,0,m1,m0) + FP4(s,m2,0,0): two masked copies of the raw nibbles
                     // are the B operands; the block's exponent byte (minus one for the halving) is
                     // their E8M0 scale.
-                    const uint32_t E = kexp;
-                    const int sb = (int)__builtin_elementwise_sub_sat((unsigned short)E, (unsigned short)1);
-                    const v8i b1 = {(int)(raw[0] & 0xBBBBBBBBu), (int)(raw[1] & 0xBBBBBBBBu), (int)(raw[2] & 0xBBBBBBBBu),
-                                    (int)(raw[3] & 0xBBBBBBBBu), 0, 0, 0, 0};
-                    const v8i b2 = {(int)(raw[0] & 0xCCCCCCCCu), (int)(raw[1] & 0xCCCCCCCCu), (int)(raw[2] & 0xCCCCCCCCu),
-                                    (int)(raw[3] & 0xCCCCCCCCu), 0, 0, 0, 0};
-                    __builtin_amdgcn_sched_barrier(0);
-                    if (more) fill_keys(u, T1 + 16 * u);
-                    __builtin_amdgcn_sched_barrier(0);
+                    if (N == 32) {
+                        const int sb = (int)__builtin_elementwise_sub_sat((unsigned short)kexp, (unsigned short)1);
+                        const v8i b1 = {(int)(raw[0] & 0xBBBBBBBBu), (int)(raw[1] & 0xBBBBBBBBu), (int)(raw[2] & 0xBBBBBBBBu),
+                                        (int)(raw[3] & 0xBBBBBBBBu), 0, 0, 0, 0};
+                        const v8i b2 = {(int)(raw[0] & 0xCCCCCCCCu), (int)(raw[1] & 0xCCCCCCCCu), (int)(raw[2] & 0xCCCCCCCCu),
+                                        (int)(raw[3] & 0xCCCCCCCCu), 0, 0, 0, 0};
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (more) fill_keys(u, T1 + 16 * u);
+                        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int hg = 0; hg < HG; ++hg) {
-                        s_acc[hg][u] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aq8[hg], b1, s_acc[hg][u], 0, 4, 0, sa8[hg], 0, sb);
-                        s_acc[hg][u] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aq8[hg], b2, s_acc[hg][u], 0, 4, 0, sa8[hg], 0, sb);
-                    }
-                } else {
-                    float sc0, sc1;
-                    if (N == 16) {
-                        sc0 = scale_operand(kexp & 0xFFu);
-                        sc1 = scale_operand(kexp >> 8);
+                        for (int hg = 0; hg < HG; ++hg) {
+                            s_acc[hg][u] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aq8[hg], b1, s_acc[hg][u], 0, 4, 0, sa8[hg], 0, sb);
+                            s_acc[hg][u] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aq8[hg], b2, s_acc[hg][u], 0, 4, 0, sa8[hg], 0, sb);
+                        }
                     } else {
-                        sc0 = sc1 = scale_operand(kexp);
-                    }
-                    Unpacked kk[4];
+                        // the lane's 32 nibbles are two blocks of 16 (dwords 0-1 and 2-3) with an exponent each
+                        const int sb0 = (int)__builtin_elementwise_sub_sat((unsigned short)(kexp & 0xFFu), (unsigned short)1);
+                        const int sb1 = (int)__builtin_elementwise_sub_sat((unsigned short)(kexp >> 8), (unsigned short)1);
+                        const v8i lo1 = {(int)(raw[0] & 0xBBBBBBBBu), (int)(raw[1] & 0xBBBBBBBBu), 0, 0, 0, 0, 0, 0};
+                        const v8i lo2 = {(int)(raw[0] & 0xCCCCCCCCu), (int)(raw[1] & 0xCCCCCCCCu), 0, 0, 0, 0, 0, 0};
+                        const v8i hi1 = {0, 0, (int)(raw[2] & 0xBBBBBBBBu), (int)(raw[3] & 0xBBBBBBBBu), 0, 0, 0, 0};
+                        const v8i hi2 = {0, 0, (int)(raw[2] & 0xCCCCCCCCu), (int)(raw[3] & 0xCCCCCCCCu), 0, 0, 0, 0};
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (more) fill_keys(u, T1 + 16 * u);
+                        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int d = 0; d < 4; ++d) kk[d] = unpack8(raw[d], d < 2 ? sc0 : sc1);
-                    // the stage has been read into registers: re-fill it for the next tile
-                    __builtin_amdgcn_sched_barrier(0);
-                    if (more) fill_keys(u, T1 + 16 * u);
-                    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                    for (int d = 0; d < 4; ++d) {
-                        const bf16x8 bk = join(kk[d].p[0], kk[d].p[1], kk[d].p[2], kk[d].p[3]);
-#pragma unroll
-                        for (int hg = 0; hg < HG; ++hg)
-                            s_acc[hg][u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aq[hg][d], bk, s_acc[hg][u], 0, 0, 0);
+                        for (int hg = 0; hg < HG; ++hg) {
+                            s_acc[hg][u] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aq8[hg], lo1, s_acc[hg][u], 0, 4, 0, sa8[hg], 0, sb0);
+                            s_acc[hg][u] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aq8[hg], lo2, s_acc[hg][u], 0, 4, 0, sa8[hg], 0, sb0);
+                            s_acc[hg][u] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aq8[hg], hi1, s_acc[hg][u], 0, 4, 0, sa8[hg], 0, sb1);
+                            s_acc[hg][u] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aq8[hg], hi2, s_acc[hg][u], 0, 4, 0, sa8[hg], 0, sb1);
+                        }
                     }
                 }
             });
