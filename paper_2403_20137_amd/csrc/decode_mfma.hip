@@ -437,7 +437,7 @@ __device__ __forceinline__ void lds_read_val_stage(uint32_t m_addr, uint32_t e_a
 constexpr int vmcnt_imm(int n) { return (n & 0xF) | (0x7 << 4) | (0xF << 8) | ((n >> 4) << 14); }
 
 template <int N, int HG>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4)))
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((N == 16 && HG == 2) ? 2 : 3, 4)))
 void decode_split_lds_p4(DecodeArgs a, int dt) {
     static_assert(N == 16 || N == 32, "LDS pipeline is built for blocks of 16 or 32");
     constexpr int NB = kD / N;
@@ -451,19 +451,19 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
     constexpr int kWaveBytes = kVe + 1024;
     // Keys go to the scaled FP8 x FP4 MFMA as raw nibbles: a block of 32 is exactly its MX block; a
     // block of 16 takes two products per 32 channels, each with the other block's nibbles zeroed.
-    constexpr int kQl = kWaves * kWaveBytes;       // query operand staging, an LDS object of its own:
-    constexpr int kQf = kQl;                       //   q' as fp32 [NH][128]
-    constexpr int kQ8 = kQf + NH * kD * 4;         //   FP8 limbs [NH*4 rows][128], then scale bytes [NH*4][4]
-    constexpr int kTotal = kQ8 + NH * 4 * kD + NH * 16;
-    static_assert(kWaves * NH * kD * 4 + kWaves * NH * 8 <= kQl, "merge buffers alias the staging area");
-    // The DMA rings and the query staging are separate LDS objects: the compiler waits for every
-    // outstanding DMA before it touches an object that a DMA may write, and the set-up must not wait
-    // for the first tile.
-    __shared__ __align__(16) uint8_t smem[kQl];
-    __shared__ __align__(16) uint8_t q_lds[kTotal - kQl];
+    constexpr int kRings = kWaves * kWaveBytes;
+    static_assert(kWaves * NH * kD * 4 + kWaves * NH * 8 <= kRings, "merge buffers alias the staging area");
+    // The DMA rings are an LDS object of their own: the compiler waits for every outstanding DMA
+    // before it touches an object that a DMA may write, and the set-up must not wait for the first tile.
+    __shared__ __align__(16) uint8_t smem[kRings];
     // probabilities of the current tile, bf16 hi/lo limbs: [wave][HG][2 limbs][4 heads][64 tokens].  A separate
     // LDS object, so the compiler can tell its reads apart from the DMA targets inside smem.
     __shared__ __align__(16) uint16_t p_lds[kWaves][HG * 2 * 4 * kTileTok];
+    // Until the main loop starts the same bytes stage the query: q' as fp32 [NH][128] in the first half,
+    // its FP8 limbs [NH*4 rows][128] in the second (the permutation and the block maxima of the BFP cast
+    // pass through there before the limbs are written); the limbs' scale bytes [NH*4][4] sit beside.
+    static_assert(sizeof(p_lds) == NH * kD * 4 + NH * 4 * kD, "query staging fills the probability buffer exactly");
+    __shared__ __align__(16) uint8_t qsc_lds[NH * 16];
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS bases stay in scalar registers
@@ -599,7 +599,6 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
     // after them, so they have arrived by now); everything after works on LDS only.
     float* const qr = (float*)&p_lds[0][0];                 // [NH][kD], unscaled
     int* const scratch = (int*)(qr + NH * kD);              // permutation, then block maxima of the cast
-    static_assert(sizeof(p_lds) >= NH * kD * 4 + kD * 4, "query staging fits the probability buffer");
 #pragma unroll
     for (int k = 0; k < kQPerThread; ++k) {
         const int g = (tid + 256 * k) / kD;
@@ -643,9 +642,9 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
         // Each block of 32 query values shares a power-of-two scale 2^sh chosen so that the largest
         // lands in [128, 256); limb l holds the FP8 rounding of the residual at scale 2^(sh - 4l), so four
         // limbs carry 16 bits relative to the block's maximum.
-        float* qf = (float*)(q_lds + (kQf - kQl));
-        uint8_t* q8 = q_lds + (kQ8 - kQl);
-        uint8_t* qsc = q8 + NH * 4 * kD;
+        float* qf = qr;                                   // scaled in place
+        uint8_t* q8 = (uint8_t*)(qr + NH * kD);           // over the scratch area, which is done with
+        uint8_t* qsc = qsc_lds;
         for (int i = tid; i < NH * kD; i += 256) {
             qf[i] = qr[i] * a.scale_log2e;
         }
@@ -678,6 +677,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
             aq8[hg] = v8i{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
             sa8[hg] = qsc[(hg * 16 + j) * 4 + kg];
         }
+        lds_barrier();                                    // the buffer goes over to the probabilities
     }
 
     const int a_head = j >> 2, a_par = (j >> 1) & 1, a_limb = j & 1;

@@ -56,10 +56,8 @@ SplitPlan plan_splits(const kvbfp_layout* L, int32_t n_q_heads, int64_t max_len)
     // of token tiles.
     const int64_t units = (int64_t)L->batch * L->n_kv_heads;
     const int64_t tiles = (max_len + kTokenTile - 1) / kTokenTile;
-    // Resident workgroups per compute unit of the split pass: three with up to four heads per kv-head
-    // in a launch, two with five to eight (twice the accumulators and probability buffers).
-    const int64_t group = L->n_kv_heads > 0 ? n_q_heads / L->n_kv_heads : 1;
-    const int64_t target_wgs = 256 * (group > 4 ? 2 : 3);
+    (void)n_q_heads;
+    const int64_t target_wgs = 256 * 3;   // three resident workgroups per compute unit
     int64_t want = (target_wgs + units - 1) / units;
     if (want < 1) want = 1;
     if (want > tiles) want = tiles;
