@@ -216,10 +216,24 @@ def bulk_quantize_rate(device="cuda", reps=5):
             "with_perm_us_median": float(np.median(us_perm)), "with_perm_gelem_s": elems / np.median(us_perm) / 1e3}
 
 
+def device_info():
+    """Name, compute units and clocks of the GPU the numbers were taken on (clocks as the driver reports them)."""
+    p = torch.cuda.get_device_properties(0)
+    info = {"name": p.name, "compute_units": p.multi_processor_count}
+    try:
+        import subprocess
+        out = subprocess.run(["rocm-smi", "--showclocks", "--json"], capture_output=True, text=True, timeout=20).stdout
+        card = next(iter(json.loads(out).values()))
+        info["current_clocks"] = {k: v for k, v in card.items() if "clock" in k.lower()}
+    except Exception:
+        pass
+    return info
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default=HEADLINE, choices=sorted(synth.WORKLOADS))
     ap.add_argument("--layers", type=int, default=0, help="distinct layer caches in the ring (0 = enough for >= 1 GB)")
@@ -310,6 +324,17 @@ def main():
         try:
             q8 = np.array([ring.decode_kernels(i, q_mant_bits=8)[0] for i in range(min(args.steps, 20))])
             result["decode_split_us_median_query_bfp8"] = float(np.median(q8))
+            # the same call over ONE cache again and again: whatever of it stays in the 256 MB last-level
+            # cache is not read from HBM, so this figure is LLC-assisted and not a bandwidth claim
+            hot = []
+            for _ in range(12):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                ring.decode(0)
+                e1.record()
+                hot.append((e0, e1))
+            torch.cuda.synchronize()
+            result["decode_us_median_single_cache_llc_assisted"] = float(np.median([a.elapsed_time(b) for a, b in hot][2:]) * 1e3)
             # four query tokens per sequence (G * 4 virtual heads per kv-head) over the same caches
             q4 = torch.stack([ring.q] * 4, dim=1).contiguous()
             ws4 = torch.empty((kvbfp.decode_workspace_bytes(ring.layout, w.n_q_heads * 4, ring.S_max),), dtype=torch.uint8,
@@ -326,6 +351,7 @@ def main():
             result["quantize_append_bulk"] = bulk_quantize_rate()
         except Exception as e:      # reported, never hidden
             result["quantize_append_bulk"] = {"error": repr(e)}
+    result["device"] = device_info()
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(ring)
     print(json.dumps(result))
