@@ -158,9 +158,10 @@ size_t kvbfp_decode_workspace_bytes(const kvbfp_layout* layout, int32_t n_q_head
  *   workspace   : DEVICE, at least kvbfp_decode_workspace_bytes(layout, n_q_heads, max_len) bytes,
  *                 256-byte aligned; contents are scratch.
  * Accumulation is fp32; the output is rounded once to `dtype`.
- * Range: with fp16/bf16 I/O the products run on the matrix cores with power-of-two rescaling; cached
- * blocks whose exponent byte is below 10 (every magnitude under 2^-116) and query blocks outside
- * 2^-110 .. 2^110 lose their scale there.  fp32 I/O takes the general pass, which has no such limit.
+ * Range: up to 32 query heads per kv-head the products run on the matrix cores with power-of-two
+ * rescaling; cached blocks whose exponent byte is below 10 (every magnitude under 2^-116) and query
+ * blocks outside 2^-110 .. 2^110 lose their scale or their low-order bits there.  Wider groups take the
+ * general pass (fp32 multiply-adds), which has no such limit.
  * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP. */
 int kvbfp_decode_attention(const kvbfp_layout* layout, const kvbfp_cache* cache, int32_t n_q_heads,
                            const void* q, kvbfp_dtype dtype, const int32_t* seq_len_dev,

@@ -53,8 +53,9 @@ __device__ __forceinline__ float code_value(uint32_t c) {
     return (c >> (P - 1)) ? -m : m;
 }
 
-// Generic, precision-first split pass: fp32 FMAs everywhere, any block size, any group size
-// (query heads are processed four per workgroup; larger groups re-read the cache).
+// Generic split pass: fp32 FMAs everywhere, any block size, any group size (query heads are processed
+// four per workgroup; larger groups re-read the cache).  The fallback for what the matrix-core passes
+// do not take: more than 32 (virtual) heads per kv-head, planes that are not 16-byte aligned.
 // grid = (n_splits, H_kv * ceil(G/4), B), block = 256.
 template <int P>
 __global__ __launch_bounds__(kTile) void decode_split_generic(DecodeArgs a, int dt) {
@@ -421,9 +422,9 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
         return fail(KVBFP_ERR_UNSUPPORTED, "decode_attention: too many heads for the grid");
     const dim3 grid1((unsigned)sp.n_splits, (unsigned)(a.H_kv * gg), (unsigned)L->batch);
     auto aligned16 = [](const void* p) { return ((uintptr_t)p & 15u) == 0; };
-    // Matrix-core passes: 16-bit I/O, up to 8 (virtual) heads of a kv-head per launch; larger groups take
+    // Matrix-core passes: up to 8 (virtual) heads of a kv-head per launch; larger groups take
     // several launches over head subsets (the cache is then read once per subset), up to 4 of them.
-    const bool fast = a.G <= 32 && dtype != KVBFP_F32 && aligned16(a.k_mant) &&
+    const bool fast = a.G <= 32 && aligned16(a.k_mant) &&
                       aligned16(a.v_mant) && aligned16(a.k_exp) && aligned16(a.v_exp);
     a.g_base = 0;
     a.g_cnt = a.G < 8 ? a.G : 8;
@@ -439,7 +440,7 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
         // the others (otherwise the cache-write kernel goes first, as in the two separate calls).
         const int64_t tiles = (max_len + kTokenTile - 1) / kTokenTile, tiles_per_split = sp.split_len / kTokenTile;
         const int64_t last_tiles = tiles - (int64_t)(sp.n_splits - 1) * tiles_per_split;
-        const bool in_kernel = fast && L->mant_bits == 4 && (L->block == 16 || L->block == 32) &&
+        const bool in_kernel = fast && dtype != KVBFP_F32 && L->mant_bits == 4 && (L->block == 16 || L->block == 32) &&
                                tiles_per_split - last_tiles >= 2;
         if (in_kernel) {
             a.k_new = k_new; a.v_new = v_new; a.new_stride_b = new_stride_b; a.new_stride_h = new_stride_h;

@@ -68,12 +68,13 @@ __device__ __forceinline__ int slot_channel(int x) { return (x < 4) ? 2 * x : 2 
 
 // N = block size, HG = groups of four query heads per KV head (G <= 4*HG).
 // grid = (n_splits, H_kv, B), block = 256 (four wavefronts).
-template <int N, int HG>
+// PL = bf16 limbs of a probability: 2 (16 bits, enough for 16-bit outputs) or 3 (24 bits, fp32 outputs).
+template <int N, int HG, int PL>
 __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt) {
     constexpr int NB = kD / N;
     constexpr int NH = HG * 4;
     __shared__ float q_s[NH][kD];                               // scaled, permuted queries
-    __shared__ __align__(16) uint16_t p_s[kWaves][HG][2][4][kSuper];   // probabilities, bf16 hi/lo limbs
+    __shared__ __align__(16) uint16_t p_s[kWaves][HG][PL][4][kSuper];  // probabilities, bf16 limbs
     __shared__ float o_s[kWaves][NH][kD];                       // per-wavefront outputs for the merge
     __shared__ float ml_s[kWaves][NH][2];
 
@@ -243,10 +244,17 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
             for (int u = 0; u < 4; ++u) {
                 const float pw = exp2f(s[u] - m_ref);
                 const __bf16 ph = (__bf16)pw;
-                const __bf16 pl = (__bf16)(pw - (float)ph);
-                psum += (float)ph + (float)pl;
+                const float r1 = pw - (float)ph;
+                const __bf16 pl = (__bf16)r1;
                 p_s[wave][hg][0][kg][16 * u + j] = __builtin_bit_cast(unsigned short, ph);
                 p_s[wave][hg][1][kg][16 * u + j] = __builtin_bit_cast(unsigned short, pl);
+                if (PL == 3) {
+                    const __bf16 p3 = (__bf16)(r1 - (float)pl);
+                    p_s[wave][hg][PL - 1][kg][16 * u + j] = __builtin_bit_cast(unsigned short, p3);
+                    psum += ((float)ph + (float)pl) + (float)p3;
+                } else {
+                    psum += (float)ph + (float)pl;
+                }
             }
             l_run[hg] = l_run[hg] * alpha + psum;                   // per-lane partial; summed at the end
             m_run[hg] = m_new;
@@ -284,18 +292,23 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
             }
 #pragma unroll
             for (int hg = 0; hg < HG; ++hg) {
-                // probabilities of tokens 16u + 4kg .. +3 for this lane's row (head, parity, limb)
-                const uint2 pp = *(const uint2*)&p_s[wave][hg][a_limb][a_head][16 * u + 4 * kg];
-                uint32_t ar[4];
-                ar[0] = __builtin_amdgcn_perm(pp.x, pp.x, sel_even);
-                ar[1] = __builtin_amdgcn_perm(pp.x, pp.x, sel_odd);
-                ar[2] = __builtin_amdgcn_perm(pp.y, pp.y, sel_even);
-                ar[3] = __builtin_amdgcn_perm(pp.y, pp.y, sel_odd);
-                const bf16x8 ap = __builtin_bit_cast(bf16x8, u32x4{ar[0], ar[1], ar[2], ar[3]});
+                // probabilities of tokens 16u + 4kg .. +3 for this lane's row (head, parity, limb); a third
+                // limb takes a second round with that limb in the rows of limb 0 and zeros in the others
 #pragma unroll
-                for (int m = 0; m < 4; ++m) {
-                    const bf16x8 bv = join(vv[0].p[m], vv[1].p[m], vv[2].p[m], vv[3].p[m]);
-                    o_acc[hg][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ap, bv, o_acc[hg][m], 0, 0, 0);
+                for (int round = 0; round < (PL == 3 ? 2 : 1); ++round) {
+                    uint2 pp = *(const uint2*)&p_s[wave][hg][round == 0 ? a_limb : PL - 1][a_head][16 * u + 4 * kg];
+                    if (round == 1 && a_limb == 1) pp = make_uint2(0u, 0u);
+                    uint32_t ar[4];
+                    ar[0] = __builtin_amdgcn_perm(pp.x, pp.x, sel_even);
+                    ar[1] = __builtin_amdgcn_perm(pp.x, pp.x, sel_odd);
+                    ar[2] = __builtin_amdgcn_perm(pp.y, pp.y, sel_even);
+                    ar[3] = __builtin_amdgcn_perm(pp.y, pp.y, sel_odd);
+                    const bf16x8 ap = __builtin_bit_cast(bf16x8, u32x4{ar[0], ar[1], ar[2], ar[3]});
+#pragma unroll
+                    for (int m = 0; m < 4; ++m) {
+                        const bf16x8 bv = join(vv[0].p[m], vv[1].p[m], vv[2].p[m], vv[3].p[m]);
+                        o_acc[hg][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ap, bv, o_acc[hg][m], 0, 0, 0);
+                    }
                 }
             }
         }
@@ -887,14 +900,26 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
     }
 }
 
-// Blocks of 16 and 32 go through the LDS pipeline, blocks of 64 and 128 through the register-staged pass.
+// 16-bit I/O: blocks of 16 and 32 go through the LDS pipeline, blocks of 64 and 128 through the
+// register-staged pass with two probability limbs.  fp32 I/O: the register-staged pass with three
+// probability limbs and the three-limb bf16 query for every block size (the FP8 query limbs of the LDS
+// pipeline carry 16 bits, too few for the 1e-5 bar).
 template <int HG>
 hipError_t launch_n(const DecodeArgs& a, int dt, int block, dim3 grid, hipStream_t s) {
+    if (dt == KVBFP_F32) {
+        switch (block) {
+            case 16: decode_split_mfma_p4<16, HG, 3><<<grid, 256, 0, s>>>(a, dt); break;
+            case 32: decode_split_mfma_p4<32, HG, 3><<<grid, 256, 0, s>>>(a, dt); break;
+            case 64: decode_split_mfma_p4<64, HG, 3><<<grid, 256, 0, s>>>(a, dt); break;
+            default: decode_split_mfma_p4<128, HG, 3><<<grid, 256, 0, s>>>(a, dt); break;
+        }
+        return hipGetLastError();
+    }
     switch (block) {
         case 16: decode_split_lds_p4<16, HG><<<grid, 256, 0, s>>>(a, dt); break;
         case 32: decode_split_lds_p4<32, HG><<<grid, 256, 0, s>>>(a, dt); break;
-        case 64: decode_split_mfma_p4<64, HG><<<grid, 256, 0, s>>>(a, dt); break;
-        default: decode_split_mfma_p4<128, HG><<<grid, 256, 0, s>>>(a, dt); break;
+        case 64: decode_split_mfma_p4<64, HG, 2><<<grid, 256, 0, s>>>(a, dt); break;
+        default: decode_split_mfma_p4<128, HG, 2><<<grid, 256, 0, s>>>(a, dt); break;
     }
     return hipGetLastError();
 }

@@ -69,12 +69,13 @@ __device__ __forceinline__ Pieces unpack4(uint32_t w, float s_hi, float s_lo) {
 
 // N = block size, HG = groups of four query heads per KV head (G <= 4*HG).
 // grid = (n_splits, H_kv, B), block = 256 (four wavefronts).
-template <int N, int HG>
+// PL = bf16 limbs of a probability: 2 (16 bits, enough for 16-bit outputs) or 3 (24 bits, fp32 outputs).
+template <int N, int HG, int PL>
 __global__ __launch_bounds__(256) void decode_split_mfma_p8(DecodeArgs a, int dt) {
     constexpr int NB = kD / N;
     constexpr int NH = HG * 4;
     __shared__ float q_s[NH][kD];                               // scaled, permuted queries
-    __shared__ __align__(16) uint16_t p_s[kWaves][HG][2][4][kSuper];   // probabilities, bf16 hi/lo limbs
+    __shared__ __align__(16) uint16_t p_s[kWaves][HG][PL][4][kSuper];  // probabilities, bf16 limbs
     __shared__ float o_s[kWaves][NH][kD];                       // per-wavefront outputs for the merge
     __shared__ float ml_s[kWaves][NH][2];
 
@@ -234,10 +235,17 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p8(DecodeArgs a, int dt
             for (int u = 0; u < 4; ++u) {
                 const float pw = exp2f(s[u] - m_ref);
                 const __bf16 ph = (__bf16)pw;
-                const __bf16 pl = (__bf16)(pw - (float)ph);
-                psum += (float)ph + (float)pl;
+                const float r1 = pw - (float)ph;
+                const __bf16 pl = (__bf16)r1;
                 p_s[wave][hg][0][kg][16 * u + j] = __builtin_bit_cast(unsigned short, ph);
                 p_s[wave][hg][1][kg][16 * u + j] = __builtin_bit_cast(unsigned short, pl);
+                if (PL == 3) {
+                    const __bf16 p3 = (__bf16)(r1 - (float)pl);
+                    p_s[wave][hg][PL - 1][kg][16 * u + j] = __builtin_bit_cast(unsigned short, p3);
+                    psum += ((float)ph + (float)pl) + (float)p3;
+                } else {
+                    psum += (float)ph + (float)pl;
+                }
             }
             l_run[hg] = l_run[hg] * alpha + psum;                   // per-lane partial; summed at the end
             m_run[hg] = m_new;
@@ -268,8 +276,12 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p8(DecodeArgs a, int dt
             }
 #pragma unroll
             for (int hg = 0; hg < HG; ++hg) {
-                // probabilities of tokens 16u + 4kg .. +3 for this lane's row (head, parity, limb)
-                const uint2 pp = *(const uint2*)&p_s[wave][hg][a_limb][a_head][16 * u + 4 * kg];
+                // probabilities of tokens 16u + 4kg .. +3 for this lane's row (head, parity, limb); a third
+                // limb takes a second round with that limb in the rows of limb 0 and zeros in the others
+#pragma unroll
+                for (int round = 0; round < (PL == 3 ? 2 : 1); ++round) {
+                uint2 pp = *(const uint2*)&p_s[wave][hg][round == 0 ? a_limb : PL - 1][a_head][16 * u + 4 * kg];
+                if (round == 1 && a_limb == 1) pp = make_uint2(0u, 0u);
                 uint32_t ar[4];
                 ar[0] = __builtin_amdgcn_perm(pp.x, pp.x, sel_even);
                 ar[1] = __builtin_amdgcn_perm(pp.x, pp.x, sel_odd);
@@ -285,6 +297,7 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p8(DecodeArgs a, int dt
                 o_acc[hg][2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ap, join(vb[0].l01, vb[1].l01, vb[2].l01, vb[3].l01), o_acc[hg][2], 0, 0, 0);
                 o_acc[hg][3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ap, join(vb[0].h23, vb[1].h23, vb[2].h23, vb[3].h23), o_acc[hg][3], 0, 0, 0);
                 o_acc[hg][3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ap, join(vb[0].l23, vb[1].l23, vb[2].l23, vb[3].l23), o_acc[hg][3], 0, 0, 0);
+                }
             }
         }
         // the next tile overwrites the probability buffer
@@ -348,13 +361,13 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p8(DecodeArgs a, int dt
     }
 }
 
-template <int HG>
+template <int HG, int PL>
 hipError_t launch_n(const DecodeArgs& a, int dt, int block, dim3 grid, hipStream_t s) {
     switch (block) {
-        case 16: decode_split_mfma_p8<16, HG><<<grid, 256, 0, s>>>(a, dt); break;
-        case 32: decode_split_mfma_p8<32, HG><<<grid, 256, 0, s>>>(a, dt); break;
-        case 64: decode_split_mfma_p8<64, HG><<<grid, 256, 0, s>>>(a, dt); break;
-        default: decode_split_mfma_p8<128, HG><<<grid, 256, 0, s>>>(a, dt); break;
+        case 16: decode_split_mfma_p8<16, HG, PL><<<grid, 256, 0, s>>>(a, dt); break;
+        case 32: decode_split_mfma_p8<32, HG, PL><<<grid, 256, 0, s>>>(a, dt); break;
+        case 64: decode_split_mfma_p8<64, HG, PL><<<grid, 256, 0, s>>>(a, dt); break;
+        default: decode_split_mfma_p8<128, HG, PL><<<grid, 256, 0, s>>>(a, dt); break;
     }
     return hipGetLastError();
 }
@@ -365,8 +378,9 @@ namespace kvbfp {
 
 hipError_t launch_decode_split_mfma_p8(const DecodeArgs& a, int dtype, int block, int batch, hipStream_t s) {
     const dim3 grid((unsigned)a.n_splits, (unsigned)a.H_kv, (unsigned)batch);
-    if (a.g_cnt <= 4) return launch_n<1>(a, dtype, block, grid, s);
-    return launch_n<2>(a, dtype, block, grid, s);
+    // fp32 outputs take three probability limbs (24 bits), 16-bit outputs two
+    if (dtype == KVBFP_F32) return a.g_cnt <= 4 ? launch_n<1, 3>(a, dtype, block, grid, s) : launch_n<2, 3>(a, dtype, block, grid, s);
+    return a.g_cnt <= 4 ? launch_n<1, 2>(a, dtype, block, grid, s) : launch_n<2, 2>(a, dtype, block, grid, s);
 }
 
 }  // namespace kvbfp

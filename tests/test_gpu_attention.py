@@ -74,6 +74,17 @@ def test_query_cast_to_bfp_matches_oracle(dtype, p, n, G, qbits):
         assert (plain.double().cpu() - got.double().cpu()).norm() > 1e-2 * got.double().cpu().norm()
 
 
+@pytest.mark.parametrize("p,n", [(4, 16), (4, 32), (4, 128), (8, 16), (8, 64)])
+@pytest.mark.parametrize("G", [7, 8, 12])
+def test_fp32_io_with_wide_groups(p, n, G):
+    # fp32 I/O on the matrix cores: three bf16 limbs for the query and for the probabilities, two head
+    # groups per workgroup (G > 4) and a second launch over the heads beyond the eighth (G = 12); long
+    # enough for several splits, with the second sequence ending inside the first tile
+    k, v, q, pk, pv = make_small(torch.float32, B=2, S=1500, Hkv=2, G=G, seed=90 + G)
+    got, want = run_both(k, v, q, n, p, [1500, 131], 128 ** -0.5, pk, pv)
+    assert_attention_close(got, want, torch.float32, "p=%d n=%d G=%d" % (p, n, G))
+
+
 @pytest.mark.parametrize("p", [4, 8])
 @pytest.mark.parametrize("G", [2, 3, 5, 8, 9, 16, 24, 32, 40])
 def test_group_sizes_and_no_permutation(G, p):
