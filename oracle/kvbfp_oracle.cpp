@@ -323,6 +323,134 @@ int kvo_decode_attention(int32_t B, int32_t Hkv, int32_t Hq, int32_t D, int32_t 
     return 0;
 }
 
+// ---------------------------------------------------------------------------
+// Rotary embeddings in the reordered channel order (Sec. II-D, Eq. (RoFreq); Alg. 1 step 5).
+//
+// In the original channel order the rotation of a row x at token index m is
+//     (R x)[c] = x[c] cos(m Theta[c]) + s[c] x[i[c]] sin(m Theta[c]),
+// with, for the paper's ordering (pairs of consecutive channels, pair_layout 0)
+//     Theta = [th_0, th_0, th_1, th_1, ...],  i = [1, 0, 3, 2, ...],  s = [-1, +1, -1, +1, ...],
+// and for the half-split ordering of the open-source Llama code (footnote of Sec. III, pair_layout 1)
+//     Theta = [th_0 .. th_{D/2-1}, th_0 .. th_{D/2-1}],  i[c] = (c + D/2) mod D,  s = [-1 x D/2, +1 x D/2].
+// Alg. 1 step 5 applies the head's permutation to the three vectors: position j of the reordered row
+// holds original channel perm[j], so Theta'[j] = Theta[perm[j]], s'[j] = s[perm[j]], and the partner
+// of position j is the position that holds channel i[perm[j]]: i'[j] = perm^{-1}[ i[perm[j]] ].
+//   theta      : float [D/2]
+//   perm       : int32 [n_heads][D]  (gather convention, as everywhere here)
+//   theta_out  : float [n_heads][D];  partner_out : int32 [n_heads][D];  sign_out : float [n_heads][D]
+// ---------------------------------------------------------------------------
+int kvo_permute_rope(int32_t D, int32_t n_heads, int32_t pair_layout, const float* theta,
+                     const int32_t* perm, float* theta_out, int32_t* partner_out, float* sign_out) {
+    if (D <= 0 || D % 2 != 0 || n_heads <= 0 || !theta || !perm || !theta_out || !partner_out || !sign_out)
+        return -1;
+    if (pair_layout != 0 && pair_layout != 1) return -1;
+    std::vector<float> Theta(D), sgn(D);
+    std::vector<int> partner(D), inv(D);
+    for (int c = 0; c < D; ++c) {
+        if (pair_layout == 0) {
+            Theta[c] = theta[c / 2];
+            partner[c] = (c % 2 == 0) ? c + 1 : c - 1;
+            sgn[c] = (c % 2 == 0) ? -1.0f : 1.0f;
+        } else {
+            Theta[c] = theta[c % (D / 2)];
+            partner[c] = (c + D / 2) % D;
+            sgn[c] = (c < D / 2) ? -1.0f : 1.0f;
+        }
+    }
+    for (int h = 0; h < n_heads; ++h) {
+        const int32_t* pi = perm + (int64_t)h * D;
+        std::fill(inv.begin(), inv.end(), -1);
+        for (int j = 0; j < D; ++j) {
+            if (pi[j] < 0 || pi[j] >= D || inv[pi[j]] != -1) return -1;   // not a permutation
+            inv[pi[j]] = j;
+        }
+        for (int j = 0; j < D; ++j) {
+            theta_out[(int64_t)h * D + j] = Theta[pi[j]];
+            sign_out[(int64_t)h * D + j] = sgn[pi[j]];
+            partner_out[(int64_t)h * D + j] = inv[partner[pi[j]]];
+        }
+    }
+    return 0;
+}
+
+// ---------------------------------------------------------------------------
+// Decode attention over a cache whose keys were stored BEFORE the rotary embedding (Sec. III, last
+// paragraph of the algorithm's description: the keys are fetched from the cache, the correctly
+// ordered rotary embedding is applied to them, then the product with pi(q) is taken).
+// Per cached token t of a sequence (token index m = t), in the cache's channel order:
+//     k_rot[j] = k'[j] cos(m Theta'[j]) + s'[j] k'[i'[j]] sin(m Theta'[j])
+// with (Theta', i', s') of the token's kv-head as kvo_permute_rope returns them; the angle is the
+// product of the integer m and the fp32 value Theta'[j], taken in double.  Everything else is
+// kvo_decode_attention: q is used as given (already rotated at its own position by the caller),
+// gathered through perm_k if that is given.
+// ---------------------------------------------------------------------------
+int kvo_decode_attention_rope(int32_t B, int32_t Hkv, int32_t Hq, int32_t D, int32_t n, int32_t p,
+                              int64_t S_max,
+                              const uint8_t* k_mant, const uint8_t* k_exp,
+                              const uint8_t* v_mant, const uint8_t* v_exp,
+                              const float* q, const int64_t* seq_len, double softmax_scale,
+                              const int32_t* perm_k, const int32_t* perm_v,
+                              const float* rope_theta, const int32_t* rope_partner, const float* rope_sign,
+                              double* out) {
+    if (!k_mant || !k_exp || !v_mant || !v_exp || !q || !seq_len || !out) return -1;
+    if (!rope_theta || !rope_partner || !rope_sign) return -1;
+    if (B <= 0 || Hkv <= 0 || Hq <= 0 || Hq % Hkv != 0) return -1;
+    if (!bfp_params_ok(D, n, p)) return -1;
+    for (int64_t i = 0; i < (int64_t)Hkv * D; ++i)
+        if (rope_partner[i] < 0 || rope_partner[i] >= D) return -1;
+    RoundingGuard guard;
+    const int G = Hq / Hkv;
+    const int NB = D / n;
+    const int64_t row_bytes = (int64_t)D * p / 8;
+    std::vector<double> qp(D), o(D), kraw(D), krot(D);
+    std::vector<double> s;
+    for (int b = 0; b < B; ++b) {
+        const int64_t L = seq_len[b];
+        if (L < 0 || L > S_max) return -1;
+        s.assign((size_t)L, 0.0);
+        for (int h = 0; h < Hq; ++h) {
+            const int g = h / G;
+            const float* qrow = q + ((int64_t)b * Hq + h) * D;
+            double* orow = out + ((int64_t)b * Hq + h) * D;
+            const int32_t* pk = perm_k ? perm_k + (int64_t)g * D : nullptr;
+            const int32_t* pv = perm_v ? perm_v + (int64_t)g * D : nullptr;
+            const float* th = rope_theta + (int64_t)g * D;
+            const int32_t* pa = rope_partner + (int64_t)g * D;
+            const float* sg = rope_sign + (int64_t)g * D;
+            for (int j = 0; j < D; ++j) qp[j] = (double)qrow[pk ? pk[j] : j];
+            for (int j = 0; j < D; ++j) orow[j] = 0.0;
+            if (L == 0) continue;
+            const int64_t base = ((int64_t)b * Hkv + g) * S_max;
+            double m = -std::numeric_limits<double>::infinity();
+            for (int64_t t = 0; t < L; ++t) {
+                const uint8_t* mrow = k_mant + (base + t) * row_bytes;
+                const uint8_t* erow = k_exp + (base + t) * NB;
+                for (int j = 0; j < D; ++j) kraw[j] = decode_code(load_code(mrow, j, p), erow[j / n], p);
+                for (int j = 0; j < D; ++j) {
+                    const double ang = (double)t * (double)th[j];
+                    krot[j] = kraw[j] * std::cos(ang) + (double)sg[j] * kraw[pa[j]] * std::sin(ang);
+                }
+                double acc = 0.0;
+                for (int j = 0; j < D; ++j) acc += qp[j] * krot[j];
+                s[(size_t)t] = softmax_scale * acc;
+                m = std::max(m, s[(size_t)t]);
+            }
+            double denom = 0.0;
+            for (int j = 0; j < D; ++j) o[j] = 0.0;
+            for (int64_t t = 0; t < L; ++t) {
+                const double w = std::exp(s[(size_t)t] - m);
+                denom += w;
+                const uint8_t* mrow = v_mant + (base + t) * row_bytes;
+                const uint8_t* erow = v_exp + (base + t) * NB;
+                for (int j = 0; j < D; ++j)
+                    o[j] += w * decode_code(load_code(mrow, j, p), erow[j / n], p);
+            }
+            for (int j = 0; j < D; ++j) orow[pv ? pv[j] : j] = o[j] / denom;
+        }
+    }
+    return 0;
+}
+
 // Scores only (softmax_scale * q'.K^T) for one (b, h): used by invariance pins.
 int kvo_scores(int32_t D, int32_t n, int32_t p, const uint8_t* k_mant, const uint8_t* k_exp,
                int64_t L, const double* q_perm, double softmax_scale, double* s_out) {

@@ -34,7 +34,8 @@ def lib():
         build()
         _lib = C.CDLL(_SO)
         for name in ("kvo_calibrate_perm", "kvo_permute_weights", "kvo_quantize_append",
-                     "kvo_dequantize", "kvo_decode_attention", "kvo_scores"):
+                     "kvo_dequantize", "kvo_decode_attention", "kvo_scores", "kvo_permute_rope",
+                     "kvo_decode_attention_rope"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -159,6 +160,58 @@ def decode_attention(k_mant, k_exp, v_mant, v_exp, D, n, p, q, seq_len, softmax_
                                     C.c_int32(q_mant_bits), _p(out, C.c_double))
     if rc != 0:
         raise ValueError("kvo_decode_attention rc=%d" % rc)
+    return out
+
+
+def permute_rope(theta, perm, pair_layout=0):
+    """Alg. 1 step 5.  theta: float32 [D/2]; perm: int32 [n_heads][D]; pair_layout 0 = consecutive
+    pairs (Eq. (RoFreq)), 1 = half-split (footnote of Sec. III).
+    -> (theta' float32 [n_heads][D], partner' int32 [n_heads][D], sign' float32 [n_heads][D])."""
+    theta = _f32(theta)
+    perm = np.ascontiguousarray(perm, dtype=np.int32)
+    n_heads, D = perm.shape
+    assert theta.shape == (D // 2,)
+    th = np.empty((n_heads, D), dtype=np.float32)
+    pa = np.empty((n_heads, D), dtype=np.int32)
+    sg = np.empty((n_heads, D), dtype=np.float32)
+    rc = lib().kvo_permute_rope(C.c_int32(D), C.c_int32(n_heads), C.c_int32(pair_layout), _p(theta, C.c_float),
+                                _p(perm, C.c_int32), _p(th, C.c_float), _p(pa, C.c_int32), _p(sg, C.c_float))
+    if rc != 0:
+        raise ValueError("kvo_permute_rope rc=%d" % rc)
+    return th, pa, sg
+
+
+def decode_attention_rope(k_mant, k_exp, v_mant, v_exp, D, n, p, q, seq_len, softmax_scale,
+                          rope_theta, rope_partner, rope_sign, perm_k=None, perm_v=None):
+    """Keys cached before the rotary embedding, rotated at read with the reordered parameters of
+    permute_rope.  q: float32 [B][Hq][D] (already rotated) -> float64 [B][Hq][D]."""
+    q = _f32(q)
+    B, Hq, Dq = q.shape
+    Bc, Hkv, S_max, _ = k_mant.shape
+    assert Bc == B and Dq == D
+    for a in (k_mant, k_exp, v_mant, v_exp):
+        assert a.flags.c_contiguous and a.dtype == np.uint8
+    seq_len = np.ascontiguousarray(np.broadcast_to(np.asarray(seq_len, dtype=np.int64), (B,)))
+    if perm_k is not None:
+        perm_k = np.ascontiguousarray(perm_k, dtype=np.int32)
+    if perm_v is not None:
+        perm_v = np.ascontiguousarray(perm_v, dtype=np.int32)
+    rope_theta = _f32(rope_theta)
+    rope_sign = _f32(rope_sign)
+    rope_partner = np.ascontiguousarray(rope_partner, dtype=np.int32)
+    assert rope_theta.shape == (Hkv, D) and rope_partner.shape == (Hkv, D) and rope_sign.shape == (Hkv, D)
+    out = np.empty((B, Hq, D), dtype=np.float64)
+    rc = lib().kvo_decode_attention_rope(C.c_int32(B), C.c_int32(Hkv), C.c_int32(Hq), C.c_int32(D),
+                                         C.c_int32(n), C.c_int32(p), C.c_int64(S_max),
+                                         _p(k_mant, C.c_uint8), _p(k_exp, C.c_uint8),
+                                         _p(v_mant, C.c_uint8), _p(v_exp, C.c_uint8),
+                                         _p(q, C.c_float), _p(seq_len, C.c_int64),
+                                         C.c_double(float(softmax_scale)),
+                                         _p(perm_k, C.c_int32), _p(perm_v, C.c_int32),
+                                         _p(rope_theta, C.c_float), _p(rope_partner, C.c_int32),
+                                         _p(rope_sign, C.c_float), _p(out, C.c_double))
+    if rc != 0:
+        raise ValueError("kvo_decode_attention_rope rc=%d" % rc)
     return out
 
 
