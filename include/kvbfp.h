@@ -227,6 +227,50 @@ int kvbfp_decode_attention_multi(const kvbfp_layout* layout, const kvbfp_cache* 
                                  int32_t q_mant_bits, void* out, void* workspace,
                                  size_t workspace_bytes, void* hip_stream);
 
+/* Rotary embeddings under the reorder, parameter side (Sec. II-D; Alg. 1 step 5).  HOST.
+ * In the original channel order a row x at token index m is rotated as
+ *     (R x)[c] = x[c] cos(m Theta[c]) + s[c] x[i[c]] sin(m Theta[c])
+ * where channels come in pairs that share one frequency: KVBFP_ROPE_PAIRS_ADJACENT pairs channels
+ * (2k, 2k+1) (the ordering of Sec. II-D: Theta = [th_0, th_0, th_1, th_1, ..], i = [1, 0, 3, 2, ..],
+ * s = [-1, +1, -1, +1, ..]); KVBFP_ROPE_PAIRS_HALF_SPLIT pairs (k, k + head_dim/2) (the ordering of the
+ * open-source Llama code named in the footnote of Sec. III).  The call applies each head's
+ * permutation to the three vectors, for rows that are stored in the reordered order:
+ *     theta_out[h][j] = Theta[perm[h][j]],  sign_out[h][j] = s[perm[h][j]],
+ *     partner_out[h][j] = the POSITION in the reordered row of channel i[perm[h][j]].
+ *   theta : HOST float [head_dim/2];  perm : HOST int32 [n_heads][head_dim] (gather convention)
+ *   theta_out, sign_out : HOST float [n_heads][head_dim];  partner_out : HOST int32 [n_heads][head_dim]
+ * Errors: INVALID_ARG (NULL, odd head_dim, unknown layout, perm row not a permutation). */
+typedef enum { KVBFP_ROPE_PAIRS_ADJACENT = 0, KVBFP_ROPE_PAIRS_HALF_SPLIT = 1 } kvbfp_rope_pairs;
+int kvbfp_permute_rope(const float* theta, kvbfp_rope_pairs pairs, int32_t n_heads, int32_t head_dim,
+                       const int32_t* perm, float* theta_out, int32_t* partner_out, float* sign_out);
+
+/* Decode attention over keys that were cached BEFORE the rotary embedding (Sec. III: the keys are
+ * fetched from the cache, the correctly ordered rotary embedding is applied, then the product with
+ * pi(q) is taken; Alg. 1 step 5).  DEVICE, async unless kernel_ms is given.
+ * As kvbfp_decode_attention, except that the key of token t of a sequence enters the score as
+ *     k_rot[j] = k'[j] cos(t Theta'[j]) + s'[j] k'[i'[j]] sin(t Theta'[j])      (k' = the cached row)
+ * with the token index t = its position in the cache and the angle t * Theta'[j] taken exactly (the
+ * kernel builds its sine/cosine tables in double precision).  q is used as given: the caller rotates the
+ * query at its own token index, in whatever order it keeps it (perm_k gathers it as usual).
+ *   rope_theta, rope_sign : DEVICE float [n_kv_heads][head_dim];  rope_partner : DEVICE int32, same shape:
+ *       what kvbfp_permute_rope returns for perm_k (identity permutation if the rows were never
+ *       reordered).  The kernel relies on their structure: partner is an involution without fixed
+ *       points, and a position and its partner have equal theta and opposite signs; other contents
+ *       are memory-safe with an unspecified result.
+ *   kernel_ms : HOST float[2] or NULL.  Non-NULL: the call waits for its kernels and returns the
+ *       durations of the split pass and of the combine pass in milliseconds (HIP events).
+ * One query token per sequence, query in its input type.  The rotation costs vector arithmetic per
+ * cached key element that the plain path does not have; this pass is several times slower than
+ * kvbfp_decode_attention on the same cache (a cache of already rotated keys, reordered at append time,
+ * needs none of it).
+ * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP. */
+int kvbfp_decode_attention_rope(const kvbfp_layout* layout, const kvbfp_cache* cache, int32_t n_q_heads,
+                                const void* q, kvbfp_dtype dtype, const int32_t* seq_len_dev,
+                                int64_t max_len, float softmax_scale, const int32_t* perm_k,
+                                const int32_t* perm_v, const float* rope_theta, const int32_t* rope_partner,
+                                const float* rope_sign, void* out, void* workspace, size_t workspace_bytes,
+                                void* hip_stream, float* kernel_ms);
+
 /* DEVICE, SYNCHRONOUS, for measurement.  Enqueues exactly the launches of
  * kvbfp_decode_attention_qbfp (Sec. III; same arguments, same result in `out`) with HIP events
  * recorded on `hip_stream` before the split pass, between the two passes and after the combine

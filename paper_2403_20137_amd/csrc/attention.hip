@@ -57,11 +57,27 @@ __device__ __forceinline__ float code_value(uint32_t c) {
 // four per workgroup; larger groups re-read the cache).  The fallback for what the matrix-core passes
 // do not take: more than 32 (virtual) heads per kv-head, planes that are not 16-byte aligned.
 // grid = (n_splits, H_kv * ceil(G/4), B), block = 256.
-template <int P>
+//
+// ROPE: the keys were cached before the rotary embedding and are rotated here, at token index m = their
+// position in the cache (Sec. III; Alg. 1 step 5 for the reordered parameters Theta', i', s').  With
+// k_rot[j] = k'[j] cos(m Theta'[j]) + s'[j] k'[i'[j]] sin(m Theta'[j]) and the structure of the three
+// vectors (i' an involution, equal Theta' and opposite s' within a pair) the score is
+//     q'.k_rot = sum_j k'[j] ( q'[j] cos(m Theta'[j]) + q''[j] sin(m Theta'[j]) ),  q''[j] = -s'[j] q'[i'[j]],
+// so no cached element has to meet its partner.  m = tile0 + r: the tile's angle is folded into the two
+// query vectors once per tile (A = q' ch + q'' sh, B = q'' ch - q' sh), and the phasor of the offset r
+// = 16 a + b inside the tile is the product of two 16-entry tables per channel.  Tables and the tile
+// phasor are built in double precision from the fp32 frequencies (one sincos of Theta'[j], one of
+// t_begin Theta'[j], then complex products), so that angles of 10^5 radians keep fp32 accuracy.
+template <int P, bool ROPE>
 __global__ __launch_bounds__(kTile) void decode_split_generic(DecodeArgs a, int dt) {
     constexpr int kRowBytes = kD * P / 8;
     constexpr int kRowVec = kRowBytes / 16;
-    __shared__ float qs[kHeadsPerWg][kD];
+    __shared__ float qs[kHeadsPerWg][kD];                      // ROPE: A of the current tile
+    __shared__ float qb[ROPE ? kHeadsPerWg : 1][kD];           // B of the current tile
+    __shared__ float q1[ROPE ? kHeadsPerWg : 1][kD];           // q'
+    __shared__ float q2[ROPE ? kHeadsPerWg : 1][kD];           // q''
+    __shared__ float2 ph_lo[ROPE ? kD : 1][16];                // (cos, sin)(b Theta'[j]),    b < 16
+    __shared__ float2 ph_mid[ROPE ? kD : 1][16];               // (cos, sin)(16 a Theta'[j]), a < 16
     __shared__ float sc[kHeadsPerWg][kTile];
     __shared__ float alpha_s[kHeadsPerWg];
     __shared__ float ored[4][kHeadsPerWg][kD];
@@ -112,6 +128,41 @@ __global__ __launch_bounds__(kTile) void decode_split_generic(DecodeArgs a, int 
         __syncthreads();
     }
 
+    double hi_c = 1.0, hi_s = 0.0, step_c = 1.0, step_s = 0.0;   // thread j < D: phasor of tile0 Theta'[j], of 256 Theta'[j]
+    if (ROPE) {
+        for (int i = tid; i < kHeadsPerWg * kD; i += kTile) (&q1[0][0])[i] = (&qs[0][0])[i];
+        __syncthreads();
+        for (int i = tid; i < kHeadsPerWg * kD; i += kTile) {
+            const int g = i / kD, j = i % kD;
+            q2[g][j] = -a.rope_sign[kvh * kD + j] * q1[g][a.rope_partner[kvh * kD + j] & (kD - 1)];
+        }
+        if (tid < kD) {
+            const double th = (double)a.rope_theta[kvh * kD + tid];
+            double c1, s1;
+            sincos(th, &s1, &c1);
+            double pc = 1.0, ps = 0.0;
+            for (int k = 0; k < 16; ++k) {
+                ph_lo[tid][k] = make_float2((float)pc, (float)ps);
+                const double nc = pc * c1 - ps * s1;
+                ps = ps * c1 + pc * s1;
+                pc = nc;
+            }
+            const double c16 = pc, s16 = ps;
+            pc = 1.0;
+            ps = 0.0;
+            for (int k = 0; k < 16; ++k) {
+                ph_mid[tid][k] = make_float2((float)pc, (float)ps);
+                const double nc = pc * c16 - ps * s16;
+                ps = ps * c16 + pc * s16;
+                pc = nc;
+            }
+            step_c = pc;
+            step_s = ps;
+            sincos((double)t_begin * th, &hi_s, &hi_c);
+        }
+        __syncthreads();
+    }
+
     const int64_t base = ((int64_t)b * a.H_kv + kvh) * a.max_seq;
     float m_run = -INFINITY, l_run = 0.f;          // wave g owns head g0+g (uniform per wave)
     float o[kHeadsPerWg][2];
@@ -120,6 +171,21 @@ __global__ __launch_bounds__(kTile) void decode_split_generic(DecodeArgs a, int 
     const int cp = lane;                            // V phase: channels 2cp, 2cp+1
 
     for (int64_t tile0 = t_begin; tile0 < t_end; tile0 += kTile) {
+        if (ROPE) {   // the queries of this tile (nobody reads qs / qb between the end of a tile and here)
+            if (tid < kD) {
+                const float ch = (float)hi_c, sh = (float)hi_s;
+#pragma unroll
+                for (int g = 0; g < kHeadsPerWg; ++g) {
+                    const float x = q1[g][tid], y = q2[g][tid];
+                    qs[g][tid] = x * ch + y * sh;
+                    qb[g][tid] = y * ch - x * sh;
+                }
+                const double nc = hi_c * step_c - hi_s * step_s;
+                hi_s = hi_s * step_c + hi_c * step_s;
+                hi_c = nc;
+            }
+            __syncthreads();
+        }
         // ---- scores: one cached token per thread
         const int64_t t = tile0 + tid;
         float s[kHeadsPerWg];
@@ -152,12 +218,29 @@ __global__ __launch_bounds__(kTile) void decode_split_generic(DecodeArgs a, int 
 #pragma unroll
                     for (int i = 0; i < 16; ++i) v[i] = code_value<8>((w[i / 4] >> (8 * (i % 4))) & 0xFFu);
                 }
+                if (ROPE) {
+                    float acc[kHeadsPerWg];
 #pragma unroll
-                for (int g = 0; g < kHeadsPerWg; ++g) {
-                    float acc = 0.f;
+                    for (int g = 0; g < kHeadsPerWg; ++g) acc[g] = 0.f;
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) acc = fmaf(qs[g][c * 16 + i], v[i], acc);
-                    s[g] = fmaf(scale, acc, s[g]);
+                    for (int i = 0; i < 16; ++i) {
+                        const int j = c * 16 + i;
+                        const float2 pm = ph_mid[j][tid >> 4], pl = ph_lo[j][tid & 15];
+                        const float kc = v[i] * (pm.x * pl.x - pm.y * pl.y);     // k' cos((16a + b) Theta')
+                        const float ks = v[i] * (pm.y * pl.x + pm.x * pl.y);     // k' sin(...)
+#pragma unroll
+                        for (int g = 0; g < kHeadsPerWg; ++g) acc[g] = fmaf(qs[g][j], kc, fmaf(qb[g][j], ks, acc[g]));
+                    }
+#pragma unroll
+                    for (int g = 0; g < kHeadsPerWg; ++g) s[g] = fmaf(scale, acc[g], s[g]);
+                } else {
+#pragma unroll
+                    for (int g = 0; g < kHeadsPerWg; ++g) {
+                        float acc = 0.f;
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) acc = fmaf(qs[g][c * 16 + i], v[i], acc);
+                        s[g] = fmaf(scale, acc, s[g]);
+                    }
                 }
             }
         }
@@ -373,8 +456,14 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
                        const int32_t* perm_v, int32_t q_mant_bits, void* out, void* workspace,
                        size_t workspace_bytes, void* hip_stream, float* kernel_ms = nullptr,
                        const void* k_new = nullptr, const void* v_new = nullptr, int64_t new_stride_b = 0,
-                       int64_t new_stride_h = 0, int32_t n_q_tokens = 1) {
+                       int64_t new_stride_h = 0, int32_t n_q_tokens = 1, const float* rope_theta = nullptr,
+                       const int32_t* rope_partner = nullptr, const float* rope_sign = nullptr) {
     clear_error();
+    const bool rope = rope_theta || rope_partner || rope_sign;
+    if (rope && !(rope_theta && rope_partner && rope_sign))
+        return fail(KVBFP_ERR_INVALID_ARG, "decode_attention_rope: rope_theta, rope_partner and rope_sign are all needed");
+    if (rope && (q_mant_bits != 0 || n_q_tokens != 1 || k_new || v_new))
+        return fail(KVBFP_ERR_UNSUPPORTED, "decode_attention_rope: plain single-token decode only");
     if (n_q_tokens < 1 || n_q_tokens > 64)
         return fail(KVBFP_ERR_INVALID_ARG, "decode_attention: n_q_tokens = %d (1..64)", n_q_tokens);
     if (q_mant_bits != 0 && q_mant_bits != 4 && q_mant_bits != 8)
@@ -415,6 +504,7 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
     a.n_q_tokens = n_q_tokens; a.real_Hq = real_heads; a.real_G = real_heads / L->n_kv_heads;
     a.q_mant_bits = q_mant_bits;
     a.scale_log2e = softmax_scale * 1.4426950408889634f;
+    a.rope_theta = rope_theta; a.rope_partner = rope_partner; a.rope_sign = rope_sign;
 
     hipStream_t s = (hipStream_t)hip_stream;
     const int gg = (a.G + kHeadsPerWg - 1) / kHeadsPerWg;
@@ -422,9 +512,9 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
         return fail(KVBFP_ERR_UNSUPPORTED, "decode_attention: too many heads for the grid");
     const dim3 grid1((unsigned)sp.n_splits, (unsigned)(a.H_kv * gg), (unsigned)L->batch);
     auto aligned16 = [](const void* p) { return ((uintptr_t)p & 15u) == 0; };
-    // Matrix-core passes: up to 8 (virtual) heads of a kv-head per launch; larger groups take
+    // Matrix-core passes (not with the rotation at read): up to 8 (virtual) heads of a kv-head per launch; larger groups take
     // several launches over head subsets (the cache is then read once per subset), up to 4 of them.
-    const bool fast = a.G <= 32 && aligned16(a.k_mant) &&
+    const bool fast = !rope && a.G <= 32 && aligned16(a.k_mant) &&
                       aligned16(a.v_mant) && aligned16(a.k_exp) && aligned16(a.v_exp);
     a.g_base = 0;
     a.g_cnt = a.G < 8 ? a.G : 8;
@@ -468,8 +558,13 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
             a.k_new = a.v_new = nullptr;       // the current token is cast by the first launch only
         }
     } else {
-        if (L->mant_bits == 4) decode_split_generic<4><<<grid1, kTile, 0, s>>>(a, (int)dtype);
-        else decode_split_generic<8><<<grid1, kTile, 0, s>>>(a, (int)dtype);
+        if (rope) {
+            if (L->mant_bits == 4) decode_split_generic<4, true><<<grid1, kTile, 0, s>>>(a, (int)dtype);
+            else decode_split_generic<8, true><<<grid1, kTile, 0, s>>>(a, (int)dtype);
+        } else {
+            if (L->mant_bits == 4) decode_split_generic<4, false><<<grid1, kTile, 0, s>>>(a, (int)dtype);
+            else decode_split_generic<8, false><<<grid1, kTile, 0, s>>>(a, (int)dtype);
+        }
         err = hipGetLastError();
     }
     if (kernel_ms) (void)hipEventRecord(ev[1], s);
@@ -532,6 +627,21 @@ int kvbfp_decode_attention_multi(const kvbfp_layout* L, const kvbfp_cache* cache
     return decode_impl(L, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v,
                        q_mant_bits, out, workspace, workspace_bytes, hip_stream, nullptr, nullptr, nullptr, 0, 0,
                        n_q_tokens);
+}
+
+int kvbfp_decode_attention_rope(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t n_q_heads,
+                                const void* q, kvbfp_dtype dtype, const int32_t* seq_len_dev,
+                                int64_t max_len, float softmax_scale, const int32_t* perm_k,
+                                const int32_t* perm_v, const float* rope_theta, const int32_t* rope_partner,
+                                const float* rope_sign, void* out, void* workspace, size_t workspace_bytes,
+                                void* hip_stream, float* kernel_ms) {
+    if (!rope_theta || !rope_partner || !rope_sign) {
+        clear_error();
+        return fail(KVBFP_ERR_INVALID_ARG, "decode_attention_rope: rope_theta/rope_partner/rope_sign is NULL");
+    }
+    return decode_impl(L, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v, 0, out,
+                       workspace, workspace_bytes, hip_stream, kernel_ms, nullptr, nullptr, 0, 0, 1, rope_theta,
+                       rope_partner, rope_sign);
 }
 
 int kvbfp_decode_attention_profile(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t n_q_heads,

@@ -35,6 +35,11 @@ struct DecodeArgs {
     int64_t new_stride_b, new_stride_h;
     int32_t q_mant_bits;      // 0, or the mantissa bits the permuted query is cast to (block = cache block)
     float scale_log2e;
+    // Keys cached before the rotary embedding (kvbfp_decode_attention_rope): the reordered frequency,
+    // partner-position and sign vectors of Alg. 1 step 5, each [H_kv][D]; nullptr = no rotation at read.
+    const float* rope_theta;
+    const int32_t* rope_partner;
+    const float* rope_sign;
 };
 
 // Row of q / out, in units of head_dim elements, of virtual head s of kv-head kvh in batch b.
@@ -47,7 +52,7 @@ __host__ __device__ inline int hidden_tokens(const DecodeArgs& a, int s) {
     return o > 0 ? o : 0;
 }
 
-// Fast split pass for 4-bit mantissas and 16-bit I/O (decode_mfma.hip).  Returns hipSuccess after
+// Matrix-core split pass for 4-bit mantissas (decode_mfma.hip).  Returns hipSuccess after
 // enqueuing; the caller has already validated the arguments.
 hipError_t launch_decode_split_mfma(const DecodeArgs& a, int dtype, int block, int batch, hipStream_t s);
 // (a.g_cnt <= 8 heads per launch; larger groups take several launches over head subsets.)

@@ -201,4 +201,42 @@ int kvbfp_permute_weights(const void* w_in, void* w_out, kvbfp_dtype dtype, int3
     return KVBFP_OK;
 }
 
+int kvbfp_permute_rope(const float* theta, kvbfp_rope_pairs pairs, int32_t n_heads, int32_t head_dim,
+                       const int32_t* perm, float* theta_out, int32_t* partner_out, float* sign_out) {
+    clear_error();
+    if (!theta || !perm || !theta_out || !partner_out || !sign_out)
+        return fail(KVBFP_ERR_INVALID_ARG, "permute_rope: NULL pointer");
+    if (n_heads <= 0 || head_dim <= 0 || head_dim % 2 != 0)
+        return fail(KVBFP_ERR_INVALID_ARG, "permute_rope: n_heads %d, head_dim %d (positive, head_dim even)", n_heads,
+                    head_dim);
+    if (pairs != KVBFP_ROPE_PAIRS_ADJACENT && pairs != KVBFP_ROPE_PAIRS_HALF_SPLIT)
+        return fail(KVBFP_ERR_INVALID_ARG, "permute_rope: unknown pair layout %d", (int)pairs);
+    const int32_t half = head_dim / 2;
+    // channel c rotates in plane pair_of(c) as its first (sine sign -1) or second (+1) coordinate
+    auto pair_of = [&](int32_t c) { return pairs == KVBFP_ROPE_PAIRS_ADJACENT ? c >> 1 : (c < half ? c : c - half); };
+    auto is_first = [&](int32_t c) { return pairs == KVBFP_ROPE_PAIRS_ADJACENT ? (c & 1) == 0 : c < half; };
+    std::vector<int32_t> where((size_t)head_dim);       // where[c] = position of original channel c in the reordered row
+    for (int32_t h = 0; h < n_heads; ++h) {
+        const int32_t* pi = perm + (int64_t)h * head_dim;
+        std::fill(where.begin(), where.end(), -1);
+        for (int32_t j = 0; j < head_dim; ++j) {
+            if (pi[j] < 0 || pi[j] >= head_dim || where[(size_t)pi[j]] >= 0)
+                return fail(KVBFP_ERR_INVALID_ARG, "permute_rope: perm row %d is not a permutation", h);
+            where[(size_t)pi[j]] = j;
+        }
+        for (int32_t j = 0; j < head_dim; ++j) {
+            const int32_t c = pi[j], plane = pair_of(c);
+            const bool first = is_first(c);
+            int32_t mate;                                // the other coordinate of the plane, original numbering
+            if (pairs == KVBFP_ROPE_PAIRS_ADJACENT) mate = first ? c + 1 : c - 1;
+            else mate = first ? c + half : c - half;
+            const int64_t o = (int64_t)h * head_dim + j;
+            theta_out[o] = theta[plane];
+            sign_out[o] = first ? -1.0f : 1.0f;
+            partner_out[o] = where[(size_t)mate];
+        }
+    }
+    return KVBFP_OK;
+}
+
 }  // extern "C"

@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_PKG, "libkvbfp.so")
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
 F32, F16, BF16 = 0, 1, 2
 STAT_MAXABS, STAT_L2 = 0, 1
+ROPE_PAIRS_ADJACENT, ROPE_PAIRS_HALF_SPLIT = 0, 1
 
 _TORCH_DT = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
 _NP_DT = {np.dtype(np.float32): F32, np.dtype(np.float16): F16}
@@ -24,6 +25,7 @@ _NP_DT = {np.dtype(np.float32): F32, np.dtype(np.float16): F16}
 EXPORTS = ["kvbfp_cache_bytes", "kvbfp_calibrate_perm", "kvbfp_permute_weights",
            "kvbfp_quantize_append", "kvbfp_dequantize", "kvbfp_decode_workspace_bytes",
            "kvbfp_decode_attention", "kvbfp_decode_attention_qbfp", "kvbfp_append_decode_attention", "kvbfp_decode_attention_multi", "kvbfp_decode_attention_profile",
+           "kvbfp_permute_rope", "kvbfp_decode_attention_rope",
            "kvbfp_last_error", "kvbfp_version"]
 
 
@@ -64,6 +66,12 @@ def lib():
                                            C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_int32, C.c_void_p]
         l.kvbfp_permute_weights.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int32,
                                             C.c_int64, C.c_int32, C.c_void_p]
+        l.kvbfp_permute_rope.argtypes = [C.c_void_p, C.c_int, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.c_void_p]
+        l.kvbfp_decode_attention_rope.argtypes = [C.POINTER(Layout), C.POINTER(CachePtrs), C.c_int32, C.c_void_p,
+                                                  C.c_int, C.c_void_p, C.c_int64, C.c_float, C.c_void_p,
+                                                  C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                  C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         l.kvbfp_quantize_append.argtypes = [C.POINTER(Layout), C.POINTER(CachePtrs), C.c_void_p, C.c_void_p,
                                             C.c_int, C.c_int32, C.c_int64, C.c_int64, C.c_int64, C.c_int64,
                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -211,6 +219,21 @@ def permute_weights(w, n_heads, head_dim, perm, heads_per_perm=1):
     return out
 
 
+def permute_rope(theta, perm, pairs=ROPE_PAIRS_ADJACENT):
+    """HOST.  theta: float32 [head_dim/2]; perm: int32 [n_heads][head_dim].
+    Returns (theta', partner', sign') as numpy arrays [n_heads][head_dim] (float32, int32, float32)."""
+    theta = np.ascontiguousarray(theta, dtype=np.float32)
+    perm = np.ascontiguousarray(perm, dtype=np.int32)
+    if perm.ndim != 2 or theta.shape != (perm.shape[1] // 2,):
+        raise ValueError("theta must be [head_dim/2] and perm [n_heads][head_dim]")
+    th = np.empty(perm.shape, dtype=np.float32)
+    pa = np.empty(perm.shape, dtype=np.int32)
+    sg = np.empty(perm.shape, dtype=np.float32)
+    _check(lib().kvbfp_permute_rope(theta.ctypes.data, int(pairs), perm.shape[0], perm.shape[1], perm.ctypes.data,
+                                    th.ctypes.data, pa.ctypes.data, sg.ctypes.data))
+    return th, pa, sg
+
+
 def quantize_append(cache: Cache, k_new, v_new, pos0=0, pos_dev=None, perm_k=None, perm_v=None,
                     stream=None):
     """DEVICE, async.  k_new / v_new: [batch][n_new][n_kv_heads][head_dim] device tensors (strided in
@@ -292,6 +315,28 @@ def decode_attention_qbfp(cache: Cache, q, max_len, softmax_scale, q_mant_bits, 
                                              int(q_mant_bits), _dev_ptr(out), _dev_ptr(workspace),
                                              workspace.numel(), _stream_ptr(stream)))
     return out
+
+
+def decode_attention_rope(cache: Cache, q, max_len, softmax_scale, rope_theta, rope_partner, rope_sign,
+                          seq_len_dev=None, perm_k=None, perm_v=None, out=None, workspace=None, stream=None,
+                          profile=False):
+    """DEVICE, async (synchronous with profile=True).  Keys cached before the rotary embedding, rotated at
+    read; rope_theta / rope_partner / rope_sign: device tensors [n_kv_heads][head_dim] (float32, int32,
+    float32) as permute_rope returns them.  Returns `out`, or (out, split_ms, combine_ms) with profile."""
+    L, n_q_heads, out, workspace = _decode_common(cache, q, max_len, out, workspace)
+    for t in (rope_theta, rope_partner, rope_sign):
+        if t is None or tuple(t.shape) != (L.n_kv_heads, L.head_dim) or not t.is_contiguous():
+            raise ValueError("rope_theta/rope_partner/rope_sign must be contiguous [n_kv_heads][head_dim] device tensors")
+    ptrs = cache.ptrs
+    ms = (C.c_float * 2)() if profile else None
+    _check(lib().kvbfp_decode_attention_rope(C.byref(L), C.byref(ptrs), n_q_heads, _dev_ptr(q),
+                                             _TORCH_DT[q.dtype], _dev_ptr(seq_len_dev, torch.int32),
+                                             int(max_len), float(softmax_scale),
+                                             _dev_ptr(perm_k, torch.int32), _dev_ptr(perm_v, torch.int32),
+                                             _dev_ptr(rope_theta, torch.float32), _dev_ptr(rope_partner, torch.int32),
+                                             _dev_ptr(rope_sign, torch.float32), _dev_ptr(out), _dev_ptr(workspace),
+                                             workspace.numel(), _stream_ptr(stream), ms))
+    return (out, float(ms[0]), float(ms[1])) if profile else out
 
 
 def decode_attention_profile(cache: Cache, q, max_len, softmax_scale, q_mant_bits=0, seq_len_dev=None, perm_k=None,

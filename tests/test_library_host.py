@@ -72,6 +72,25 @@ def test_calibrate_from_weights_and_permute_weights_equal_oracle():
     assert np.array_equal(synth.to_f32_numpy(out), want)
 
 
+@pytest.mark.parametrize("pairs", [0, 1])
+def test_permute_rope_equals_oracle(pairs):
+    # Alg. 1 step 5 on the host: frequencies, partner positions and sine signs in the reordered order
+    rng = np.random.default_rng(8 + pairs)
+    theta = rng.uniform(1e-4, 1.0, 64).astype(np.float32)
+    perm = np.stack([rng.permutation(128) for _ in range(5)]).astype(np.int32)
+    got = kvbfp.permute_rope(theta, perm, pairs)
+    want = O.permute_rope(theta, perm, pairs)
+    for g, w in zip(got, want):
+        assert g.dtype == w.dtype and np.array_equal(g, w)
+    bad = perm.copy()
+    bad[2, 0] = bad[2, 1]
+    with pytest.raises(kvbfp.KvbfpError) as ei:
+        kvbfp.permute_rope(theta, bad, pairs)
+    assert ei.value.status == kvbfp.ERR_INVALID_ARG and "permutation" in str(ei.value)
+    with pytest.raises(kvbfp.KvbfpError):
+        kvbfp.permute_rope(theta, perm, 2)
+
+
 def test_host_argument_errors():
     w = np.zeros((256, 4), dtype=np.float32)
     perm = np.tile(np.arange(128, dtype=np.int32), (2, 1))
@@ -141,6 +160,14 @@ def test_device_calls_reject_bad_arguments_before_launching():
     assert daq(5) == kvbfp.ERR_INVALID_ARG and "q_mant_bits" in kvbfp.last_error()
     assert daq(-8) == kvbfp.ERR_INVALID_ARG
     assert daq(8, n_q=3) == kvbfp.ERR_INVALID_ARG      # the other checks are those of the plain call
+    def dar(theta=fake, partner=fake, sign=fake):
+        return lib.kvbfp_decode_attention_rope(C.byref(good), C.byref(ptrs), 4, fake, kvbfp.BF16, None, 64, 0.1,
+                                               None, None, theta, partner, sign, fake, None, 0, None, None)
+
+    assert dar(theta=None) == kvbfp.ERR_INVALID_ARG and "rope" in kvbfp.last_error()
+    assert dar(partner=None) == kvbfp.ERR_INVALID_ARG
+    assert dar(sign=None) == kvbfp.ERR_INVALID_ARG
+    assert dar() == kvbfp.ERR_WORKSPACE                # complete arguments reach the workspace check
     assert da(ws=None) == kvbfp.ERR_WORKSPACE
     assert da(ws_bytes=16) == kvbfp.ERR_WORKSPACE and "workspace" in kvbfp.last_error()
     assert da(ws=C.c_void_p(0x1010)) == kvbfp.ERR_WORKSPACE
