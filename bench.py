@@ -348,6 +348,15 @@ def main():
                 e1.record()
             torch.cuda.synchronize()
             result["decode_4_query_tokens_us_median"] = float(np.median([a.elapsed_time(b) for a, b in ev][2:]) * 1e3)
+            # the same caches read as if their keys had been stored before the rotary embedding: rotation at
+            # read with the reordered parameters (Alg. 1 step 5), split pass only, HIP events inside the call
+            theta = (10000.0 ** (-np.arange(w.head_dim // 2, dtype=np.float64) / (w.head_dim // 2))).astype(np.float32)
+            rp = [torch.from_numpy(x).to(ring.q.device)
+                  for x in kvbfp.permute_rope(theta, ring.perm_k_host, kvbfp.ROPE_PAIRS_HALF_SPLIT)]
+            rope_us = [kvbfp.decode_attention_rope(ring.caches[i % len(ring.caches)], ring.q, ring.S_max, ring.scale, *rp,
+                                                   perm_k=ring.perm_k, perm_v=ring.perm_v, out=ring.out,
+                                                   workspace=ring.workspace, profile=True)[1] * 1e3 for i in range(8)]
+            result["decode_split_us_median_rotary_at_read"] = float(np.median(rope_us[2:]))
             result["quantize_append_bulk"] = bulk_quantize_rate()
         except Exception as e:      # reported, never hidden
             result["quantize_append_bulk"] = {"error": repr(e)}
