@@ -14,11 +14,11 @@
 // notes of the repository):
 //   * shared exponent: the finest power-of-two scale for which plain
 //     round-to-nearest-even of the block's largest magnitude still fits the
-//     symmetric mantissa range (Sec. II-B: "exponent based on the largest
-//     absolute value", mantissas in [-(2^(p-1)-1), 2^(p-1)-1]);
+//     symmetric mantissa range (Sec. II-B derives the exponent from the block's
+//     largest magnitude; mantissas in [-(2^(p-1)-1), 2^(p-1)-1]);
 //   * stored exponent byte E = e + 127 + (p-2), E = 0 reserved for an all-zero
 //     block, b = 8 exponent bits (Sec. I: BFP12/BFP16 use an 8-bit exponent);
-//   * rounding: to nearest, ties to even (Sec. IV: "rounding to the nearest");
+//   * rounding: to nearest (Sec. IV names no tie rule), ties to even;
 //   * mantissa code: sign-magnitude, zero always encoded with sign 0;
 //   * permutation: stable ascending argsort of the per-channel statistic
 //     (Alg. 1 steps 1-2; Sec. III allows either order, a flag selects
