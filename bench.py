@@ -44,10 +44,11 @@ def algorithmic_bytes(w: synth.Workload, seq_after_append: int):
 class LayerRing:
     """`n_layers` packed caches of one workload, filled by bulk quantize_append on the GPU."""
 
-    def __init__(self, w: synth.Workload, n_layers: int, device="cuda"):
+    def __init__(self, w: synth.Workload, n_layers: int, device="cuda", capacity_pad=0):
         self.w = w
-        self.S_max = w.seq + 1
-        self.layout = kvbfp.make_layout(w.head_dim, w.block, w.mant_bits, w.n_kv_heads, w.batch, self.S_max)
+        self.S_max = w.seq + 1                      # tokens per sequence after the step's append
+        self.capacity = self.S_max + capacity_pad   # tokens a sequence's region can hold (layout.max_seq)
+        self.layout = kvbfp.make_layout(w.head_dim, w.block, w.mant_bits, w.n_kv_heads, w.batch, self.capacity)
         kg = synth.outlier_gains(synth.BASE_SEED, synth.TID_K_GAIN, w.n_kv_heads, w.head_dim, w.outlier_count, w.outlier_gain)
         vg = synth.outlier_gains(synth.BASE_SEED, synth.TID_V_GAIN, w.n_kv_heads, w.head_dim, w.outlier_count, w.outlier_gain)
         self.k_gain, self.v_gain = kg, vg
@@ -103,6 +104,37 @@ class LayerRing:
             self.caches[i % len(self.caches)], self.q, self.S_max, self.scale, q_mant_bits, perm_k=self.perm_k,
             perm_v=self.perm_v, out=self.out, workspace=self.workspace)
         return split_ms * 1e3, combine_ms * 1e3
+
+
+def paged_split_us(ring: LayerRing, page=256, n_pools=4):
+    """The workload's caches again as pools of 256-token pages, every sequence's pages scattered over its
+    pool by a seeded shuffle; split pass of kvbfp_decode_attention_paged, HIP events inside the call,
+    cycling over pools that together exceed the last-level cache."""
+    w = ring.w
+    per_seq = (ring.S_max + page - 1) // page
+    pool_layout = kvbfp.make_layout(w.head_dim, w.block, w.mant_bits, w.n_kv_heads, w.batch * per_seq, page)
+    rng = np.random.default_rng(synth.BASE_SEED)
+    pools = []
+    for layer in range(n_pools):
+        pool = kvbfp.alloc_cache(pool_layout, ring.q.device)
+        table = torch.as_tensor(rng.permutation(w.batch * per_seq).reshape(w.batch, per_seq).astype(np.int32),
+                                device=ring.q.device)
+        k = synth.kv_rows(w.batch, w.seq, w.n_kv_heads, w.head_dim, w.dtype, ring.k_gain, synth.BASE_SEED + layer, synth.TID_K,
+                          ring.q.device)
+        v = synth.kv_rows(w.batch, w.seq, w.n_kv_heads, w.head_dim, w.dtype, ring.v_gain, synth.BASE_SEED + layer, synth.TID_V,
+                          ring.q.device)
+        kvbfp.quantize_append_paged(pool, table, k, v, pos0=0, perm_k=ring.perm_k, perm_v=ring.perm_v)
+        kvbfp.quantize_append_paged(pool, table, ring.k_new, ring.v_new, pos_dev=ring.pos, perm_k=ring.perm_k,
+                                    perm_v=ring.perm_v)
+        torch.cuda.synchronize()
+        del k, v
+        pools.append((pool, table))
+    us = []
+    for i in range(12):
+        pool, table = pools[i % n_pools]
+        us.append(kvbfp.decode_attention_paged(pool, table, ring.q, ring.S_max, ring.scale, perm_k=ring.perm_k,
+                                               perm_v=ring.perm_v, out=ring.out, profile=True)[1] * 1e3)
+    return float(np.median(us[2:]))
 
 
 def capture_step_graphs(ring: LayerRing):
@@ -237,6 +269,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default=HEADLINE, choices=sorted(synth.WORKLOADS))
     ap.add_argument("--layers", type=int, default=0, help="distinct layer caches in the ring (0 = enough for >= 1 GB)")
+    ap.add_argument("--capacity-pad", type=int, default=0,
+                    help="tokens of spare capacity per sequence region beyond the workload's length")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of graph replays")
@@ -267,7 +301,7 @@ def main():
     w = synth.WORKLOADS[args.workload]
     n_layers = args.layers or max(2, -(-1_100_000_000 // w.cache_bytes(w.seq + 1)))
     n_layers = min(n_layers, 64)
-    ring = LayerRing(w, n_layers)
+    ring = LayerRing(w, n_layers, capacity_pad=args.capacity_pad)
     dec_bytes, app_bytes = algorithmic_bytes(w, w.seq + 1)
     ring.fused = not args.separate_calls
     eager_sec_per_step, app_us, dec_us = time_steps(ring, args.steps, args.warmup)
@@ -357,6 +391,7 @@ def main():
                                                    perm_k=ring.perm_k, perm_v=ring.perm_v, out=ring.out,
                                                    workspace=ring.workspace, profile=True)[1] * 1e3 for i in range(8)]
             result["decode_split_us_median_rotary_at_read"] = float(np.median(rope_us[2:]))
+            result["decode_split_us_median_paged_256"] = paged_split_us(ring)
             result["quantize_append_bulk"] = bulk_quantize_rate()
         except Exception as e:      # reported, never hidden
             result["quantize_append_bulk"] = {"error": repr(e)}

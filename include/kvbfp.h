@@ -271,6 +271,36 @@ int kvbfp_decode_attention_rope(const kvbfp_layout* layout, const kvbfp_cache* c
                                 const float* rope_sign, void* out, void* workspace, size_t workspace_bytes,
                                 void* hip_stream, float* kernel_ms);
 
+/* Paged caches.  The four planes form a POOL of pages instead of one region per sequence:
+ *   pool layout : batch = number of pages in the pool, max_seq = tokens per page (a power of two, at
+ *                 least 256, so that no 256-token tile of the kernels straddles two pages); planes
+ *                 [n_pages][n_kv_heads][page_tokens][..] as kvbfp_cache_bytes(pool) sizes them.
+ *   block_table : DEVICE int32 [batch][table_stride]; tokens [i * page_tokens, (i + 1) * page_tokens) of
+ *                 sequence b live in page block_table[b * table_stride + i].  Entries that no token of the
+ *                 call touches are not read.  Page numbers cannot be checked on the host: the kernels
+ *                 clamp them to [0, n_pages) (memory-safe, result then unspecified).
+ *   batch       : number of sequences (the pool layout's batch field counts pages).
+ * A sequence can hold table_stride * page_tokens tokens; positions, lengths and max_len are checked
+ * against that.  Everything else (arguments, results, errors) is as in the call without `_paged`:
+ * the same bytes land in the same rows of a page that the contiguous call writes into a sequence's
+ * region, and attention returns the same values.
+ * kvbfp_decode_attention_paged takes q_mant_bits like kvbfp_decode_attention_qbfp (0 = query as given)
+ * and kernel_ms like kvbfp_decode_attention_rope (NULL = asynchronous).
+ * Errors: as the plain calls, plus UNSUPPORTED for a page size that is not a power of two >= 256. */
+int kvbfp_quantize_append_paged(const kvbfp_layout* pool, const kvbfp_cache* cache, const int32_t* block_table,
+                                int64_t table_stride, int32_t batch, const void* k_new, const void* v_new,
+                                kvbfp_dtype dtype, int32_t n_new, int64_t stride_b, int64_t stride_t,
+                                int64_t stride_h, int64_t pos0, const int32_t* pos_dev, const int32_t* perm_k,
+                                const int32_t* perm_v, void* hip_stream);
+size_t kvbfp_decode_workspace_bytes_paged(const kvbfp_layout* pool, int64_t table_stride, int32_t batch,
+                                          int32_t n_q_heads, int64_t max_len);
+int kvbfp_decode_attention_paged(const kvbfp_layout* pool, const kvbfp_cache* cache, const int32_t* block_table,
+                                 int64_t table_stride, int32_t batch, int32_t n_q_heads, const void* q,
+                                 kvbfp_dtype dtype, const int32_t* seq_len_dev, int64_t max_len,
+                                 float softmax_scale, const int32_t* perm_k, const int32_t* perm_v,
+                                 int32_t q_mant_bits, void* out, void* workspace, size_t workspace_bytes,
+                                 void* hip_stream, float* kernel_ms);
+
 /* DEVICE, SYNCHRONOUS, for measurement.  Enqueues exactly the launches of
  * kvbfp_decode_attention_qbfp (Sec. III; same arguments, same result in `out`) with HIP events
  * recorded on `hip_stream` before the split pass, between the two passes and after the combine

@@ -163,7 +163,6 @@ __global__ __launch_bounds__(kTile) void decode_split_generic(DecodeArgs a, int 
         __syncthreads();
     }
 
-    const int64_t base = ((int64_t)b * a.H_kv + kvh) * a.max_seq;
     float m_run = -INFINITY, l_run = 0.f;          // wave g owns head g0+g (uniform per wave)
     float o[kHeadsPerWg][2];
 #pragma unroll
@@ -186,6 +185,8 @@ __global__ __launch_bounds__(kTile) void decode_split_generic(DecodeArgs a, int 
             }
             __syncthreads();
         }
+        // rows of the planes are addressed as base + token; a paged cache has one base per 256-token tile
+        const int64_t base = kvbfp::cache_row(a, b, kvh, tile0) - tile0;
         // ---- scores: one cached token per thread
         const int64_t t = tile0 + tid;
         float s[kHeadsPerWg];
@@ -457,8 +458,17 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
                        size_t workspace_bytes, void* hip_stream, float* kernel_ms = nullptr,
                        const void* k_new = nullptr, const void* v_new = nullptr, int64_t new_stride_b = 0,
                        int64_t new_stride_h = 0, int32_t n_q_tokens = 1, const float* rope_theta = nullptr,
-                       const int32_t* rope_partner = nullptr, const float* rope_sign = nullptr) {
+                       const int32_t* rope_partner = nullptr, const float* rope_sign = nullptr,
+                       const Paging* paging = nullptr) {
     clear_error();
+    kvbfp_layout logical;
+    const kvbfp_layout* pool = L;
+    if (paging) {
+        if (k_new || v_new || n_q_tokens != 1)
+            return fail(KVBFP_ERR_UNSUPPORTED, "decode_attention_paged: plain single-token decode only");
+        if (int rc = check_paging(pool, *paging, &logical)) return rc;
+        L = &logical;             // from here on: what the sequences look like
+    }
     const bool rope = rope_theta || rope_partner || rope_sign;
     if (rope && !(rope_theta && rope_partner && rope_sign))
         return fail(KVBFP_ERR_INVALID_ARG, "decode_attention_rope: rope_theta, rope_partner and rope_sign are all needed");
@@ -505,6 +515,11 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
     a.q_mant_bits = q_mant_bits;
     a.scale_log2e = softmax_scale * 1.4426950408889634f;
     a.rope_theta = rope_theta; a.rope_partner = rope_partner; a.rope_sign = rope_sign;
+    if (paging) {
+        a.block_table = paging->block_table; a.table_stride = paging->table_stride;
+        a.n_pages = pool->batch;
+        a.log2_page = log2_exact((int)pool->max_seq);
+    }
 
     hipStream_t s = (hipStream_t)hip_stream;
     const int gg = (a.G + kHeadsPerWg - 1) / kHeadsPerWg;
@@ -525,13 +540,9 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
         if (n_q_tokens != 1) return fail(KVBFP_ERR_UNSUPPORTED, "append_decode_attention: one query token only");
         if (new_stride_b < 0 || new_stride_h < 0)
             return fail(KVBFP_ERR_INVALID_ARG, "append_decode_attention: negative stride");
-        // Inside the split pass the cast delays the workgroup that holds the last token by a few
-        // microseconds; that is free only if its split is at least two 256-token tiles shorter than
-        // the others (otherwise the cache-write kernel goes first, as in the two separate calls).
-        const int64_t tiles = (max_len + kTokenTile - 1) / kTokenTile, tiles_per_split = sp.split_len / kTokenTile;
-        const int64_t last_tiles = tiles - (int64_t)(sp.n_splits - 1) * tiles_per_split;
-        const bool in_kernel = fast && dtype != KVBFP_F32 && L->mant_bits == 4 && (L->block == 16 || L->block == 32) &&
-                               tiles_per_split - last_tiles >= 2;
+        // Inside the LDS split pass the cast is done by the one wavefront that reads the new row, off
+        // the path of everybody else; elsewhere the cache-write kernel goes first, as in the two calls.
+        const bool in_kernel = fast && dtype != KVBFP_F32 && L->mant_bits == 4 && (L->block == 16 || L->block == 32);
         if (in_kernel) {
             a.k_new = k_new; a.v_new = v_new; a.new_stride_b = new_stride_b; a.new_stride_h = new_stride_h;
         } else {
@@ -642,6 +653,28 @@ int kvbfp_decode_attention_rope(const kvbfp_layout* L, const kvbfp_cache* cache,
     return decode_impl(L, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v, 0, out,
                        workspace, workspace_bytes, hip_stream, kernel_ms, nullptr, nullptr, 0, 0, 1, rope_theta,
                        rope_partner, rope_sign);
+}
+
+size_t kvbfp_decode_workspace_bytes_paged(const kvbfp_layout* pool, int64_t table_stride, int32_t batch,
+                                          int32_t n_q_heads, int64_t max_len) {
+    clear_error();
+    static const int32_t placeholder = 0;      // only its address is looked at here
+    const Paging pg{&placeholder, table_stride, batch};
+    kvbfp_layout logical;
+    if (check_paging(pool, pg, &logical) != KVBFP_OK) return 0;
+    return kvbfp_decode_workspace_bytes(&logical, n_q_heads, max_len);
+}
+
+int kvbfp_decode_attention_paged(const kvbfp_layout* pool, const kvbfp_cache* cache, const int32_t* block_table,
+                                 int64_t table_stride, int32_t batch, int32_t n_q_heads, const void* q,
+                                 kvbfp_dtype dtype, const int32_t* seq_len_dev, int64_t max_len,
+                                 float softmax_scale, const int32_t* perm_k, const int32_t* perm_v,
+                                 int32_t q_mant_bits, void* out, void* workspace, size_t workspace_bytes,
+                                 void* hip_stream, float* kernel_ms) {
+    const Paging pg{block_table, table_stride, batch};
+    return decode_impl(pool, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v,
+                       q_mant_bits, out, workspace, workspace_bytes, hip_stream, kernel_ms, nullptr, nullptr, 0, 0, 1,
+                       nullptr, nullptr, nullptr, &pg);
 }
 
 int kvbfp_decode_attention_profile(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t n_q_heads,

@@ -40,7 +40,23 @@ struct DecodeArgs {
     const float* rope_theta;
     const int32_t* rope_partner;
     const float* rope_sign;
+    // Paged cache (kvbfp_decode_attention_paged): the planes are a pool [n_pages][H_kv][2^log2_page][..]
+    // and tokens [i 2^log2_page, (i+1) 2^log2_page) of sequence b live in page
+    // block_table[b * table_stride + i]; nullptr = one contiguous region of max_seq tokens per sequence.
+    // A page holds a multiple of 256 tokens, so a tile of the split kernels never straddles two pages.
+    const int32_t* block_table;
+    int64_t table_stride;
+    int32_t log2_page, n_pages;
 };
+
+// Row index (one row = one token of one kv-head) of token t of sequence b in the four planes.  Page
+// numbers come from device memory the host cannot check: they are clamped to the pool.
+__device__ inline int64_t cache_row(const DecodeArgs& a, int b, int kvh, int64_t t) {
+    if (!a.block_table) return ((int64_t)b * a.H_kv + kvh) * a.max_seq + t;
+    int page = a.block_table[(int64_t)b * a.table_stride + (t >> a.log2_page)];
+    page = page < 0 ? 0 : (page >= a.n_pages ? a.n_pages - 1 : page);
+    return (((int64_t)page * a.H_kv + kvh) << a.log2_page) + (t & (((int64_t)1 << a.log2_page) - 1));
+}
 
 // Row of q / out, in units of head_dim elements, of virtual head s of kv-head kvh in batch b.
 __host__ __device__ inline int64_t query_row(const DecodeArgs& a, int b, int kvh, int s) {

@@ -149,7 +149,9 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
 
     // Plane bases of this (batch, kv-head) are wave-uniform (scalar registers); everything inside
     // the split is addressed with 32-bit offsets from them.
-    const int64_t base = ((int64_t)b * a.H_kv + kvh) * a.max_seq + t_begin;
+    // (Paged cache: the bases are those of the pool and every tile looks up its page.)
+    const bool paged = a.block_table != nullptr;
+    const int64_t base = paged ? 0 : ((int64_t)b * a.H_kv + kvh) * a.max_seq + t_begin;
     const uint8_t* __restrict__ k_mant = a.k_mant + base * 64;
     const uint8_t* __restrict__ v_mant = a.v_mant + base * 64;
     const uint8_t* __restrict__ k_exp = a.k_exp + base * NB;
@@ -184,10 +186,11 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
     // clamping or masking; otherwise rows are clamped to the last cached token and masked.
     auto tile = [&](const int T0, auto full_tag) {
         constexpr bool FULL = decltype(full_tag)::value;
-        const uint8_t* __restrict__ kp = k_mant + (size_t)T0 * 64;
-        const uint8_t* __restrict__ vp = v_mant + (size_t)T0 * 64;
-        const uint8_t* __restrict__ kep = k_exp + (size_t)T0 * NB;
-        const uint8_t* __restrict__ vep = v_exp + (size_t)T0 * NB;
+        const size_t R0 = paged ? (size_t)kvbfp::cache_row(a, b, kvh, t_begin + T0) : (size_t)T0;   // wave-uniform
+        const uint8_t* __restrict__ kp = k_mant + R0 * 64;
+        const uint8_t* __restrict__ vp = v_mant + R0 * 64;
+        const uint8_t* __restrict__ kep = k_exp + R0 * NB;
+        const uint8_t* __restrict__ vep = v_exp + R0 * NB;
         const int left = n_tok - T0;                 // cached tokens from T0 on (>= 1)
 
         // ---------------- scores of 64 tokens
@@ -449,7 +452,9 @@ __device__ __forceinline__ void lds_read_val_stage(uint32_t m_addr, uint32_t e_a
 
 constexpr int vmcnt_imm(int n) { return (n & 0xF) | (0x7 << 4) | (0xF << 8) | ((n >> 4) << 14); }
 
-template <int N, int HG>
+// PAGED: the planes are a pool of pages and every 64-token tile looks up its page (a scalar load, issued a
+// tile ahead of the requests that need it); a separate instantiation, so the contiguous case is untouched.
+template <int N, int HG, bool PAGED>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((N == 16 && HG == 2) ? 2 : 3, 4)))
 void decode_split_lds_p4(DecodeArgs a, int dt) {
     static_assert(N == 16 || N == 32, "LDS pipeline is built for blocks of 16 or 32");
@@ -487,8 +492,12 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
 
     int64_t L = a.seq_len ? (int64_t)a.seq_len[b] : a.max_len;
     L = L < 0 ? 0 : (L > a.max_len ? a.max_len : L);
-    const int64_t t_begin = (int64_t)split * a.split_len;
-    const int64_t t_end = min(t_begin + a.split_len, L);
+    // Tiles are dealt out round-robin: split s takes the 256-token tiles s, s + n_splits, s + 2 n_splits, ...
+    // The workgroups of one (batch, kv-head) then sweep the sequence side by side instead of each
+    // streaming a distant region of its own, which the memory system serves a few percent faster, and no
+    // split is more than one tile longer than another.  "Split-relative" tokens below count from t_begin.
+    const int64_t t_begin = (int64_t)split * 256;
+    const int64_t t_end = L;
 
     if (t_begin >= t_end) {   // nothing cached in this split
         for (int i = tid; i < a.g_cnt * kD; i += 256)
@@ -502,31 +511,65 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
     }
 
     // ---- kvbfp_append_decode_attention: the current token, position L - 1, is cast and stored by the
-    // workgroup whose split holds that position, before that workgroup requests any cache bytes (its
-    // requests would otherwise pick up what was there before).  Lanes 0-7 of wavefront 0 take the key
-    // row, lanes 8-15 the value row; the rest of the wavefront runs along with zeros (the block maximum
-    // is a cross-lane reduction) and stores nothing.  __syncthreads() also waits for the stores.
-    if (a.k_new != nullptr && L - 1 >= t_begin && L - 1 < t_end) {
-        if (wave == 0) {
-            const int sub = lane & 7, which = (lane >> 3) & 1;
-            const bool live = lane < 16;
-            const void* src = which ? a.v_new : a.k_new;
-            const int32_t* pr = which ? a.perm_v : a.perm_k;
-            const int64_t off = (int64_t)b * a.new_stride_b + (int64_t)kvh * a.new_stride_h;
+    // one wavefront whose 64-token tiles include that position (nobody else ever reads the row), off
+    // everybody else's path.  Lanes 0-7 take the key row, lanes 8-15 the value row; the rest of the
+    // wavefront runs along with zeros (the block maximum is a cross-lane reduction) and stores nothing.
+    //   * The row and its permutation are requested here, ahead of the first tile, as raw bits (once
+    //     the cache streams, a round trip to memory takes several microseconds).
+    //   * After the set-up below (so that its barriers are not held up) the row is reordered through
+    //     this wavefront's part of the probability buffer, cast and stored.
+    //   * Before the wavefront requests its last tile, the one that holds the row, it waits for the
+    //     stores (new_row_stored below).
+    // If that tile is the wavefront's first, all of this happens right here instead, before the first
+    // request.
+    const bool appends = a.k_new != nullptr && (int)(((L - 1) >> 8) % a.n_splits) == split &&
+                         (int)(((L - 1) & 255) >> 6) == wave;                       // wave-uniform
+    const bool appends_first = appends && (L - 1) < t_begin + 256;
+    const int nr_sub = lane & 7, nr_which = (lane >> 3) & 1;
+    const bool nr_live = lane < 16;
+    uint32_t nr_bits[16];
+    int nr_perm[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        nr_bits[i] = 0u;
+        nr_perm[i] = nr_sub * 16 + i;
+    }
+    auto widen = [&](uint32_t h) {
+        return dt == KVBFP_F16 ? (float)__builtin_bit_cast(_Float16, (unsigned short)h) : __uint_as_float(h << 16);
+    };
+    auto store_new_row = [&](const float (&x)[16]) {
+        kvbfp::cast::encode_store<4, N>(x, nr_sub, nr_live, const_cast<uint8_t*>(nr_which ? a.v_mant : a.k_mant),
+                                        const_cast<uint8_t*>(nr_which ? a.v_exp : a.k_exp),
+                                        kvbfp::cache_row(a, b, kvh, L - 1));
+    };
+    if (appends) {
+        const uint16_t* src = (const uint16_t*)(nr_which ? a.v_new : a.k_new) + (int64_t)b * a.new_stride_b +
+                              (int64_t)kvh * a.new_stride_h;
+        const int32_t* pr = nr_which ? a.perm_v : a.perm_k;
+        if (appends_first) {      // short sequence: nothing streams yet, gather straight from memory
             float x[16];
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int c = pr ? (pr[kvh * kD + sub * 16 + i] & (kD - 1)) : (sub * 16 + i);
-                x[i] = live ? load_as_float(src, dt, off + c) : 0.f;
+                const int c = pr ? (pr[kvh * kD + nr_sub * 16 + i] & (kD - 1)) : (nr_sub * 16 + i);
+                x[i] = nr_live ? widen(src[c]) : 0.f;
             }
-            kvbfp::cast::encode_store<4, N>(x, sub, live, const_cast<uint8_t*>(which ? a.v_mant : a.k_mant),
-                                            const_cast<uint8_t*>(which ? a.v_exp : a.k_exp),
-                                            ((int64_t)b * a.H_kv + kvh) * a.max_seq + (L - 1));
+            store_new_row(x);
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            __builtin_amdgcn_sched_barrier(0);
+        } else if (nr_live) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) nr_bits[i] = src[nr_sub * 16 + i];
+            if (pr) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) nr_perm[i] = pr[kvh * kD + nr_sub * 16 + i] & (kD - 1);
+            }
         }
-        __syncthreads();
     }
 
-    const int64_t base = ((int64_t)b * a.H_kv + kvh) * a.max_seq + t_begin;
+    const int64_t base = PAGED ? 0 : ((int64_t)b * a.H_kv + kvh) * a.max_seq + t_begin;
+    // row (relative to the bases below) of the 64-token tile that starts at token T of the split
+    auto tile_row = [&](const int T) -> int64_t { return PAGED ? kvbfp::cache_row(a, b, kvh, t_begin + T) : (int64_t)T; };
     const uint8_t* __restrict__ k_mant = a.k_mant + base * 64;
     const uint8_t* __restrict__ v_mant = a.v_mant + base * 64;
     const uint8_t* __restrict__ k_exp = a.k_exp + base * NB;
@@ -552,13 +595,14 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
     // masking is needed
     const uint32_t ve_src = (uint32_t)(lane & (4 * NB - 1)) * 4u;
 
-    // Fills stage u (keys or values) with the 16 tokens starting at token t of the split.  `left` is
+    // Fills stage u (keys or values) with the 16 tokens starting at token t of the split, which is row
+    // `row` of the planes (tile_row of its tile plus its offset inside the tile).  `left` is
     // wave-uniform, so the ragged case is a scalar branch; rows past the last cached token re-read
     // that token (left - 1 may be negative: earlier rows of the split are cached too).
-    auto fill_keys = [&](const int u, const int t) {
+    auto fill_keys = [&](const int u, const int t, const int64_t row) {
         const int left = n_tok - t;
-        const uint8_t* __restrict__ mp = k_mant + (int64_t)t * 64;
-        const uint8_t* __restrict__ ep = k_exp + (int64_t)t * NB;
+        const uint8_t* __restrict__ mp = k_mant + row * 64;
+        const uint8_t* __restrict__ ep = k_exp + row * NB;
         uint8_t* const lm = wbase + kKm + u * 1024;
         uint8_t* const le = wbase + kKe + u * 256;
         if (left >= 16) {
@@ -571,10 +615,10 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
             __builtin_amdgcn_global_load_lds(KVBFP_GPTR(ep + eo), KVBFP_LPTR(le), 4, 0, 0);
         }
     };
-    auto fill_vals = [&](const int u, const int t) {
+    auto fill_vals = [&](const int u, const int t, const int64_t row) {
         const int left = n_tok - t;
-        const uint8_t* __restrict__ mp = v_mant + (int64_t)t * 64;
-        const uint8_t* __restrict__ ep = v_exp + (int64_t)t * NB;
+        const uint8_t* __restrict__ mp = v_mant + row * 64;
+        const uint8_t* __restrict__ ep = v_exp + row * NB;
         uint8_t* const lm = wbase + kVm + u * 1024;
         uint8_t* const le = wbase + kVe + u * 256;
         if (left >= 16) {
@@ -626,10 +670,11 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
     const int T_first = wave * kTileTok;
     const bool has_work = T_first < n_tok;
     if (has_work) {
+        const int64_t row0 = tile_row(T_first);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) fill_keys(u, T_first + 16 * u);
+        for (int u = 0; u < 4; ++u) fill_keys(u, T_first + 16 * u, row0 + 16 * u);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) fill_vals(u, T_first + 16 * u);
+        for (int u = 0; u < 4; ++u) fill_vals(u, T_first + 16 * u, row0 + 16 * u);
     }
 
     // ---- query operand of the score product to LDS (whole workgroup) -------------------------------
@@ -692,6 +737,17 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
         }
         lds_barrier();                                    // the buffer goes over to the probabilities
     }
+    if (appends && !appends_first) {
+        float* const row = (float*)&p_lds[wave][0] + nr_which * kD;     // [2][kD] floats: this wavefront's 1 KB
+        if (nr_live) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) row[nr_sub * 16 + i] = widen(nr_bits[i]);
+        }
+        float x[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) x[i] = nr_live ? row[nr_perm[i]] : 0.f;
+        store_new_row(x);
+    }
 
     const int a_head = j >> 2, a_par = (j >> 1) & 1, a_limb = j & 1;
     const uint32_t sel_even = a_par ? 0x01000c0cu : 0x0c0c0100u;
@@ -716,10 +772,16 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
     const uint32_t ps_rd = lds_addr(&p_lds[wave][(a_limb * 4 + a_head) * kTileTok + 4 * kg]);   // + head group and column tile
 
     if (has_work) {
-        constexpr int kStep = kWaves * kTileTok;
+        const int kStep = a.n_splits * kWaves * kTileTok;      // this workgroup's next 256-token tile
         for (int T0 = T_first; T0 < n_tok; T0 += kStep) {
             const int T1 = T0 + kStep;
             const bool more = T1 < n_tok;            // wave-uniform
+            const int64_t row1 = more ? tile_row(T1) : 0;
+            if (appends && more && T1 + kStep >= n_tok) {      // next comes the tile with the new row: its stores first
+                __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+                __builtin_amdgcn_sched_barrier(0);
+            }
             const int left = n_tok - T0;
 
             // ---------------- scores
@@ -745,7 +807,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
                         const v8i b2 = {(int)(raw[0] & 0xCCCCCCCCu), (int)(raw[1] & 0xCCCCCCCCu), (int)(raw[2] & 0xCCCCCCCCu),
                                         (int)(raw[3] & 0xCCCCCCCCu), 0, 0, 0, 0};
                         __builtin_amdgcn_sched_barrier(0);
-                        if (more) fill_keys(u, T1 + 16 * u);
+                        if (more) fill_keys(u, T1 + 16 * u, row1 + 16 * u);
                         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                         for (int hg = 0; hg < HG; ++hg) {
@@ -761,7 +823,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
                         const v8i hi1 = {0, 0, (int)(raw[2] & 0xBBBBBBBBu), (int)(raw[3] & 0xBBBBBBBBu), 0, 0, 0, 0};
                         const v8i hi2 = {0, 0, (int)(raw[2] & 0xCCCCCCCCu), (int)(raw[3] & 0xCCCCCCCCu), 0, 0, 0, 0};
                         __builtin_amdgcn_sched_barrier(0);
-                        if (more) fill_keys(u, T1 + 16 * u);
+                        if (more) fill_keys(u, T1 + 16 * u, row1 + 16 * u);
                         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                         for (int hg = 0; hg < HG; ++hg) {
@@ -822,7 +884,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
                 pp[0] = lds_read_b64<(16 * u) * 2>(ps_rd);
                 if (HG > 1) pp[HG - 1] = lds_read_b64<(2 * 4 * kTileTok + 16 * u) * 2>(ps_rd);
                 __builtin_amdgcn_sched_barrier(0);
-                if (more) fill_vals(u, T1 + 16 * u);
+                if (more) fill_vals(u, T1 + 16 * u, row1 + 16 * u);
                 __builtin_amdgcn_sched_barrier(0);
                 Unpacked vv[4];
 #pragma unroll
@@ -915,9 +977,14 @@ hipError_t launch_n(const DecodeArgs& a, int dt, int block, dim3 grid, hipStream
         }
         return hipGetLastError();
     }
+    if (a.block_table && block <= 32) {
+        if (block == 16) decode_split_lds_p4<16, HG, true><<<grid, 256, 0, s>>>(a, dt);
+        else decode_split_lds_p4<32, HG, true><<<grid, 256, 0, s>>>(a, dt);
+        return hipGetLastError();
+    }
     switch (block) {
-        case 16: decode_split_lds_p4<16, HG><<<grid, 256, 0, s>>>(a, dt); break;
-        case 32: decode_split_lds_p4<32, HG><<<grid, 256, 0, s>>>(a, dt); break;
+        case 16: decode_split_lds_p4<16, HG, false><<<grid, 256, 0, s>>>(a, dt); break;
+        case 32: decode_split_lds_p4<32, HG, false><<<grid, 256, 0, s>>>(a, dt); break;
         case 64: decode_split_mfma_p4<64, HG, 2><<<grid, 256, 0, s>>>(a, dt); break;
         default: decode_split_mfma_p4<128, HG, 2><<<grid, 256, 0, s>>>(a, dt); break;
     }

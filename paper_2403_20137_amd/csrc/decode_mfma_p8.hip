@@ -153,7 +153,9 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p8(DecodeArgs a, int dt
 
     // Plane bases of this (batch, kv-head) are wave-uniform; everything inside the split is
     // addressed with 32-bit offsets from them.
-    const int64_t base = ((int64_t)b * a.H_kv + kvh) * a.max_seq + t_begin;
+    // (Paged cache: the bases are those of the pool and every tile looks up its page.)
+    const bool paged = a.block_table != nullptr;
+    const int64_t base = paged ? 0 : ((int64_t)b * a.H_kv + kvh) * a.max_seq + t_begin;
     const uint8_t* __restrict__ k_mant = a.k_mant + base * 128;
     const uint8_t* __restrict__ v_mant = a.v_mant + base * 128;
     const uint8_t* __restrict__ k_exp = a.k_exp + base * NB;
@@ -186,10 +188,11 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p8(DecodeArgs a, int dt
     // otherwise rows are clamped to the last cached token and masked.
     auto tile = [&](const int T0, auto full_tag) {
         constexpr bool FULL = decltype(full_tag)::value;
-        const uint8_t* __restrict__ kp = k_mant + (size_t)T0 * 128;
-        const uint8_t* __restrict__ vp = v_mant + (size_t)T0 * 128;
-        const uint8_t* __restrict__ kep = k_exp + (size_t)T0 * NB;
-        const uint8_t* __restrict__ vep = v_exp + (size_t)T0 * NB;
+        const size_t R0 = paged ? (size_t)kvbfp::cache_row(a, b, kvh, t_begin + T0) : (size_t)T0;   // wave-uniform
+        const uint8_t* __restrict__ kp = k_mant + R0 * 128;
+        const uint8_t* __restrict__ vp = v_mant + R0 * 128;
+        const uint8_t* __restrict__ kep = k_exp + R0 * NB;
+        const uint8_t* __restrict__ vep = v_exp + R0 * NB;
         const int left = n_tok - T0;                 // cached tokens from T0 on (>= 1)
 
         // ---------------- scores of 64 tokens

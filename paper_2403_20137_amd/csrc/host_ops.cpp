@@ -51,6 +51,23 @@ int check_cache(const kvbfp_cache* c, bool need_k, bool need_v) {
     return KVBFP_OK;
 }
 
+int check_paging(const kvbfp_layout* pool, const Paging& pg, kvbfp_layout* logical) {
+    if (int rc = check_device_layout(pool)) return rc;
+    if (!pg.block_table) return fail(KVBFP_ERR_INVALID_ARG, "paged cache: block_table is NULL");
+    const int64_t page = pool->max_seq;
+    if (page < kTokenTile || (page & (page - 1)) != 0)
+        return fail(KVBFP_ERR_UNSUPPORTED, "paged cache: %lld tokens per page (a power of two, at least %d)",
+                    (long long)page, kTokenTile);
+    if (pg.batch <= 0 || pg.table_stride <= 0)
+        return fail(KVBFP_ERR_INVALID_ARG, "paged cache: batch %d, table_stride %lld", pg.batch, (long long)pg.table_stride);
+    if (pg.table_stride > ((int64_t)1 << 30) / page)
+        return fail(KVBFP_ERR_UNSUPPORTED, "paged cache: more than 2^30 tokens per sequence");
+    *logical = *pool;
+    logical->batch = pg.batch;
+    logical->max_seq = pg.table_stride * page;
+    return KVBFP_OK;
+}
+
 SplitPlan plan_splits(const kvbfp_layout* L, int32_t n_q_heads, int64_t max_len) {
     // Enough workgroups to cover 256 compute units a few times over, each split a whole number
     // of token tiles.

@@ -34,11 +34,24 @@ struct SplitPlan {
 constexpr int kTokenTile = 256;
 SplitPlan plan_splits(const kvbfp_layout* L, int32_t n_q_heads, int64_t max_len);
 
+// A paged cache: `pool` describes the pool of pages (batch = pages, max_seq = tokens per page, a power of
+// two and a multiple of kTokenTile); sequence b keeps tokens [i page, (i+1) page) in page
+// block_table[b * table_stride + i].
+struct Paging {
+    const int32_t* block_table;   // DEVICE int32 [batch][table_stride]
+    int64_t table_stride;
+    int32_t batch;                // sequences
+};
+// Validates pool and paging; on success *logical is the layout the sequences appear to have
+// (batch sequences of table_stride pages each).
+int check_paging(const kvbfp_layout* pool, const Paging& pg, kvbfp_layout* logical);
+
 // kvbfp_quantize_append, optionally with sequence lengths in place of positions (len_cap >= 0, see
-// quantize.hip); does not clear the error state.
+// quantize.hip) and optionally into a paged cache (L is then the pool); does not clear the error state.
 int quantize_append_impl(const kvbfp_layout* L, const kvbfp_cache* cache, const void* k_new,
                          const void* v_new, kvbfp_dtype dtype, int32_t n_new, int64_t stride_b,
                          int64_t stride_t, int64_t stride_h, int64_t pos0, const int32_t* pos_dev,
-                         int64_t len_cap, const int32_t* perm_k, const int32_t* perm_v, void* hip_stream);
+                         int64_t len_cap, const int32_t* perm_k, const int32_t* perm_v, void* hip_stream,
+                         const Paging* paging = nullptr);
 
 }  // namespace kvbfp

@@ -56,7 +56,10 @@ struct QuantArgs {
     int64_t pos0;
     const int32_t* pos_dev;
     int64_t len_cap;                         // >= 0: pos_dev holds sequence lengths, the row goes to min(max(len, 0), len_cap) - 1
-    int64_t max_seq;
+    int64_t max_seq;                         // tokens a sequence can hold (paged: pages per sequence x page)
+    const int32_t* block_table;              // paged cache: [B][table_stride], nullptr otherwise
+    int64_t table_stride;
+    int32_t log2_page, n_pages;
     int32_t H, n_new;
     uint32_t n_rows;                         // B * H * n_new, below 2^31
     FastDiv div_n_new, div_H;
@@ -95,7 +98,13 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(QuantArgs a) {
         if (a.pos_dev) pos = a.len_cap >= 0 ? min(max((int64_t)a.pos_dev[b], (int64_t)0), a.len_cap) - 1 : (int64_t)a.pos_dev[b];
         pos += t;
         live[k] = in_range && pos >= 0 && pos < a.max_seq;
-        crow[k] = ((int64_t)b * a.H + h) * a.max_seq + pos;
+        if (a.block_table) {      // page numbers cannot be checked on the host: clamped to the pool
+            int page = live[k] ? a.block_table[(int64_t)b * a.table_stride + (pos >> a.log2_page)] : 0;
+            page = page < 0 ? 0 : (page >= a.n_pages ? a.n_pages - 1 : page);
+            crow[k] = (((int64_t)page * a.H + h) << a.log2_page) + (pos & (((int64_t)1 << a.log2_page) - 1));
+        } else {
+            crow[k] = ((int64_t)b * a.H + h) * a.max_seq + pos;
+        }
         head[k] = (int32_t)h;
         srow[k] = (const uint8_t*)T.src + ((int64_t)b * a.stride_b + (int64_t)t * a.stride_t + (int64_t)h * a.stride_h) * ESZ;
         if (MODE != kElementwise) {
@@ -287,6 +296,17 @@ int kvbfp_quantize_append(const kvbfp_layout* L, const kvbfp_cache* cache, const
                                        pos_dev, -1, perm_k, perm_v, hip_stream);
 }
 
+int kvbfp_quantize_append_paged(const kvbfp_layout* pool, const kvbfp_cache* cache, const int32_t* block_table,
+                                int64_t table_stride, int32_t batch, const void* k_new, const void* v_new,
+                                kvbfp_dtype dtype, int32_t n_new, int64_t stride_b, int64_t stride_t,
+                                int64_t stride_h, int64_t pos0, const int32_t* pos_dev, const int32_t* perm_k,
+                                const int32_t* perm_v, void* hip_stream) {
+    clear_error();
+    const kvbfp::Paging pg{block_table, table_stride, batch};
+    return kvbfp::quantize_append_impl(pool, cache, k_new, v_new, dtype, n_new, stride_b, stride_t, stride_h, pos0,
+                                       pos_dev, -1, perm_k, perm_v, hip_stream, &pg);
+}
+
 }  // extern "C"
 
 // len_cap >= 0: pos_dev holds sequence lengths (clamped to [0, len_cap]) and row i of sequence b goes
@@ -295,7 +315,13 @@ int kvbfp::quantize_append_impl(const kvbfp_layout* L, const kvbfp_cache* cache,
                                 const void* v_new, kvbfp_dtype dtype, int32_t n_new, int64_t stride_b,
                                 int64_t stride_t, int64_t stride_h, int64_t pos0, const int32_t* pos_dev,
                                 int64_t len_cap, const int32_t* perm_k, const int32_t* perm_v,
-                                void* hip_stream) {
+                                void* hip_stream, const Paging* paging) {
+    kvbfp_layout logical;
+    const kvbfp_layout* pool = L;
+    if (paging) {
+        if (int rc = check_paging(pool, *paging, &logical)) return rc;
+        L = &logical;             // from here on: what the sequences look like
+    }
     if (int rc = check_device_layout(L)) return rc;
     if (int rc = check_cache(cache, k_new != nullptr, v_new != nullptr)) return rc;
     const int esz = dtype_size(dtype);
@@ -314,6 +340,12 @@ int kvbfp::quantize_append_impl(const kvbfp_layout* L, const kvbfp_cache* cache,
     if (v_new) a.t[nt++] = QuantTensor{v_new, perm_v, cache->v_mant, cache->v_exp};
     a.stride_b = stride_b; a.stride_t = stride_t; a.stride_h = stride_h;
     a.pos0 = pos0; a.pos_dev = pos_dev; a.len_cap = len_cap; a.max_seq = L->max_seq;
+    if (paging) {
+        a.block_table = paging->block_table; a.table_stride = paging->table_stride;
+        a.n_pages = pool->batch;
+        a.log2_page = 0;
+        while (((int64_t)1 << a.log2_page) < pool->max_seq) ++a.log2_page;
+    }
     a.H = L->n_kv_heads; a.n_new = n_new;
     const int64_t n_rows = (int64_t)L->batch * L->n_kv_heads * n_new;
     if (n_rows > 0x7FFFFFFF) return fail(KVBFP_ERR_UNSUPPORTED, "quantize_append: too many rows");

@@ -26,6 +26,7 @@ EXPORTS = ["kvbfp_cache_bytes", "kvbfp_calibrate_perm", "kvbfp_permute_weights",
            "kvbfp_quantize_append", "kvbfp_dequantize", "kvbfp_decode_workspace_bytes",
            "kvbfp_decode_attention", "kvbfp_decode_attention_qbfp", "kvbfp_append_decode_attention", "kvbfp_decode_attention_multi", "kvbfp_decode_attention_profile",
            "kvbfp_permute_rope", "kvbfp_decode_attention_rope",
+           "kvbfp_quantize_append_paged", "kvbfp_decode_workspace_bytes_paged", "kvbfp_decode_attention_paged",
            "kvbfp_last_error", "kvbfp_version"]
 
 
@@ -72,6 +73,16 @@ def lib():
                                                   C.c_int, C.c_void_p, C.c_int64, C.c_float, C.c_void_p,
                                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                                   C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+        l.kvbfp_quantize_append_paged.argtypes = [C.POINTER(Layout), C.POINTER(CachePtrs), C.c_void_p, C.c_int64,
+                                                  C.c_int32, C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int64,
+                                                  C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
+                                                  C.c_void_p, C.c_void_p]
+        l.kvbfp_decode_workspace_bytes_paged.restype = C.c_size_t
+        l.kvbfp_decode_workspace_bytes_paged.argtypes = [C.POINTER(Layout), C.c_int64, C.c_int32, C.c_int32, C.c_int64]
+        l.kvbfp_decode_attention_paged.argtypes = [C.POINTER(Layout), C.POINTER(CachePtrs), C.c_void_p, C.c_int64,
+                                                   C.c_int32, C.c_int32, C.c_void_p, C.c_int, C.c_void_p, C.c_int64,
+                                                   C.c_float, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+                                                   C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         l.kvbfp_quantize_append.argtypes = [C.POINTER(Layout), C.POINTER(CachePtrs), C.c_void_p, C.c_void_p,
                                             C.c_int, C.c_int32, C.c_int64, C.c_int64, C.c_int64, C.c_int64,
                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -336,6 +347,69 @@ def decode_attention_rope(cache: Cache, q, max_len, softmax_scale, rope_theta, r
                                              _dev_ptr(rope_theta, torch.float32), _dev_ptr(rope_partner, torch.int32),
                                              _dev_ptr(rope_sign, torch.float32), _dev_ptr(out), _dev_ptr(workspace),
                                              workspace.numel(), _stream_ptr(stream), ms))
+    return (out, float(ms[0]), float(ms[1])) if profile else out
+
+
+def _check_table(block_table, batch):
+    if block_table is None or block_table.dim() != 2 or block_table.dtype != torch.int32 or \
+            not block_table.is_contiguous() or block_table.shape[0] != batch:
+        raise ValueError("block_table must be a contiguous int32 device tensor [batch][pages per sequence]")
+
+
+def quantize_append_paged(pool: Cache, block_table, k_new, v_new, pos0=0, pos_dev=None, perm_k=None, perm_v=None,
+                          stream=None):
+    """DEVICE, async.  quantize_append into a pool of pages (pool.layout: batch = pages, max_seq = tokens
+    per page); block_table: int32 [batch][pages per sequence]."""
+    ref = k_new if k_new is not None else v_new
+    if ref is None:
+        return
+    for t in (k_new, v_new):
+        if t is not None:
+            if t.dim() != 4 or t.stride(3) != 1 or t.shape != ref.shape or t.stride() != ref.stride() \
+                    or t.dtype != ref.dtype:
+                raise ValueError("k_new/v_new must be 4-D, channel-contiguous, same shape/strides/dtype")
+    _check_table(block_table, ref.shape[0])
+    L = pool.layout
+    if ref.shape[2] != L.n_kv_heads or ref.shape[3] != L.head_dim:
+        raise ValueError("k_new/v_new shape does not match the layout")
+    ptrs = pool.ptrs
+    _check(lib().kvbfp_quantize_append_paged(C.byref(L), C.byref(ptrs), _dev_ptr(block_table, torch.int32),
+                                             block_table.shape[1], ref.shape[0], _dev_ptr(k_new), _dev_ptr(v_new),
+                                             _TORCH_DT[ref.dtype], ref.shape[1], ref.stride(0), ref.stride(1),
+                                             ref.stride(2), int(pos0), _dev_ptr(pos_dev, torch.int32),
+                                             _dev_ptr(perm_k, torch.int32), _dev_ptr(perm_v, torch.int32),
+                                             _stream_ptr(stream)))
+
+
+def decode_workspace_bytes_paged(pool_layout: Layout, pages_per_seq, batch, n_q_heads, max_len):
+    return int(lib().kvbfp_decode_workspace_bytes_paged(C.byref(pool_layout), int(pages_per_seq), int(batch),
+                                                        int(n_q_heads), int(max_len)))
+
+
+def decode_attention_paged(pool: Cache, block_table, q, max_len, softmax_scale, q_mant_bits=0, seq_len_dev=None,
+                           perm_k=None, perm_v=None, out=None, workspace=None, stream=None, profile=False):
+    """DEVICE, async (synchronous with profile=True).  decode_attention over a pool of pages.
+    Returns `out`, or (out, split_ms, combine_ms) with profile."""
+    L = pool.layout
+    if q.dim() != 3 or not q.is_contiguous():
+        raise ValueError("q must be a contiguous [batch][n_q_heads][head_dim] tensor")
+    _check_table(block_table, q.shape[0])
+    n_q_heads = q.shape[1]
+    if out is None:
+        out = torch.empty_like(q)
+    if workspace is None:
+        need = decode_workspace_bytes_paged(L, block_table.shape[1], q.shape[0], n_q_heads, max_len)
+        if need == 0:
+            _check(ERR_INVALID_ARG)
+        workspace = torch.empty((need,), dtype=torch.uint8, device=q.device)
+    ptrs = pool.ptrs
+    ms = (C.c_float * 2)() if profile else None
+    _check(lib().kvbfp_decode_attention_paged(C.byref(L), C.byref(ptrs), _dev_ptr(block_table, torch.int32),
+                                              block_table.shape[1], q.shape[0], n_q_heads, _dev_ptr(q),
+                                              _TORCH_DT[q.dtype], _dev_ptr(seq_len_dev, torch.int32), int(max_len),
+                                              float(softmax_scale), _dev_ptr(perm_k, torch.int32),
+                                              _dev_ptr(perm_v, torch.int32), int(q_mant_bits), _dev_ptr(out),
+                                              _dev_ptr(workspace), workspace.numel(), _stream_ptr(stream), ms))
     return (out, float(ms[0]), float(ms[1])) if profile else out
 
 

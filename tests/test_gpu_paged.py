@@ -1,0 +1,144 @@
+"""Paged caches: the same bytes and the same attention as the contiguous cache, with every sequence's
+tokens scattered over a pool of pages through a block table.  Paging is addressing only, so the
+oracle is the contiguous one: pages are gathered back through the table before the comparison."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import kvbfp_oracle as O
+from paper_2403_20137_amd import kvbfp, synth
+from test_gpu_attention import make_small
+from util import assert_attention_close, dev_i32, oracle_cache
+
+pytestmark = pytest.mark.gpu
+
+D = 128
+SENTINEL = 0xA5
+
+
+def make_pool(B, Hkv, n, p, page, pages_per_seq, lens, seed, spare=3):
+    """A pool with a few spare pages and a block table that scatters the pages each sequence needs;
+    entries a sequence never reaches hold an invalid page number."""
+    rng = np.random.default_rng(seed)
+    need = [(l + page - 1) // page for l in lens]
+    n_pages = sum(need) + spare
+    order = rng.permutation(n_pages)
+    table = np.full((B, pages_per_seq), -7, dtype=np.int32)
+    at = 0
+    for b in range(B):
+        table[b, :need[b]] = order[at:at + need[b]]
+        at += need[b]
+    L = kvbfp.make_layout(D, n, p, Hkv, n_pages, page)
+    pool = kvbfp.alloc_cache(L, "cuda", fill=SENTINEL)
+    return pool, table, need
+
+
+def gather_pages(pool, table, need, B, S_max, page):
+    """The pool's rows in sequence order, [B][Hkv][S_max][..] per plane (numpy); rows of pages a sequence
+    does not own are filled with the sentinel."""
+    out = []
+    for t in pool.planes():
+        src = t.cpu().numpy()
+        dst = np.full((B,) + src.shape[1:2] + (S_max,) + src.shape[3:], SENTINEL, dtype=np.uint8)
+        for b in range(B):
+            for i in range(need[b]):
+                hi = min((i + 1) * page, S_max)
+                dst[b, :, i * page:hi] = src[table[b, i], :, :hi - i * page]
+        out.append(dst)
+    return out
+
+
+def fill_both(k, v, n, p, page, pages_per_seq, lens, pk, pv, seed, chunks=(None,)):
+    """k, v: CPU [B][S][Hkv][D].  Writes lens[b] tokens of every sequence into a paged pool (GPU) and into
+    contiguous planes (oracle); returns (pool, table_dev, planes)."""
+    B, S, Hkv, _ = k.shape
+    pool, table, need = make_pool(B, Hkv, n, p, page, pages_per_seq, lens, seed)
+    table_dev = dev_i32(table)
+    S_max = pages_per_seq * page
+    # oracle: every sequence holds its first lens[b] tokens, the rest keeps the sentinel
+    planes = None
+    for b in range(B):
+        one = oracle_cache(k[b:b + 1, :lens[b]], v[b:b + 1, :lens[b]], n, p, S_max, 0,
+                           None if pk is None else pk, None if pv is None else pv, fill=SENTINEL)
+        planes = [x.copy() for x in one] if planes is None else [np.concatenate([a, c]) for a, c in zip(planes, one)]
+    # GPU: the longest prefix all sequences share in bulk, then token by token with per-sequence positions
+    common = min(lens)
+    kd, vd = k.cuda(), v.cuda()
+    kvbfp.quantize_append_paged(pool, table_dev, kd[:, :common], vd[:, :common], pos0=0, perm_k=dev_i32(pk),
+                                perm_v=dev_i32(pv))
+    for b in range(B):
+        if lens[b] > common:      # the tail of sequence b alone: a table of one row
+            kvbfp.quantize_append_paged(pool, table_dev[b:b + 1].contiguous(), kd[b:b + 1, common:lens[b]],
+                                        vd[b:b + 1, common:lens[b]], pos_dev=dev_i32([common]),
+                                        perm_k=dev_i32(pk), perm_v=dev_i32(pv))
+    torch.cuda.synchronize()
+    got = gather_pages(pool, table, need, B, S_max, page)
+    for name, g, w in zip(("k_mant", "k_exp", "v_mant", "v_exp"), got, planes):
+        for b in range(B):
+            assert np.array_equal(g[b, :, :lens[b]], w[b, :, :lens[b]]), (name, b)
+            own = need[b] * page
+            assert np.all(g[b, :, lens[b]:own] == SENTINEL), (name, b, "rows after the last token were written")
+    return pool, table_dev, planes
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.float16, torch.bfloat16])
+@pytest.mark.parametrize("p,n", [(4, 16), (4, 32), (4, 64), (8, 16), (8, 128)])
+@pytest.mark.parametrize("G,page", [(1, 256), (4, 256), (8, 512)])
+def test_paged_cache_matches_oracle(dtype, p, n, G, page):
+    # 1300 and 700 tokens: six and three 256-token pages (or three and two of 512), last page ragged
+    lens = [1300, 700]
+    k, v, q, pk, pv = make_small(dtype, B=2, S=1300, Hkv=2, G=G, seed=160 + G)
+    pool, table, planes = fill_both(k, v, n, p, page, 8, lens, pk, pv, seed=G + page)
+    want = O.decode_attention(*planes, D, n, p, synth.to_f32_numpy(q), lens, float(np.float32(128 ** -0.5)), pk, pv)
+    got = kvbfp.decode_attention_paged(pool, table, q.cuda(), 1300, float(np.float32(128 ** -0.5)),
+                                       seq_len_dev=dev_i32(lens), perm_k=dev_i32(pk), perm_v=dev_i32(pv))
+    torch.cuda.synchronize()
+    assert_attention_close(got, want, dtype, "p=%d n=%d G=%d page=%d" % (p, n, G, page))
+
+
+def test_paged_equals_contiguous_bit_for_bit_and_wide_groups():
+    # same kernels, same order of operations: the paged result is the contiguous one exactly; G = 40 takes
+    # the general pass, G = 12 two launches of the matrix-core pass
+    for G in (12, 40):
+        lens = [900, 900]
+        k, v, q, pk, pv = make_small(torch.bfloat16, B=2, S=900, Hkv=1, G=G, seed=170 + G)
+        pool, table, planes = fill_both(k, v, 32, 4, 256, 4, lens, pk, pv, seed=G)
+        L = kvbfp.make_layout(D, 32, 4, 1, 2, 1024)
+        flat = kvbfp.alloc_cache(L, "cuda", fill=0)
+        kvbfp.quantize_append(flat, k.cuda(), v.cuda(), perm_k=dev_i32(pk), perm_v=dev_i32(pv))
+        a = kvbfp.decode_attention(flat, q.cuda(), 900, 0.1, perm_k=dev_i32(pk), perm_v=dev_i32(pv))
+        b = kvbfp.decode_attention_paged(pool, table, q.cuda(), 900, 0.1, perm_k=dev_i32(pk), perm_v=dev_i32(pv))
+        torch.cuda.synchronize()
+        assert torch.equal(a, b)
+        want = O.decode_attention(*planes, D, 32, 4, synth.to_f32_numpy(q), lens, float(np.float32(0.1)), pk, pv)
+        assert_attention_close(b, want, torch.bfloat16)
+
+
+def test_query_cast_and_profile_variant_on_pages():
+    lens = [600, 300, 10]
+    k, v, q, pk, pv = make_small(torch.bfloat16, B=3, S=600, Hkv=2, G=4, seed=180)
+    pool, table, planes = fill_both(k, v, 16, 4, 256, 3, lens, pk, pv, seed=9)
+    want = O.decode_attention(*planes, D, 16, 4, synth.to_f32_numpy(q), lens, float(np.float32(0.09)), pk, pv,
+                              q_mant_bits=8)
+    got, split_ms, combine_ms = kvbfp.decode_attention_paged(pool, table, q.cuda(), 600, float(np.float32(0.09)),
+                                                            q_mant_bits=8, seq_len_dev=dev_i32(lens),
+                                                            perm_k=dev_i32(pk), perm_v=dev_i32(pv), profile=True)
+    assert_attention_close(got, want, torch.bfloat16)
+    assert split_ms > 0 and combine_ms > 0
+
+
+def test_paged_argument_errors():
+    L = kvbfp.make_layout(D, 32, 4, 2, 4, 384)          # 384 tokens per page: not a power of two
+    pool = kvbfp.alloc_cache(L, "cuda", fill=0)
+    table = dev_i32(np.zeros((1, 2)))
+    q = torch.zeros(1, 2, D, device="cuda", dtype=torch.bfloat16)
+    with pytest.raises(kvbfp.KvbfpError) as ei:
+        kvbfp.decode_attention_paged(pool, table, q, 100, 0.1)
+    assert "page" in str(ei.value)
+    L = kvbfp.make_layout(D, 32, 4, 2, 4, 256)
+    pool = kvbfp.alloc_cache(L, "cuda", fill=0)
+    with pytest.raises(kvbfp.KvbfpError):               # 2 pages of 256 hold 512 tokens
+        kvbfp.decode_attention_paged(pool, table, q, 513, 0.1)
+    x = torch.zeros(1, 2, 2, D, device="cuda", dtype=torch.bfloat16)
+    with pytest.raises(kvbfp.KvbfpError):
+        kvbfp.quantize_append_paged(pool, table, x, x, pos0=511)

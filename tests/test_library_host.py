@@ -168,6 +168,21 @@ def test_device_calls_reject_bad_arguments_before_launching():
     assert dar(partner=None) == kvbfp.ERR_INVALID_ARG
     assert dar(sign=None) == kvbfp.ERR_INVALID_ARG
     assert dar() == kvbfp.ERR_WORKSPACE                # complete arguments reach the workspace check
+    def dap(pool, stride=2, batch=1, max_len=300, table=fake):
+        return lib.kvbfp_decode_attention_paged(C.byref(pool), C.byref(ptrs), table, stride, batch, 4, fake, kvbfp.BF16,
+                                                None, max_len, 0.1, None, None, 0, fake, None, 0, None, None)
+
+    pages = kvbfp.make_layout(128, 32, 4, 2, 6, 256)
+    assert dap(kvbfp.make_layout(128, 32, 4, 2, 6, 384)) == kvbfp.ERR_UNSUPPORTED and "page" in kvbfp.last_error()
+    assert dap(kvbfp.make_layout(128, 32, 4, 2, 6, 128)) == kvbfp.ERR_UNSUPPORTED
+    assert dap(pages, table=None) == kvbfp.ERR_INVALID_ARG
+    assert dap(pages, batch=0) == kvbfp.ERR_INVALID_ARG
+    assert dap(pages, max_len=513) == kvbfp.ERR_INVALID_ARG          # two pages of 256 tokens
+    assert dap(pages) == kvbfp.ERR_WORKSPACE                          # complete arguments reach the workspace check
+    assert kvbfp.decode_workspace_bytes_paged(pages, 2, 3, 4, 512) == kvbfp.decode_workspace_bytes(
+        kvbfp.make_layout(128, 32, 4, 2, 3, 512), 4, 512)
+    assert lib.kvbfp_quantize_append_paged(C.byref(pages), C.byref(ptrs), fake, 2, 1, fake, fake, kvbfp.BF16, 2, 256,
+                                           256, 128, 511, None, None, None, None) == kvbfp.ERR_INVALID_ARG
     assert da(ws=None) == kvbfp.ERR_WORKSPACE
     assert da(ws_bytes=16) == kvbfp.ERR_WORKSPACE and "workspace" in kvbfp.last_error()
     assert da(ws=C.c_void_p(0x1010)) == kvbfp.ERR_WORKSPACE
