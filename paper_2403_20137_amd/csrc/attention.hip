@@ -67,7 +67,8 @@ __device__ __forceinline__ float code_value(uint32_t c) {
 // query vectors once per tile (A = q' ch + q'' sh, B = q'' ch - q' sh), and the phasor of the offset r
 // = 16 a + b inside the tile is the product of two 16-entry tables per channel.  Tables and the tile
 // phasor are built in double precision from the fp32 frequencies (one sincos of Theta'[j], one of
-// t_begin Theta'[j], then complex products), so that angles of 10^5 radians keep fp32 accuracy.
+// t_begin Theta'[j] and of the tile step, then complex products), so that angles of 10^5 radians keep
+// fp32 accuracy.
 template <int P, bool ROPE>
 __global__ __launch_bounds__(kTile) void decode_split_generic(DecodeArgs a, int dt) {
     constexpr int kRowBytes = kD * P / 8;
@@ -94,8 +95,10 @@ __global__ __launch_bounds__(kTile) void decode_split_generic(DecodeArgs a, int 
 
     int64_t L = a.seq_len ? (int64_t)a.seq_len[b] : a.max_len;
     L = L < 0 ? 0 : (L > a.max_len ? a.max_len : L);
-    const int64_t t_begin = (int64_t)split * a.split_len;
-    const int64_t t_end = min(t_begin + a.split_len, L);
+    // 256-token tiles are dealt out round-robin: split s takes tiles s, s + n_splits, s + 2 n_splits, ...
+    const int64_t t_begin = (int64_t)split * kTile;
+    const int64_t t_end = L;
+    const int64_t tile_step = (int64_t)a.n_splits * kTile;
     const int nb = kD >> a.log2_block;
 
     if (t_begin >= t_end) {   // nothing cached in this split
@@ -128,7 +131,7 @@ __global__ __launch_bounds__(kTile) void decode_split_generic(DecodeArgs a, int 
         __syncthreads();
     }
 
-    double hi_c = 1.0, hi_s = 0.0, step_c = 1.0, step_s = 0.0;   // thread j < D: phasor of tile0 Theta'[j], of 256 Theta'[j]
+    double hi_c = 1.0, hi_s = 0.0, step_c = 1.0, step_s = 0.0;   // thread j < D: phasor of tile0 Theta'[j], of the tile step
     if (ROPE) {
         for (int i = tid; i < kHeadsPerWg * kD; i += kTile) (&q1[0][0])[i] = (&qs[0][0])[i];
         __syncthreads();
@@ -156,8 +159,7 @@ __global__ __launch_bounds__(kTile) void decode_split_generic(DecodeArgs a, int 
                 ps = ps * c16 + pc * s16;
                 pc = nc;
             }
-            step_c = pc;
-            step_s = ps;
+            sincos((double)tile_step * th, &step_s, &step_c);     // from one of this workgroup's tiles to its next
             sincos((double)t_begin * th, &hi_s, &hi_c);
         }
         __syncthreads();
@@ -169,7 +171,7 @@ __global__ __launch_bounds__(kTile) void decode_split_generic(DecodeArgs a, int 
     for (int g = 0; g < kHeadsPerWg; ++g) o[g][0] = o[g][1] = 0.f;
     const int cp = lane;                            // V phase: channels 2cp, 2cp+1
 
-    for (int64_t tile0 = t_begin; tile0 < t_end; tile0 += kTile) {
+    for (int64_t tile0 = t_begin; tile0 < t_end; tile0 += tile_step) {
         if (ROPE) {   // the queries of this tile (nobody reads qs / qb between the end of a tile and here)
             if (tid < kD) {
                 const float ch = (float)hi_c, sh = (float)hi_s;
@@ -508,7 +510,7 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
     a.q = q; a.out = out; a.seq_len = seq_len_dev; a.perm_k = perm_k; a.perm_v = perm_v;
     a.part_o = (float*)workspace;
     a.part_ml = a.part_o + (size_t)L->batch * n_q_heads * sp.n_splits * kD;
-    a.max_seq = L->max_seq; a.max_len = max_len; a.split_len = sp.split_len;
+    a.max_seq = L->max_seq; a.max_len = max_len;
     a.H_kv = L->n_kv_heads; a.H_q = n_q_heads; a.G = n_q_heads / L->n_kv_heads;
     a.n_splits = sp.n_splits; a.log2_block = log2_exact(L->block);
     a.n_q_tokens = n_q_tokens; a.real_Hq = real_heads; a.real_G = real_heads / L->n_kv_heads;

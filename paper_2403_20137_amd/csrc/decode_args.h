@@ -19,7 +19,9 @@ struct DecodeArgs {
     const int32_t* perm_v;
     float* part_ml;           // [B][H_q][n_splits][2]  (m in base-2 units, l)
     float* part_o;            // [B][H_q][n_splits][D]
-    int64_t max_seq, max_len, split_len;
+    int64_t max_seq, max_len;
+    // Work division: the sequence is cut into 256-token tiles and split s (blockIdx.x) takes tiles
+    // s, s + n_splits, s + 2 n_splits, ...; each split leaves one partial result for the combine pass.
     // With several query tokens per sequence (kvbfp_decode_attention_multi) the kernels see "virtual
     // heads": H_q = n_q_tokens * real_Hq per batch and G = n_q_tokens * real_G per kv-head; virtual head
     // s of a kv-head is query token s / real_G, real head kvh * real_G + s % real_G, and may attend

@@ -69,7 +69,9 @@ __device__ __forceinline__ int slot_channel(int x) { return (x < 4) ? 2 * x : 2 
 // N = block size, HG = groups of four query heads per KV head (G <= 4*HG).
 // grid = (n_splits, H_kv, B), block = 256 (four wavefronts).
 // PL = bf16 limbs of a probability: 2 (16 bits, enough for 16-bit outputs) or 3 (24 bits, fp32 outputs).
-template <int N, int HG, int PL>
+// PAGED: the planes are a pool of pages and every tile looks up its page (a separate instantiation: the
+// contiguous case keeps its 32-bit offsets from one scalar base).
+template <int N, int HG, int PL, bool PAGED>
 __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt) {
     constexpr int NB = kD / N;
     constexpr int NH = HG * 4;
@@ -86,8 +88,10 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
 
     int64_t L = a.seq_len ? (int64_t)a.seq_len[b] : a.max_len;
     L = L < 0 ? 0 : (L > a.max_len ? a.max_len : L);
-    const int64_t t_begin = (int64_t)split * a.split_len;
-    const int64_t t_end = min(t_begin + a.split_len, L);
+    // 256-token tiles are dealt out round-robin: split s takes tiles s, s + n_splits, s + 2 n_splits, ...;
+    // "split-relative" tokens below count from t_begin
+    const int64_t t_begin = (int64_t)split * 256;
+    const int64_t t_end = L;
 
     if (t_begin >= t_end) {   // nothing cached in this split
         for (int i = tid; i < a.g_cnt * kD; i += 256)
@@ -150,13 +154,12 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
     // Plane bases of this (batch, kv-head) are wave-uniform (scalar registers); everything inside
     // the split is addressed with 32-bit offsets from them.
     // (Paged cache: the bases are those of the pool and every tile looks up its page.)
-    const bool paged = a.block_table != nullptr;
-    const int64_t base = paged ? 0 : ((int64_t)b * a.H_kv + kvh) * a.max_seq + t_begin;
+    const int64_t base = PAGED ? 0 : ((int64_t)b * a.H_kv + kvh) * a.max_seq + t_begin;
     const uint8_t* __restrict__ k_mant = a.k_mant + base * 64;
     const uint8_t* __restrict__ v_mant = a.v_mant + base * 64;
     const uint8_t* __restrict__ k_exp = a.k_exp + base * NB;
     const uint8_t* __restrict__ v_exp = a.v_exp + base * NB;
-    const int n_tok = (int)(t_end - t_begin);       // tokens of this split, <= split_len
+    const int n_tok = (int)(t_end - t_begin);       // tokens from this split's first tile to the end of the sequence
     // several query tokens: head slot s sees tokens below lim[.] only (split-relative), and a tile counts
     // as full only if every head sees all of it
     const int n_vis = (int)(L - t_begin);
@@ -186,7 +189,7 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
     // clamping or masking; otherwise rows are clamped to the last cached token and masked.
     auto tile = [&](const int T0, auto full_tag) {
         constexpr bool FULL = decltype(full_tag)::value;
-        const size_t R0 = paged ? (size_t)kvbfp::cache_row(a, b, kvh, t_begin + T0) : (size_t)T0;   // wave-uniform
+        const size_t R0 = PAGED ? (size_t)kvbfp::cache_row(a, b, kvh, t_begin + T0) : (size_t)T0;   // wave-uniform
         const uint8_t* __restrict__ kp = k_mant + R0 * 64;
         const uint8_t* __restrict__ vp = v_mant + R0 * 64;
         const uint8_t* __restrict__ kep = k_exp + R0 * NB;
@@ -323,7 +326,8 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
 
     {
         int T0 = wave * kSuper;
-        for (; T0 + kSuper <= n_full; T0 += kWaves * kSuper) tile(T0, std::true_type{});
+        const int step = a.n_splits * kWaves * kSuper;      // this workgroup's next 256-token tile
+        for (; T0 + kSuper <= n_full; T0 += step) tile(T0, std::true_type{});
         if (T0 < n_tok) tile(T0, std::false_type{});     // at most one ragged tile per wavefront
     }
 
@@ -966,28 +970,23 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
 // register-staged pass with two probability limbs.  fp32 I/O: the register-staged pass with three
 // probability limbs and the three-limb bf16 query for every block size (the FP8 query limbs of the LDS
 // pipeline carry 16 bits, too few for the 1e-5 bar).
-template <int HG>
-hipError_t launch_n(const DecodeArgs& a, int dt, int block, dim3 grid, hipStream_t s) {
-    if (dt == KVBFP_F32) {
-        switch (block) {
-            case 16: decode_split_mfma_p4<16, HG, 3><<<grid, 256, 0, s>>>(a, dt); break;
-            case 32: decode_split_mfma_p4<32, HG, 3><<<grid, 256, 0, s>>>(a, dt); break;
-            case 64: decode_split_mfma_p4<64, HG, 3><<<grid, 256, 0, s>>>(a, dt); break;
-            default: decode_split_mfma_p4<128, HG, 3><<<grid, 256, 0, s>>>(a, dt); break;
-        }
-        return hipGetLastError();
-    }
-    if (a.block_table && block <= 32) {
-        if (block == 16) decode_split_lds_p4<16, HG, true><<<grid, 256, 0, s>>>(a, dt);
-        else decode_split_lds_p4<32, HG, true><<<grid, 256, 0, s>>>(a, dt);
-        return hipGetLastError();
-    }
+template <int HG, int PL, bool PAGED>
+hipError_t launch_reg(const DecodeArgs& a, int dt, int block, dim3 grid, hipStream_t s) {
     switch (block) {
-        case 16: decode_split_lds_p4<16, HG, false><<<grid, 256, 0, s>>>(a, dt); break;
-        case 32: decode_split_lds_p4<32, HG, false><<<grid, 256, 0, s>>>(a, dt); break;
-        case 64: decode_split_mfma_p4<64, HG, 2><<<grid, 256, 0, s>>>(a, dt); break;
-        default: decode_split_mfma_p4<128, HG, 2><<<grid, 256, 0, s>>>(a, dt); break;
+        case 16: decode_split_mfma_p4<16, HG, PL, PAGED><<<grid, 256, 0, s>>>(a, dt); break;
+        case 32: decode_split_mfma_p4<32, HG, PL, PAGED><<<grid, 256, 0, s>>>(a, dt); break;
+        case 64: decode_split_mfma_p4<64, HG, PL, PAGED><<<grid, 256, 0, s>>>(a, dt); break;
+        default: decode_split_mfma_p4<128, HG, PL, PAGED><<<grid, 256, 0, s>>>(a, dt); break;
     }
+    return hipGetLastError();
+}
+
+template <int HG, bool PAGED>
+hipError_t launch_n(const DecodeArgs& a, int dt, int block, dim3 grid, hipStream_t s) {
+    if (dt == KVBFP_F32) return launch_reg<HG, 3, PAGED>(a, dt, block, grid, s);
+    if (block > 32) return launch_reg<HG, 2, PAGED>(a, dt, block, grid, s);
+    if (block == 16) decode_split_lds_p4<16, HG, PAGED><<<grid, 256, 0, s>>>(a, dt);
+    else decode_split_lds_p4<32, HG, PAGED><<<grid, 256, 0, s>>>(a, dt);
     return hipGetLastError();
 }
 
@@ -997,8 +996,8 @@ namespace kvbfp {
 
 hipError_t launch_decode_split_mfma(const DecodeArgs& a, int dtype, int block, int batch, hipStream_t s) {
     const dim3 grid((unsigned)a.n_splits, (unsigned)a.H_kv, (unsigned)batch);
-    if (a.g_cnt <= 4) return launch_n<1>(a, dtype, block, grid, s);
-    return launch_n<2>(a, dtype, block, grid, s);
+    if (a.block_table) return a.g_cnt <= 4 ? launch_n<1, true>(a, dtype, block, grid, s) : launch_n<2, true>(a, dtype, block, grid, s);
+    return a.g_cnt <= 4 ? launch_n<1, false>(a, dtype, block, grid, s) : launch_n<2, false>(a, dtype, block, grid, s);
 }
 
 }  // namespace kvbfp

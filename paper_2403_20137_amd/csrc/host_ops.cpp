@@ -69,21 +69,17 @@ int check_paging(const kvbfp_layout* pool, const Paging& pg, kvbfp_layout* logic
 }
 
 SplitPlan plan_splits(const kvbfp_layout* L, int32_t n_q_heads, int64_t max_len) {
-    // Enough workgroups to cover 256 compute units a few times over, each split a whole number
-    // of token tiles.
+    // Enough workgroups to fill 256 compute units three times over (three are resident per unit), but
+    // no more splits than there are 256-token tiles: the tiles are dealt out round-robin over the splits.
     const int64_t units = (int64_t)L->batch * L->n_kv_heads;
     const int64_t tiles = (max_len + kTokenTile - 1) / kTokenTile;
     (void)n_q_heads;
-    const int64_t target_wgs = 256 * 3;   // three resident workgroups per compute unit
+    const int64_t target_wgs = 256 * 3;
     int64_t want = (target_wgs + units - 1) / units;
-    if (want < 1) want = 1;
     if (want > tiles) want = tiles;
     if (want < 1) want = 1;
-    int64_t tiles_per_split = (tiles + want - 1) / want;
-    if (tiles_per_split < 1) tiles_per_split = 1;
     SplitPlan p;
-    p.split_len = tiles_per_split * kTokenTile;
-    p.n_splits = (int32_t)std::max<int64_t>(1, (tiles + tiles_per_split - 1) / tiles_per_split);
+    p.n_splits = (int32_t)want;
     return p;
 }
 

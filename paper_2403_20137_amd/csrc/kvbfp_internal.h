@@ -26,10 +26,9 @@ inline int dtype_size(int dtype) {
 int check_device_layout(const kvbfp_layout* L);
 int check_cache(const kvbfp_cache* c, bool need_k, bool need_v);
 
-// Number of sequence splits and tokens per split used by decode attention for this geometry.
+// Number of splits (partial results per query head) decode attention uses for this geometry.
 struct SplitPlan {
     int32_t n_splits;
-    int64_t split_len;   // multiple of kTokenTile
 };
 constexpr int kTokenTile = 256;
 SplitPlan plan_splits(const kvbfp_layout* L, int32_t n_q_heads, int64_t max_len);
