@@ -249,14 +249,23 @@ def bulk_quantize_rate(device="cuda", reps=5):
 
 
 def device_info():
-    """Name, compute units and clocks of the GPU the numbers were taken on (clocks as the driver reports them)."""
+    """Name, compute units and current clocks of the GPU the numbers were taken on.  The clocks are read from
+    the driver's sysfs files (the level marked '*' in pp_dpm_sclk / pp_dpm_mclk); no other program is started."""
     p = torch.cuda.get_device_properties(0)
     info = {"name": p.name, "compute_units": p.multi_processor_count}
     try:
-        import subprocess
-        out = subprocess.run(["rocm-smi", "--showclocks", "--json"], capture_output=True, text=True, timeout=20).stdout
-        card = next(iter(json.loads(out).values()))
-        info["current_clocks"] = {k: v for k, v in card.items() if "clock" in k.lower()}
+        import glob
+        clocks = {}
+        for path in sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk")):
+            for key, name in (("sclk", "pp_dpm_sclk"), ("mclk", "pp_dpm_mclk")):
+                with open(os.path.join(os.path.dirname(path), name)) as f:
+                    cur = [ln.split(":", 1)[1].replace("*", "").strip() for ln in f if "*" in ln]
+                if cur:
+                    clocks[key] = cur[0]
+            if clocks:
+                break
+        if clocks:
+            info["current_clocks"] = clocks
     except Exception:
         pass
     return info
