@@ -71,3 +71,51 @@ def test_bulk_prefill_bytes_sampled():
             m, e = O.quantize_append(x, w.block, w.mant_bits, w.seq, 0)
             assert np.array_equal(mant[b, h].cpu().numpy(), m[0, 0])
             assert np.array_equal(exp[b, h].cpu().numpy(), e[0, 0])
+
+
+def test_full_size_paged_and_rotation_at_read():
+    """The headline workload once more (a) as a pool of 256-token pages scattered by a seeded shuffle:
+    attention must return the contiguous call's bits, and sampled pages must hold the contiguous cache's
+    bytes; (b) read with rotation at read (keys taken as cached before the rotary embedding): sampled units
+    against the oracle."""
+    name = "llama3_8b_gqa_32k"
+    w = synth.WORKLOADS[name]
+    tdt = synth.TORCH_DTYPES[w.dtype]
+    d = synth.make_workload_inputs(w, device="cuda")
+    pk = kvbfp.calibrate_perm(d["k_calib"].cpu())
+    pv = kvbfp.calibrate_perm(d["v_calib"].cpu())
+    pkd, pvd = dev_i32(pk), dev_i32(pv)
+    S = w.seq
+    L = kvbfp.make_layout(w.head_dim, w.block, w.mant_bits, w.n_kv_heads, w.batch, S)
+    cache = kvbfp.alloc_cache(L, "cuda", fill=0)
+    kvbfp.quantize_append(cache, d["k"], d["v"], pos0=0, perm_k=pkd, perm_v=pvd)
+    scale = float(np.float32(w.head_dim ** -0.5))
+    flat = kvbfp.decode_attention(cache, d["q"], S, scale, perm_k=pkd, perm_v=pvd)
+    # (a) pages
+    page = 256
+    per_seq = S // page
+    rng = np.random.default_rng(synth.BASE_SEED)
+    table = rng.permutation(w.batch * per_seq).reshape(w.batch, per_seq).astype(np.int32)
+    pool = kvbfp.alloc_cache(kvbfp.make_layout(w.head_dim, w.block, w.mant_bits, w.n_kv_heads, w.batch * per_seq, page),
+                             "cuda", fill=0)
+    kvbfp.quantize_append_paged(pool, dev_i32(table), d["k"], d["v"], pos0=0, perm_k=pkd, perm_v=pvd)
+    paged = kvbfp.decode_attention_paged(pool, dev_i32(table), d["q"], S, scale, perm_k=pkd, perm_v=pvd)
+    torch.cuda.synchronize()
+    assert torch.equal(flat, paged)
+    for (b, i) in [(0, 0), (3, 77), (7, per_seq - 1)]:
+        for src, dst in zip(cache.planes(), pool.planes()):
+            assert torch.equal(src[b, :, i * page:(i + 1) * page], dst[int(table[b, i])]), (b, i)
+    # (b) rotation at read
+    theta = (10000.0 ** (-np.arange(w.head_dim // 2, dtype=np.float64) / (w.head_dim // 2))).astype(np.float32)
+    th, pa, sg = kvbfp.permute_rope(theta, pk, kvbfp.ROPE_PAIRS_HALF_SPLIT)
+    out = kvbfp.decode_attention_rope(cache, d["q"], S, scale, torch.from_numpy(th).cuda(), torch.from_numpy(pa).cuda(),
+                                      torch.from_numpy(sg).cuda(), perm_k=pkd, perm_v=pvd)
+    torch.cuda.synchronize()
+    G = w.group
+    tho, pao, sgo = O.permute_rope(theta, pk, 1)
+    for (b, h) in [(0, 0), (6, 5)]:
+        planes = [t[b:b + 1, h:h + 1].cpu().numpy() for t in cache.planes()]
+        qq = synth.to_f32_numpy(d["q"][b:b + 1, h * G:(h + 1) * G])
+        want = O.decode_attention_rope(*planes, w.head_dim, w.block, w.mant_bits, qq, [S], scale, tho[h:h + 1],
+                                       pao[h:h + 1], sgo[h:h + 1], perm_k=pk[h:h + 1], perm_v=pv[h:h + 1])
+        assert_attention_close(out[b:b + 1, h * G:(h + 1) * G], want, tdt, "rotation at read, unit (%d,%d)" % (b, h))
