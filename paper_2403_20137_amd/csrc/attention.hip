@@ -453,15 +453,34 @@ size_t kvbfp_decode_workspace_bytes(const kvbfp_layout* L, int32_t n_q_heads, in
     return (size_t)L->batch * (size_t)n_q_heads * (size_t)sp.n_splits * (size_t)(kD + 2) * sizeof(float);
 }
 
+// What the variants of the decode call add to the plain one; the defaults are the plain call.
+struct DecodeExtras {
+    int32_t q_mant_bits = 0;                 // query cast to BFP first (kvbfp_decode_attention_qbfp)
+    float* kernel_ms = nullptr;              // HOST float[2]: wait and return the two kernel durations
+    const void* k_new = nullptr;             // the current token, appended first (kvbfp_append_decode_attention)
+    const void* v_new = nullptr;
+    int64_t new_stride_b = 0, new_stride_h = 0;
+    int32_t n_q_tokens = 1;                  // kvbfp_decode_attention_multi
+    const float* rope_theta = nullptr;       // rotation at read (kvbfp_decode_attention_rope)
+    const int32_t* rope_partner = nullptr;
+    const float* rope_sign = nullptr;
+    const Paging* paging = nullptr;          // L is a pool of pages (kvbfp_decode_attention_paged)
+};
+
 static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t n_q_heads,
                        const void* q, kvbfp_dtype dtype, const int32_t* seq_len_dev,
                        int64_t max_len, float softmax_scale, const int32_t* perm_k,
-                       const int32_t* perm_v, int32_t q_mant_bits, void* out, void* workspace,
-                       size_t workspace_bytes, void* hip_stream, float* kernel_ms = nullptr,
-                       const void* k_new = nullptr, const void* v_new = nullptr, int64_t new_stride_b = 0,
-                       int64_t new_stride_h = 0, int32_t n_q_tokens = 1, const float* rope_theta = nullptr,
-                       const int32_t* rope_partner = nullptr, const float* rope_sign = nullptr,
-                       const Paging* paging = nullptr) {
+                       const int32_t* perm_v, void* out, void* workspace, size_t workspace_bytes,
+                       void* hip_stream, const DecodeExtras& x = DecodeExtras{}) {
+    const int32_t q_mant_bits = x.q_mant_bits, n_q_tokens = x.n_q_tokens;
+    float* const kernel_ms = x.kernel_ms;
+    const void* const k_new = x.k_new;
+    const void* const v_new = x.v_new;
+    const int64_t new_stride_b = x.new_stride_b, new_stride_h = x.new_stride_h;
+    const float* const rope_theta = x.rope_theta;
+    const int32_t* const rope_partner = x.rope_partner;
+    const float* const rope_sign = x.rope_sign;
+    const Paging* const paging = x.paging;
     clear_error();
     kvbfp_layout logical;
     const kvbfp_layout* pool = L;
@@ -604,7 +623,7 @@ int kvbfp_decode_attention(const kvbfp_layout* L, const kvbfp_cache* cache, int3
                            int64_t max_len, float softmax_scale, const int32_t* perm_k,
                            const int32_t* perm_v, void* out, void* workspace,
                            size_t workspace_bytes, void* hip_stream) {
-    return decode_impl(L, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v, 0, out,
+    return decode_impl(L, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v, out,
                        workspace, workspace_bytes, hip_stream);
 }
 
@@ -613,8 +632,10 @@ int kvbfp_decode_attention_qbfp(const kvbfp_layout* L, const kvbfp_cache* cache,
                                 int64_t max_len, float softmax_scale, const int32_t* perm_k,
                                 const int32_t* perm_v, int32_t q_mant_bits, void* out, void* workspace,
                                 size_t workspace_bytes, void* hip_stream) {
-    return decode_impl(L, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v,
-                       q_mant_bits, out, workspace, workspace_bytes, hip_stream);
+    DecodeExtras x;
+    x.q_mant_bits = q_mant_bits;
+    return decode_impl(L, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v, out,
+                       workspace, workspace_bytes, hip_stream, x);
 }
 
 int kvbfp_append_decode_attention(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t n_q_heads,
@@ -627,9 +648,11 @@ int kvbfp_append_decode_attention(const kvbfp_layout* L, const kvbfp_cache* cach
         clear_error();
         return fail(KVBFP_ERR_INVALID_ARG, "append_decode_attention: k_new/v_new is NULL");
     }
-    return decode_impl(L, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v,
-                       q_mant_bits, out, workspace, workspace_bytes, hip_stream, nullptr, k_new, v_new,
-                       new_stride_b, new_stride_h);
+    DecodeExtras x;
+    x.q_mant_bits = q_mant_bits;
+    x.k_new = k_new; x.v_new = v_new; x.new_stride_b = new_stride_b; x.new_stride_h = new_stride_h;
+    return decode_impl(L, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v, out,
+                       workspace, workspace_bytes, hip_stream, x);
 }
 
 int kvbfp_decode_attention_multi(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t n_q_heads,
@@ -637,9 +660,11 @@ int kvbfp_decode_attention_multi(const kvbfp_layout* L, const kvbfp_cache* cache
                                  const int32_t* seq_len_dev, int64_t max_len, float softmax_scale,
                                  const int32_t* perm_k, const int32_t* perm_v, int32_t q_mant_bits, void* out,
                                  void* workspace, size_t workspace_bytes, void* hip_stream) {
-    return decode_impl(L, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v,
-                       q_mant_bits, out, workspace, workspace_bytes, hip_stream, nullptr, nullptr, nullptr, 0, 0,
-                       n_q_tokens);
+    DecodeExtras x;
+    x.q_mant_bits = q_mant_bits;
+    x.n_q_tokens = n_q_tokens;
+    return decode_impl(L, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v, out,
+                       workspace, workspace_bytes, hip_stream, x);
 }
 
 int kvbfp_decode_attention_rope(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t n_q_heads,
@@ -652,9 +677,11 @@ int kvbfp_decode_attention_rope(const kvbfp_layout* L, const kvbfp_cache* cache,
         clear_error();
         return fail(KVBFP_ERR_INVALID_ARG, "decode_attention_rope: rope_theta/rope_partner/rope_sign is NULL");
     }
-    return decode_impl(L, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v, 0, out,
-                       workspace, workspace_bytes, hip_stream, kernel_ms, nullptr, nullptr, 0, 0, 1, rope_theta,
-                       rope_partner, rope_sign);
+    DecodeExtras x;
+    x.kernel_ms = kernel_ms;
+    x.rope_theta = rope_theta; x.rope_partner = rope_partner; x.rope_sign = rope_sign;
+    return decode_impl(L, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v, out,
+                       workspace, workspace_bytes, hip_stream, x);
 }
 
 size_t kvbfp_decode_workspace_bytes_paged(const kvbfp_layout* pool, int64_t table_stride, int32_t batch,
@@ -674,9 +701,12 @@ int kvbfp_decode_attention_paged(const kvbfp_layout* pool, const kvbfp_cache* ca
                                  int32_t q_mant_bits, void* out, void* workspace, size_t workspace_bytes,
                                  void* hip_stream, float* kernel_ms) {
     const Paging pg{block_table, table_stride, batch};
-    return decode_impl(pool, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v,
-                       q_mant_bits, out, workspace, workspace_bytes, hip_stream, kernel_ms, nullptr, nullptr, 0, 0, 1,
-                       nullptr, nullptr, nullptr, &pg);
+    DecodeExtras x;
+    x.q_mant_bits = q_mant_bits;
+    x.kernel_ms = kernel_ms;
+    x.paging = &pg;
+    return decode_impl(pool, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v, out,
+                       workspace, workspace_bytes, hip_stream, x);
 }
 
 int kvbfp_decode_attention_profile(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t n_q_heads,
@@ -688,8 +718,11 @@ int kvbfp_decode_attention_profile(const kvbfp_layout* L, const kvbfp_cache* cac
         clear_error();
         return fail(KVBFP_ERR_INVALID_ARG, "decode_attention_profile: kernel_ms is NULL");
     }
-    return decode_impl(L, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v,
-                       q_mant_bits, out, workspace, workspace_bytes, hip_stream, kernel_ms);
+    DecodeExtras x;
+    x.q_mant_bits = q_mant_bits;
+    x.kernel_ms = kernel_ms;
+    return decode_impl(L, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v, out,
+                       workspace, workspace_bytes, hip_stream, x);
 }
 
 }  // extern "C"
