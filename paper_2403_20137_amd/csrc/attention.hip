@@ -187,8 +187,10 @@ __global__ __launch_bounds__(kTile) void decode_split_generic(DecodeArgs a, int 
             }
             __syncthreads();
         }
-        // rows of the planes are addressed as base + token; a paged cache has one base per 256-token tile
-        const int64_t base = kvbfp::cache_row(a, b, kvh, tile0) - tile0;
+        // rows of the planes are addressed as base + token; a paged cache has one base per 64 tokens, the
+        // share of a wavefront in both phases below (pages hold a multiple of 64 tokens)
+        const int64_t tw = tile0 + wave * 64;
+        const int64_t base = tw < t_end ? kvbfp::cache_row(a, b, kvh, tw) - tw : 0;
         // ---- scores: one cached token per thread
         const int64_t t = tile0 + tid;
         float s[kHeadsPerWg];

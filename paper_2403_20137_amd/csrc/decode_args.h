@@ -45,7 +45,7 @@ struct DecodeArgs {
     // Paged cache (kvbfp_decode_attention_paged): the planes are a pool [n_pages][H_kv][2^log2_page][..]
     // and tokens [i 2^log2_page, (i+1) 2^log2_page) of sequence b live in page
     // block_table[b * table_stride + i]; nullptr = one contiguous region of max_seq tokens per sequence.
-    // A page holds a multiple of 256 tokens, so a tile of the split kernels never straddles two pages.
+    // A page holds a multiple of 64 tokens, so the 64-token tile of a wavefront never straddles two pages.
     const int32_t* block_table;
     int64_t table_stride;
     int32_t log2_page, n_pages;

@@ -55,9 +55,9 @@ int check_paging(const kvbfp_layout* pool, const Paging& pg, kvbfp_layout* logic
     if (int rc = check_device_layout(pool)) return rc;
     if (!pg.block_table) return fail(KVBFP_ERR_INVALID_ARG, "paged cache: block_table is NULL");
     const int64_t page = pool->max_seq;
-    if (page < kTokenTile || (page & (page - 1)) != 0)
+    if (page < kPageMin || (page & (page - 1)) != 0)
         return fail(KVBFP_ERR_UNSUPPORTED, "paged cache: %lld tokens per page (a power of two, at least %d)",
-                    (long long)page, kTokenTile);
+                    (long long)page, kPageMin);
     if (pg.batch <= 0 || pg.table_stride <= 0)
         return fail(KVBFP_ERR_INVALID_ARG, "paged cache: batch %d, table_stride %lld", pg.batch, (long long)pg.table_stride);
     if (pg.table_stride > ((int64_t)1 << 30) / page)

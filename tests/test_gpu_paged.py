@@ -83,12 +83,12 @@ def fill_both(k, v, n, p, page, pages_per_seq, lens, pk, pv, seed, chunks=(None,
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.float16, torch.bfloat16])
 @pytest.mark.parametrize("p,n", [(4, 16), (4, 32), (4, 64), (8, 16), (8, 128)])
-@pytest.mark.parametrize("G,page", [(1, 256), (4, 256), (8, 512)])
+@pytest.mark.parametrize("G,page", [(1, 256), (4, 256), (8, 512), (4, 64), (2, 128)])
 def test_paged_cache_matches_oracle(dtype, p, n, G, page):
     # 1300 and 700 tokens: six and three 256-token pages (or three and two of 512), last page ragged
     lens = [1300, 700]
     k, v, q, pk, pv = make_small(dtype, B=2, S=1300, Hkv=2, G=G, seed=160 + G)
-    pool, table, planes = fill_both(k, v, n, p, page, 8, lens, pk, pv, seed=G + page)
+    pool, table, planes = fill_both(k, v, n, p, page, -(-1300 // page) + 2, lens, pk, pv, seed=G + page)
     want = O.decode_attention(*planes, D, n, p, synth.to_f32_numpy(q), lens, float(np.float32(128 ** -0.5)), pk, pv)
     got = kvbfp.decode_attention_paged(pool, table, q.cuda(), 1300, float(np.float32(128 ** -0.5)),
                                        seq_len_dev=dev_i32(lens), perm_k=dev_i32(pk), perm_v=dev_i32(pv))
@@ -99,10 +99,10 @@ def test_paged_cache_matches_oracle(dtype, p, n, G, page):
 def test_paged_equals_contiguous_bit_for_bit_and_wide_groups():
     # same kernels, same order of operations: the paged result is the contiguous one exactly; G = 40 takes
     # the general pass, G = 12 two launches of the matrix-core pass
-    for G in (12, 40):
+    for G, page in ((12, 256), (40, 256), (40, 64)):
         lens = [900, 900]
         k, v, q, pk, pv = make_small(torch.bfloat16, B=2, S=900, Hkv=1, G=G, seed=170 + G)
-        pool, table, planes = fill_both(k, v, 32, 4, 256, 4, lens, pk, pv, seed=G)
+        pool, table, planes = fill_both(k, v, 32, 4, page, 1024 // page, lens, pk, pv, seed=G)
         L = kvbfp.make_layout(D, 32, 4, 1, 2, 1024)
         flat = kvbfp.alloc_cache(L, "cuda", fill=0)
         kvbfp.quantize_append(flat, k.cuda(), v.cuda(), perm_k=dev_i32(pk), perm_v=dev_i32(pv))
