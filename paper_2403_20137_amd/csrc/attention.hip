@@ -584,9 +584,13 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
     hipError_t err;
     if (fast) {
         err = hipSuccess;
-        for (int g0 = 0; g0 < a.G && err == hipSuccess; g0 += 8) {
+        // heads per launch: 8, or 16 where the LDS pipeline applies and more than 8 are left (its
+        // sixteen-head variant keeps two workgroups per CU resident instead of three)
+        const bool lds_path = dtype != KVBFP_F32 && L->mant_bits == 4 && L->block <= 32;
+        for (int g0 = 0; g0 < a.G && err == hipSuccess; g0 += a.g_cnt) {
+            const int left = a.G - g0;
             a.g_base = g0;
-            a.g_cnt = a.G - g0 < 8 ? a.G - g0 : 8;
+            a.g_cnt = (lds_path && left > 8) ? (left < 16 ? left : 16) : (left < 8 ? left : 8);
             err = L->mant_bits == 4 ? launch_decode_split_mfma(a, (int)dtype, L->block, L->batch, s)
                                     : launch_decode_split_mfma_p8(a, (int)dtype, L->block, L->batch, s);
             a.k_new = a.v_new = nullptr;       // the current token is cast by the first launch only

@@ -28,7 +28,8 @@ struct DecodeArgs {
     // to n_q_tokens - 1 - s / real_G tokens fewer than the sequence holds (causal order of the new tokens).
     int32_t H_kv, H_q, G, n_splits, log2_block;
     int32_t n_q_tokens, real_Hq, real_G;
-    int32_t g_base, g_cnt;    // matrix-core passes: this launch serves virtual heads [g_base, g_base + g_cnt) of every kv-head, g_cnt <= 8
+    int32_t g_base, g_cnt;    // matrix-core passes: this launch serves virtual heads [g_base, g_base + g_cnt) of every kv-head;
+                              // g_cnt <= 8, or <= 16 in the LDS pipeline (4-bit mantissas, blocks of 16/32, 16-bit I/O)
     // Appending the current token inside the split pass (kvbfp_append_decode_attention): the new key
     // and value row of (batch b, kv-head h) at k_new/v_new + b * new_stride_b + h * new_stride_h
     // (elements of the call's dtype); nullptr = nothing to append.
@@ -73,7 +74,8 @@ __host__ __device__ inline int hidden_tokens(const DecodeArgs& a, int s) {
 // Matrix-core split pass for 4-bit mantissas (decode_mfma.hip).  Returns hipSuccess after
 // enqueuing; the caller has already validated the arguments.
 hipError_t launch_decode_split_mfma(const DecodeArgs& a, int dtype, int block, int batch, hipStream_t s);
-// (a.g_cnt <= 8 heads per launch; larger groups take several launches over head subsets.)
+// (a.g_cnt <= 8 heads per launch, 16 where the LDS pipeline applies; larger groups take several launches over
+// head subsets.)
 // The same for 8-bit mantissas (decode_mfma_p8.hip).
 hipError_t launch_decode_split_mfma_p8(const DecodeArgs& a, int dtype, int block, int batch, hipStream_t s);
 

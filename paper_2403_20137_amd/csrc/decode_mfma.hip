@@ -459,7 +459,7 @@ constexpr int vmcnt_imm(int n) { return (n & 0xF) | (0x7 << 4) | (0xF << 8) | ((
 // PAGED: the planes are a pool of pages and every 64-token tile looks up its page (a scalar load, issued a
 // tile ahead of the requests that need it); a separate instantiation, so the contiguous case is untouched.
 template <int N, int HG, bool PAGED>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((N == 16 && HG == 2) ? 2 : 3, 4)))
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(HG == 4 ? 2 : ((N == 16 && HG == 2) ? 2 : 3), 4)))
 void decode_split_lds_p4(DecodeArgs a, int dt) {
     static_assert(N == 16 || N == 32, "LDS pipeline is built for blocks of 16 or 32");
     constexpr int NB = kD / N;
@@ -885,8 +885,10 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
                 uint32_t vw[4], ve[4];
                 lds_read_val_stage<u, NB>(vq, veq, vw, ve);
                 uint2 pp[HG];
-                pp[0] = lds_read_b64<(16 * u) * 2>(ps_rd);
-                if (HG > 1) pp[HG - 1] = lds_read_b64<(2 * 4 * kTileTok + 16 * u) * 2>(ps_rd);
+                static_for<HG>([&](auto HGI) {
+                    constexpr int hg = decltype(HGI)::value;
+                    pp[hg] = lds_read_b64<(hg * 2 * 4 * kTileTok + 16 * u) * 2>(ps_rd);
+                });
                 __builtin_amdgcn_sched_barrier(0);
                 if (more) fill_vals(u, T1 + 16 * u, row1 + 16 * u);
                 __builtin_amdgcn_sched_barrier(0);
@@ -996,6 +998,17 @@ namespace kvbfp {
 
 hipError_t launch_decode_split_mfma(const DecodeArgs& a, int dtype, int block, int batch, hipStream_t s) {
     const dim3 grid((unsigned)a.n_splits, (unsigned)a.H_kv, (unsigned)batch);
+    if (a.g_cnt > 8) {      // sixteen heads per workgroup: LDS pipeline only (the host asks for it nowhere else)
+        if (dtype == KVBFP_F32 || block > 32) return hipErrorInvalidValue;
+        if (a.block_table) {
+            if (block == 16) decode_split_lds_p4<16, 4, true><<<grid, 256, 0, s>>>(a, dtype);
+            else decode_split_lds_p4<32, 4, true><<<grid, 256, 0, s>>>(a, dtype);
+        } else {
+            if (block == 16) decode_split_lds_p4<16, 4, false><<<grid, 256, 0, s>>>(a, dtype);
+            else decode_split_lds_p4<32, 4, false><<<grid, 256, 0, s>>>(a, dtype);
+        }
+        return hipGetLastError();
+    }
     if (a.block_table) return a.g_cnt <= 4 ? launch_n<1, true>(a, dtype, block, grid, s) : launch_n<2, true>(a, dtype, block, grid, s);
     return a.g_cnt <= 4 ? launch_n<1, false>(a, dtype, block, grid, s) : launch_n<2, false>(a, dtype, block, grid, s);
 }

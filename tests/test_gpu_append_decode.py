@@ -63,12 +63,13 @@ def test_small_caches_equal_two_calls(n, G, use_perm):
 
 
 @pytest.mark.parametrize("n", [16, 32])
-@pytest.mark.parametrize("G,use_perm,qbits", [(1, False, 0), (2, True, 0), (2, True, 8)])
+@pytest.mark.parametrize("G,use_perm,qbits", [(1, False, 0), (2, True, 0), (2, True, 8), (12, True, 0)])
 def test_cast_inside_the_split_pass_equals_two_calls(n, G, use_perm, qbits):
-    # The cast moves into the split pass when the split that holds the last token is at least two
-    # 256-token tiles shorter than the others.  4 x 64 = 256 (batch, kv-head) units ask for 3 splits;
-    # 7 tiles then split 3 + 3 + 1.  The current tokens fall into the last, the first and the middle
-    # split, and one sequence is empty.
+    # In the LDS pipeline the wavefront whose 64-token tiles hold the last token casts and stores the new
+    # rows itself.  4 x 64 = 256 (batch, kv-head) units ask for 3 splits (2 with 12 heads per kv-head),
+    # tiles are dealt round-robin; the current tokens fall into the last tile of a sequence of seven
+    # full tiles (fourth wavefront), into tile 2 (third wavefront) and into tile 5 (first wavefront),
+    # and one sequence is empty.
     _case(torch.bfloat16, n, 4, G, [1792, 700, 1300, 0], 1792, use_perm, seed=60 + n + G, qbits=qbits, Hkv=64)
 
 

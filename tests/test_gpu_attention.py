@@ -85,6 +85,17 @@ def test_fp32_io_with_wide_groups(p, n, G):
     assert_attention_close(got, want, torch.float32, "p=%d n=%d G=%d" % (p, n, G))
 
 
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
+@pytest.mark.parametrize("n", [16, 32])
+@pytest.mark.parametrize("G", [10, 16, 20])
+def test_sixteen_heads_per_workgroup(dtype, n, G):
+    # more than 8 heads per kv-head in the LDS pipeline: one launch serves up to 16 (G = 20: 16 + 4);
+    # several splits, the second sequence ends inside a tile, the third holds a single token
+    k, v, q, pk, pv = make_small(dtype, B=3, S=2100, Hkv=2, G=G, seed=200 + G)
+    got, want = run_both(k, v, q, n, 4, [2100, 777, 1], 128 ** -0.5, pk, pv)
+    assert_attention_close(got, want, dtype, "n=%d G=%d" % (n, G))
+
+
 @pytest.mark.parametrize("p", [4, 8])
 @pytest.mark.parametrize("G", [2, 3, 5, 8, 9, 16, 24, 32, 40])
 def test_group_sizes_and_no_permutation(G, p):
