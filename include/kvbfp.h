@@ -218,7 +218,8 @@ int kvbfp_append_decode_attention(const kvbfp_layout* layout, const kvbfp_cache*
  *   workspace   : at least kvbfp_decode_workspace_bytes(layout, n_q_heads * n_q_tokens, max_len) bytes.
  *   n_q_tokens  : 1..64.  With n_q_tokens * (n_q_heads / n_kv_heads) <= 8 the spare rows of the
  *                 matrix-core passes hold the extra tokens and the cost is that of one token; up to
- *                 32 the cache is read once per 8; more go through the general pass.
+ *                 32 the cache is read once per 16 (4-bit mantissas in blocks of 16/32 with 16-bit
+ *                 I/O) or once per 8 (otherwise); more go through the general pass.
  * Everything else as kvbfp_decode_attention_qbfp.  n_q_tokens = 1 is that call. */
 int kvbfp_decode_attention_multi(const kvbfp_layout* layout, const kvbfp_cache* cache,
                                  int32_t n_q_heads, int32_t n_q_tokens, const void* q,
