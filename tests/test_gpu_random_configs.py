@@ -57,3 +57,48 @@ def test_random_configuration(case):
         got = kvbfp.decode_attention(cache, q.cuda(), S, scale, seq_len_dev=sl, perm_k=dev_i32(pk), perm_v=dev_i32(pv))
     torch.cuda.synchronize()
     assert_attention_close(got, want, DT[dt], str(case))
+
+
+@pytest.mark.parametrize("case", _cases()[::2], ids=lambda c: "c%02d_B%d_H%d_G%d_n%d_p%d_%s_S%d" % c[:8])
+def test_random_configuration_on_pages_and_with_rotation_at_read(case):
+    """The same sweep through the two other ways to read a cache: as a pool of pages (must return the bits
+    of the contiguous call) and with rotation at read (against the oracle)."""
+    i, B, Hkv, G, n, p, dt, S, lens, use_perm, qbits = case
+    D = 128
+    seed = 1000 + i
+    kg = synth.outlier_gains(seed, 0, Hkv, D)
+    vg = synth.outlier_gains(seed, 1, Hkv, D)
+    k = synth.kv_rows(B, S, Hkv, D, dt, kg, seed, 2)
+    v = synth.kv_rows(B, S, Hkv, D, dt, vg, seed, 3)
+    q = synth.queries(B, Hkv * G, D, dt, seed, 4)
+    pk = pv = None
+    if use_perm:
+        pk = O.calibrate_perm(synth.to_f32_numpy(synth.kv_rows(1, 32, Hkv, D, dt, kg, seed, 5)[0]))
+        pv = O.calibrate_perm(synth.to_f32_numpy(synth.kv_rows(1, 32, Hkv, D, dt, vg, seed, 6)[0]))
+    scale = float(np.float32(0.05 + 0.01 * (i % 7)))
+    sl = dev_i32(np.asarray(lens))
+    cache = gpu_cache(k.cuda(), v.cuda(), n, p, S, perm_k=pk, perm_v=pv)
+    flat = kvbfp.decode_attention_qbfp(cache, q.cuda(), S, scale, qbits, seq_len_dev=sl, perm_k=dev_i32(pk), perm_v=dev_i32(pv))
+    # pages of 64, 128 or 256 tokens, scattered
+    page = [64, 128, 256][i % 3]
+    per_seq = -(-S // page)
+    rng = np.random.default_rng(seed)
+    table = rng.permutation(B * per_seq + 2)[:B * per_seq].reshape(B, per_seq).astype(np.int32)
+    pool = kvbfp.alloc_cache(kvbfp.make_layout(D, n, p, Hkv, B * per_seq + 2, page), "cuda", fill=0)
+    kvbfp.quantize_append_paged(pool, dev_i32(table), k.cuda(), v.cuda(), pos0=0, perm_k=dev_i32(pk), perm_v=dev_i32(pv))
+    paged = kvbfp.decode_attention_paged(pool, dev_i32(table), q.cuda(), S, scale, q_mant_bits=qbits, seq_len_dev=sl,
+                                         perm_k=dev_i32(pk), perm_v=dev_i32(pv))
+    torch.cuda.synchronize()
+    assert torch.equal(flat, paged), str(case)
+    # rotation at read
+    theta = (10000.0 ** (-np.arange(D // 2, dtype=np.float64) / (D // 2))).astype(np.float32)
+    ident = np.tile(np.arange(D, dtype=np.int32), (Hkv, 1))
+    th, pa, sg = kvbfp.permute_rope(theta, ident if pk is None else pk, i % 2)
+    got = kvbfp.decode_attention_rope(cache, q.cuda(), S, scale, torch.from_numpy(th).cuda(), torch.from_numpy(pa).cuda(),
+                                      torch.from_numpy(sg).cuda(), seq_len_dev=sl, perm_k=dev_i32(pk), perm_v=dev_i32(pv))
+    torch.cuda.synchronize()
+    planes = [t.cpu().numpy() for t in cache.planes()]
+    tho, pao, sgo = O.permute_rope(theta, ident if pk is None else pk, i % 2)
+    want = O.decode_attention_rope(*planes, D, n, p, synth.to_f32_numpy(q), list(lens), scale, tho, pao, sgo,
+                                   perm_k=pk, perm_v=pv)
+    assert_attention_close(got, want, DT[dt], "rotation at read " + str(case))
