@@ -51,6 +51,10 @@ __device__ __forceinline__ float load_as_float(const void* p, int dt, int64_t i)
     return __uint_as_float(h << 16);
 }
 
+// 2^x by the hardware instruction alone (1 ulp; results below 2^-126 come out as 0 instead of as
+// denormals, which is all a softmax weight relative to the running maximum needs; 2^-inf = 0).
+__device__ __forceinline__ float exp2_raw(float x) { return __builtin_amdgcn_exp2f(x); }
+
 __device__ __forceinline__ bf16x8 join(bf16x2 a, bf16x2 b, bf16x2 c, bf16x2 d) {
     bf16x8 r;
     r[0] = a[0]; r[1] = a[1]; r[2] = b[0]; r[3] = b[1];

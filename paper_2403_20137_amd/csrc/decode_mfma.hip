@@ -244,11 +244,11 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
             tmax = row_max(tmax);           // -inf only if this head sees none of the tile (several query tokens)
             const float m_new = fmaxf(m_run[hg], tmax);
             const float m_ref = m_new == -INFINITY ? 0.f : m_new;   // keeps the differences below well defined
-            const float alpha = exp2f(m_run[hg] - m_ref);           // 0 on the first tile, 1 when the maximum stays
+            const float alpha = exp2_raw(m_run[hg] - m_ref);           // 0 on the first tile, 1 when the maximum stays
             float psum = 0.f;
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const float pw = exp2f(s[u] - m_ref);
+                const float pw = exp2_raw(s[u] - m_ref);
                 const __bf16 ph = (__bf16)pw;
                 const float r1 = pw - (float)ph;
                 const __bf16 pl = (__bf16)r1;
@@ -854,11 +854,11 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
                 tmax = row_max(tmax);       // -inf only if this head sees none of the tile (several query tokens)
                 const float m_new = fmaxf(m_run[hg], tmax);
                 const float m_ref = m_new == -INFINITY ? 0.f : m_new;
-                const float alpha = exp2f(m_run[hg] - m_ref);
+                const float alpha = exp2_raw(m_run[hg] - m_ref);
                 float psum = 0.f;
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    const float pw = exp2f(s[u] - m_ref);
+                    const float pw = exp2_raw(s[u] - m_ref);
                     const __bf16 ph = (__bf16)pw;
                     const __bf16 pl = (__bf16)(pw - (float)ph);
                     psum += (float)ph + (float)pl;
