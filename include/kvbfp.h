@@ -285,6 +285,7 @@ int kvbfp_decode_attention_rope(const kvbfp_layout* layout, const kvbfp_cache* c
  * against that.  Everything else (arguments, results, errors) is as in the call without `_paged`:
  * the same bytes land in the same rows of a page that the contiguous call writes into a sequence's
  * region, and attention returns the same values.
+ * kvbfp_dequantize_paged returns out [batch][n_tok][n_kv_heads][head_dim] as kvbfp_dequantize does.
  * kvbfp_decode_attention_paged takes q_mant_bits like kvbfp_decode_attention_qbfp (0 = query as given)
  * and kernel_ms like kvbfp_decode_attention_rope (NULL = asynchronous).
  * Errors: as the plain calls, plus UNSUPPORTED for a page size that is not a power of two >= 64. */
@@ -293,6 +294,9 @@ int kvbfp_quantize_append_paged(const kvbfp_layout* pool, const kvbfp_cache* cac
                                 kvbfp_dtype dtype, int32_t n_new, int64_t stride_b, int64_t stride_t,
                                 int64_t stride_h, int64_t pos0, const int32_t* pos_dev, const int32_t* perm_k,
                                 const int32_t* perm_v, void* hip_stream);
+int kvbfp_dequantize_paged(const kvbfp_layout* pool, const kvbfp_cache* cache, const int32_t* block_table,
+                           int64_t table_stride, int32_t batch, int32_t which, int64_t t0, int64_t n_tok,
+                           const int32_t* perm, void* out, kvbfp_dtype dtype, void* hip_stream);
 size_t kvbfp_decode_workspace_bytes_paged(const kvbfp_layout* pool, int64_t table_stride, int32_t batch,
                                           int32_t n_q_heads, int64_t max_len);
 int kvbfp_decode_attention_paged(const kvbfp_layout* pool, const kvbfp_cache* cache, const int32_t* block_table,

@@ -170,6 +170,9 @@ struct DequantArgs {
     int64_t t0, n_tok, max_seq;
     int32_t H;
     int64_t n_rows;   // B * H * n_tok
+    const int32_t* block_table;   // paged cache: [B][table_stride], nullptr otherwise
+    int64_t table_stride;
+    int32_t log2_page, n_pages;
 };
 
 __device__ __forceinline__ uint16_t narrow_bf16(float v) {
@@ -186,7 +189,13 @@ __global__ __launch_bounds__(256) void dequantize_rows_kernel(DequantArgs a) {
     const int64_t t = r % a.n_tok;
     const int32_t h = (int32_t)((r / a.n_tok) % a.H);
     const int64_t b = r / (a.n_tok * a.H);
-    const int64_t crow = (b * a.H + h) * a.max_seq + a.t0 + t;
+    int64_t crow = (b * a.H + h) * a.max_seq + a.t0 + t;
+    if (a.block_table) {      // page numbers cannot be checked on the host: clamped to the pool
+        const int64_t pos = a.t0 + t;
+        int page = a.block_table[b * a.table_stride + (pos >> a.log2_page)];
+        page = page < 0 ? 0 : (page >= a.n_pages ? a.n_pages - 1 : page);
+        crow = (((int64_t)page * a.H + h) << a.log2_page) + (pos & (((int64_t)1 << a.log2_page) - 1));
+    }
     const int E = a.exp[crow * (kDqLanesPerRow / LPB) + lane16 / LPB];
     const int e = E - 127 - (P - 2);
     uint32_t code[8];
@@ -374,10 +383,16 @@ int kvbfp::quantize_append_impl(const kvbfp_layout* L, const kvbfp_cache* cache,
 
 extern "C" {
 
-int kvbfp_dequantize(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t which, int64_t t0,
-                     int64_t n_tok, const int32_t* perm, void* out, kvbfp_dtype dtype,
-                     void* hip_stream) {
+static int dequantize_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t which, int64_t t0,
+                           int64_t n_tok, const int32_t* perm, void* out, kvbfp_dtype dtype,
+                           void* hip_stream, const kvbfp::Paging* paging) {
     clear_error();
+    kvbfp_layout logical;
+    const kvbfp_layout* pool = L;
+    if (paging) {
+        if (int rc = check_paging(pool, *paging, &logical)) return rc;
+        L = &logical;             // from here on: what the sequences look like
+    }
     if (int rc = check_device_layout(L)) return rc;
     if (which != 0 && which != 1) return fail(KVBFP_ERR_INVALID_ARG, "dequantize: which = %d", which);
     if (int rc = check_cache(cache, which == 0, which == 1)) return rc;
@@ -395,6 +410,12 @@ int kvbfp_dequantize(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t wh
     a.perm = perm; a.out = out; a.t0 = t0; a.n_tok = n_tok; a.max_seq = L->max_seq;
     a.H = L->n_kv_heads;
     a.n_rows = (int64_t)L->batch * L->n_kv_heads * n_tok;
+    if (paging) {
+        a.block_table = paging->block_table; a.table_stride = paging->table_stride;
+        a.n_pages = pool->batch;
+        a.log2_page = 0;
+        while (((int64_t)1 << a.log2_page) < pool->max_seq) ++a.log2_page;
+    }
     const int64_t blocks = (a.n_rows + kDqRowsPerBlock - 1) / kDqRowsPerBlock;
     if (blocks > 0x7FFFFFFF) return fail(KVBFP_ERR_UNSUPPORTED, "dequantize: too many rows");
     const dim3 grid((unsigned)blocks, 1, 1);
@@ -407,6 +428,19 @@ int kvbfp_dequantize(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t wh
     }
     if (err != hipSuccess) return fail(KVBFP_ERR_HIP, "dequantize: %s", hipGetErrorString(err));
     return KVBFP_OK;
+}
+
+int kvbfp_dequantize(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t which, int64_t t0,
+                     int64_t n_tok, const int32_t* perm, void* out, kvbfp_dtype dtype,
+                     void* hip_stream) {
+    return dequantize_impl(L, cache, which, t0, n_tok, perm, out, dtype, hip_stream, nullptr);
+}
+
+int kvbfp_dequantize_paged(const kvbfp_layout* pool, const kvbfp_cache* cache, const int32_t* block_table,
+                           int64_t table_stride, int32_t batch, int32_t which, int64_t t0, int64_t n_tok,
+                           const int32_t* perm, void* out, kvbfp_dtype dtype, void* hip_stream) {
+    const kvbfp::Paging pg{block_table, table_stride, batch};
+    return dequantize_impl(pool, cache, which, t0, n_tok, perm, out, dtype, hip_stream, &pg);
 }
 
 }  // extern "C"

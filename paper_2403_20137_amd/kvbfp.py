@@ -26,7 +26,8 @@ EXPORTS = ["kvbfp_cache_bytes", "kvbfp_calibrate_perm", "kvbfp_permute_weights",
            "kvbfp_quantize_append", "kvbfp_dequantize", "kvbfp_decode_workspace_bytes",
            "kvbfp_decode_attention", "kvbfp_decode_attention_qbfp", "kvbfp_append_decode_attention", "kvbfp_decode_attention_multi", "kvbfp_decode_attention_profile",
            "kvbfp_permute_rope", "kvbfp_decode_attention_rope",
-           "kvbfp_quantize_append_paged", "kvbfp_decode_workspace_bytes_paged", "kvbfp_decode_attention_paged",
+           "kvbfp_quantize_append_paged", "kvbfp_dequantize_paged", "kvbfp_decode_workspace_bytes_paged",
+           "kvbfp_decode_attention_paged",
            "kvbfp_last_error", "kvbfp_version"]
 
 
@@ -77,6 +78,9 @@ def lib():
                                                   C.c_int32, C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int64,
                                                   C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
                                                   C.c_void_p, C.c_void_p]
+        l.kvbfp_dequantize_paged.argtypes = [C.POINTER(Layout), C.POINTER(CachePtrs), C.c_void_p, C.c_int64, C.c_int32,
+                                             C.c_int32, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_int,
+                                             C.c_void_p]
         l.kvbfp_decode_workspace_bytes_paged.restype = C.c_size_t
         l.kvbfp_decode_workspace_bytes_paged.argtypes = [C.POINTER(Layout), C.c_int64, C.c_int32, C.c_int32, C.c_int64]
         l.kvbfp_decode_attention_paged.argtypes = [C.POINTER(Layout), C.POINTER(CachePtrs), C.c_void_p, C.c_int64,
@@ -379,6 +383,21 @@ def quantize_append_paged(pool: Cache, block_table, k_new, v_new, pos0=0, pos_de
                                              ref.stride(2), int(pos0), _dev_ptr(pos_dev, torch.int32),
                                              _dev_ptr(perm_k, torch.int32), _dev_ptr(perm_v, torch.int32),
                                              _stream_ptr(stream)))
+
+
+def dequantize_paged(pool: Cache, block_table, which, t0, n_tok, dtype=torch.float32, perm=None, out=None, stream=None):
+    """DEVICE, async.  dequantize from a pool of pages; returns [batch][n_tok][n_kv_heads][head_dim]."""
+    L = pool.layout
+    if block_table is None or block_table.dim() != 2 or block_table.dtype != torch.int32 or not block_table.is_contiguous():
+        raise ValueError("block_table must be a contiguous int32 device tensor [batch][pages per sequence]")
+    batch = block_table.shape[0]
+    if out is None:
+        out = torch.empty((batch, n_tok, L.n_kv_heads, L.head_dim), dtype=dtype, device=block_table.device)
+    ptrs = pool.ptrs
+    _check(lib().kvbfp_dequantize_paged(C.byref(L), C.byref(ptrs), _dev_ptr(block_table, torch.int32), block_table.shape[1],
+                                        batch, int(which), int(t0), int(n_tok), _dev_ptr(perm, torch.int32), _dev_ptr(out),
+                                        _TORCH_DT[out.dtype], _stream_ptr(stream)))
+    return out
 
 
 def decode_workspace_bytes_paged(pool_layout: Layout, pages_per_seq, batch, n_q_heads, max_len):

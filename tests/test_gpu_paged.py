@@ -127,6 +127,17 @@ def test_query_cast_and_profile_variant_on_pages():
     assert split_ms > 0 and combine_ms > 0
 
 
+def test_dequantize_from_pages_equals_the_oracle():
+    lens = [500, 321]
+    k, v, q, pk, pv = make_small(torch.bfloat16, B=2, S=500, Hkv=2, G=1, seed=190)
+    pool, table, planes = fill_both(k, v, 32, 8, 128, 4, lens, pk, pv, seed=3)
+    for which, (m, e), perm in ((0, planes[0:2], pk), (1, planes[2:4], pv)):
+        want = O.dequantize(m, e, D, 32, 8, 100, 221, perm=perm)           # tokens 100..320 exist in both sequences
+        got = kvbfp.dequantize_paged(pool, table, which, 100, 221, dtype=torch.float32, perm=dev_i32(perm))
+        torch.cuda.synchronize()
+        assert np.array_equal(got.cpu().numpy().astype(np.float64), want)
+
+
 def test_paged_argument_errors():
     L = kvbfp.make_layout(D, 32, 4, 2, 4, 384)          # 384 tokens per page: not a power of two
     pool = kvbfp.alloc_cache(L, "cuda", fill=0)
