@@ -28,15 +28,27 @@ def hipcc_path() -> str:
     return cand
 
 
-def build_library(verbose: bool = True, extra_flags=()) -> str:
-    cmd = [hipcc_path(), *HIPCC_FLAGS, *extra_flags, "-I", os.path.join(ROOT, "include"), "-I", CSRC]
-    for s in SOURCES:
-        path = os.path.join(CSRC, s)
-        cmd += (["-x", "hip", path] if s.endswith(".hip") else ["-x", "hip", path])
-    cmd += ["-o", LIB]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
+def build_library(verbose: bool = True, extra_flags=(), jobs: int = 5) -> str:
+    """Compiles every source to an object file (in parallel, in a scratch directory beside the library)
+    and links them into libkvbfp.so."""
+    import concurrent.futures
+    import tempfile
+    compile_flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    with tempfile.TemporaryDirectory(prefix="_build_", dir=PKG) as tmp:
+        def compile_one(src):
+            obj = os.path.join(tmp, os.path.splitext(src)[0] + ".o")
+            cmd = [hipcc_path(), *compile_flags, *extra_flags, *inc, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+            if verbose:
+                print(" ".join(cmd), flush=True)
+            subprocess.check_call(cmd)
+            return obj
+        with concurrent.futures.ThreadPoolExecutor(max_workers=max(1, jobs)) as pool:
+            objs = list(pool.map(compile_one, SOURCES))
+        link = [hipcc_path(), "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc", *objs, "-o", LIB]
+        if verbose:
+            print(" ".join(link), flush=True)
+        subprocess.check_call(link)
     return LIB
 
 

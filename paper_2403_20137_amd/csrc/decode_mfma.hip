@@ -974,12 +974,13 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
 // pipeline carry 16 bits, too few for the 1e-5 bar).
 template <int HG, int PL, bool PAGED>
 hipError_t launch_reg(const DecodeArgs& a, int dt, int block, dim3 grid, hipStream_t s) {
-    switch (block) {
-        case 16: decode_split_mfma_p4<16, HG, PL, PAGED><<<grid, 256, 0, s>>>(a, dt); break;
-        case 32: decode_split_mfma_p4<32, HG, PL, PAGED><<<grid, 256, 0, s>>>(a, dt); break;
-        case 64: decode_split_mfma_p4<64, HG, PL, PAGED><<<grid, 256, 0, s>>>(a, dt); break;
-        default: decode_split_mfma_p4<128, HG, PL, PAGED><<<grid, 256, 0, s>>>(a, dt); break;
+    if constexpr (PL == 3) {      // fp32 I/O: every block size; 16-bit I/O comes here with blocks of 64 and 128 only
+        if (block == 16) { decode_split_mfma_p4<16, HG, PL, PAGED><<<grid, 256, 0, s>>>(a, dt); return hipGetLastError(); }
+        if (block == 32) { decode_split_mfma_p4<32, HG, PL, PAGED><<<grid, 256, 0, s>>>(a, dt); return hipGetLastError(); }
     }
+    if (block == 64) decode_split_mfma_p4<64, HG, PL, PAGED><<<grid, 256, 0, s>>>(a, dt);
+    else if (block == 128) decode_split_mfma_p4<128, HG, PL, PAGED><<<grid, 256, 0, s>>>(a, dt);
+    else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 
