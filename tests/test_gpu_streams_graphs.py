@@ -89,3 +89,37 @@ def test_two_calls_in_flight_on_two_streams():
     sb.synchronize()
     for oa, ob in outs:
         assert torch.equal(oa, want_a) and torch.equal(ob, want_b)
+
+
+def test_graph_replays_of_the_paged_and_the_rotating_call_match_eager():
+    k, v, q = _inputs(9)
+    page, per_seq = 128, -(-S // 128)
+    rng = np.random.default_rng(9)
+    table = torch.as_tensor(rng.permutation(2 * per_seq).reshape(2, per_seq).astype(np.int32), device="cuda")
+    pool = kvbfp.alloc_cache(kvbfp.make_layout(D, N, P, HKV, 2 * per_seq, page), "cuda")
+    kvbfp.quantize_append_paged(pool, table, k, v)
+    cache, _ = _eager(k, v, q)
+    theta = (10000.0 ** (-np.arange(D // 2, dtype=np.float64) / (D // 2))).astype(np.float32)
+    rp = [torch.from_numpy(x).cuda() for x in kvbfp.permute_rope(theta, np.tile(np.arange(D, dtype=np.int32), (HKV, 1)), 1)]
+    ws = torch.empty((kvbfp.decode_workspace_bytes_paged(pool.layout, per_seq, 2, HKV * G, S),), dtype=torch.uint8, device="cuda")
+    ws2 = torch.empty((kvbfp.decode_workspace_bytes(cache.layout, HKV * G, S),), dtype=torch.uint8, device="cuda")
+    q_in = q.clone()
+    out_p, out_r = torch.empty_like(q), torch.empty_like(q)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    cap = torch.cuda.Stream()
+    with torch.cuda.graph(graph, stream=cap):
+        kvbfp.decode_attention_paged(pool, table, q_in, S, 0.09, out=out_p, workspace=ws)
+        kvbfp.decode_attention_rope(cache, q_in, S, 0.09, *rp, out=out_r, workspace=ws2)
+    for rep in range(3):
+        qi = synth.queries(2, HKV * G, D, "bf16", 200 + rep, 4, "cuda")
+        q_in.copy_(qi)
+        ws.fill_(rep + 1)
+        ws2.fill_(rep + 7)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        want_p = kvbfp.decode_attention(cache, qi, S, 0.09)
+        want_r = kvbfp.decode_attention_rope(cache, qi, S, 0.09, *rp)
+        torch.cuda.synchronize()
+        assert torch.equal(out_p, want_p) and torch.equal(out_r, want_r), "replay %d" % rep
