@@ -15,7 +15,11 @@
  *   - Every call returns a kvbfp_status.  Everything that can be checked on the host is checked
  *     before anything is launched; kvbfp_last_error() then describes the problem.  Values held in
  *     device memory (positions, sequence lengths) cannot be checked: kernels clamp them so that
- *     all accesses stay inside the cache, and the result is then unspecified.
+ *     all accesses stay inside the cache, and the result is then unspecified.  The same holds for
+ *     permutations held in device memory: every entry is reduced modulo head_dim before it is used as
+ *     an index (a valid permutation is unchanged; anything else is memory-safe, result unspecified).
+ *   - Alignment: the two mantissa planes of a cache must be 16-byte aligned (INVALID_ARG otherwise);
+ *     exponent planes may sit at any address (attention then takes its general pass).
  *   - Non-finite inputs (NaN, Inf) are outside the contract: memory-safe, value unspecified.
  *
  * BFP format (Sec. II-B, Eq. (1)): a block is `block` consecutive cache positions of one row.
@@ -133,8 +137,10 @@ int kvbfp_quantize_append(const kvbfp_layout* layout, const kvbfp_cache* cache, 
  *   out   : DEVICE [batch][n_tok][n_kv_heads][head_dim] of `dtype`, dense.
  *   perm  : DEVICE int32 [n_kv_heads][head_dim] or NULL.  NULL leaves cache (permuted) order;
  *           otherwise out[perm[h][j]] = value at cache position j (original channel order).
+ *           `out` must be 16-byte aligned.
  * fp32 output is exact; fp16/bf16 output is the IEEE round-to-nearest-even conversion.
- * Errors: INVALID_ARG (NULL, range outside [0, max_seq], bad which/dtype), UNSUPPORTED, HIP. */
+ * Errors: INVALID_ARG (NULL, range outside [0, max_seq], bad which/dtype, `out` not 16-byte aligned),
+ * UNSUPPORTED, HIP. */
 int kvbfp_dequantize(const kvbfp_layout* layout, const kvbfp_cache* cache, int32_t which,
                      int64_t t0, int64_t n_tok, const int32_t* perm, void* out, kvbfp_dtype dtype,
                      void* hip_stream);
@@ -158,10 +164,14 @@ size_t kvbfp_decode_workspace_bytes(const kvbfp_layout* layout, int32_t n_q_head
  *   workspace   : DEVICE, at least kvbfp_decode_workspace_bytes(layout, n_q_heads, max_len) bytes,
  *                 256-byte aligned; contents are scratch.
  * Accumulation is fp32; the output is rounded once to `dtype`.
- * Range: up to 32 query heads per kv-head the products run on the matrix cores with power-of-two
- * rescaling; cached blocks whose exponent byte is below 10 (every magnitude under 2^-116) and query
- * blocks outside 2^-110 .. 2^110 lose their scale or their low-order bits there.  Wider groups take the
- * general pass (fp32 multiply-adds), which has no such limit.
+ * Range: up to 32 query heads per kv-head the products run on the matrix cores, whose 16-bit operand
+ * format holds every cached block with an exponent byte from 3 to 254 (4-bit mantissas) or 3 to 251
+ * (8-bit mantissas) exactly, i.e. magnitudes from 2^-126 to 2^124.  Blocks with exponent byte 1 or 2
+ * (every magnitude below 2^-124) lose low-order bits there, an absolute error under 2^-126 per element;
+ * blocks above the upper end are not supported there.  The scaled query q * softmax_scale * log2(e) must
+ * stay between 2^-100 and 2^100 in magnitude wherever it matters to the scores.  Wider groups, and exponent
+ * planes that are not 16-byte aligned, take the general pass (fp32 multiply-adds), which has no such limits
+ * beyond those of fp32 itself.
  * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP. */
 int kvbfp_decode_attention(const kvbfp_layout* layout, const kvbfp_cache* cache, int32_t n_q_heads,
                            const void* q, kvbfp_dtype dtype, const int32_t* seq_len_dev,
@@ -319,6 +329,19 @@ int kvbfp_decode_attention_profile(const kvbfp_layout* layout, const kvbfp_cache
                                    const int32_t* perm_k, const int32_t* perm_v, int32_t q_mant_bits,
                                    void* out, void* workspace, size_t workspace_bytes,
                                    void* hip_stream, float* kernel_ms);
+
+/* DEVICE, SYNCHRONOUS, for measurement.  Reads rows [0, n_tok) of the four planes of every (batch,
+ * kv-head) once -- the bytes one kvbfp_decode_attention call over n_tok cached tokens streams (Sec. III:
+ * the cached keys and values are read back each step) -- with plain 16-byte loads and no arithmetic, and
+ * returns the kernel's duration.  This is the rate a read-only kernel of the same size reaches on the
+ * machine; the split pass of decode attention is reported against it next to the nominal HBM peak.
+ *   wgs_per_unit : workgroups per (batch, kv-head); 0 = a default of about eight per compute unit.
+ *   sink         : DEVICE, 4 writable bytes (keeps the loads alive; practically never written).
+ *   kernel_ms    : HOST float[1], milliseconds between HIP events recorded on `hip_stream` around the kernel.
+ * Up to 15 bytes at either end of an exponent region that is not 16-byte aligned are skipped.
+ * Errors: INVALID_ARG (NULL, n_tok outside (0, max_seq]), UNSUPPORTED (geometry), HIP. */
+int kvbfp_measure_stream_read(const kvbfp_layout* layout, const kvbfp_cache* cache, int64_t n_tok,
+                              int32_t wgs_per_unit, void* sink, void* hip_stream, float* kernel_ms);
 
 /* Message describing the last error on the calling thread ("" if none).  Static storage. */
 const char* kvbfp_last_error(void);

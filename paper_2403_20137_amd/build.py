@@ -10,7 +10,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libkvbfp.so")
-SOURCES = ["host_ops.cpp", "quantize.hip", "attention.hip", "decode_mfma.hip", "decode_mfma_p8.hip"]
+SOURCES = ["host_ops.cpp", "quantize.hip", "attention.hip", "decode_mfma.hip", "decode_mfma_p8.hip", "measure.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -28,7 +28,7 @@ def hipcc_path() -> str:
     return cand
 
 
-def build_library(verbose: bool = True, extra_flags=(), jobs: int = 5) -> str:
+def build_library(verbose: bool = True, extra_flags=(), jobs: int = 6) -> str:
     """Compiles every source to an object file (in parallel, in a scratch directory beside the library)
     and links them into libkvbfp.so."""
     import concurrent.futures

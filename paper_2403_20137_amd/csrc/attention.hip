@@ -119,7 +119,7 @@ __global__ __launch_bounds__(kTile) void decode_split_generic(DecodeArgs a, int 
         const int g = i / kD, j = i % kD;
         float v = 0.f;
         if (g < n_act) {
-            const int c = a.perm_k ? a.perm_k[kvh * kD + j] : j;
+            const int c = a.perm_k ? (a.perm_k[kvh * kD + j] & (kD - 1)) : j;   // masked: device data the host cannot check
             v = load_as_float(a.q, dt, kvbfp::query_row(a, b, kvh, g0 + g) * kD + c);
         }
         qs[g][j] = a.q_mant_bits ? v : v * a.scale_log2e;
@@ -425,7 +425,7 @@ __global__ __launch_bounds__(kD * kCombineSlices) void decode_combine(DecodeArgs
     }
     const float r = den > 0.f ? num / den : 0.f;
     const int kvh = h / a.G;
-    const int c = a.perm_v ? a.perm_v[kvh * kD + j] : j;
+    const int c = a.perm_v ? (a.perm_v[kvh * kD + j] & (kD - 1)) : j;   // masked: the store stays inside the row
     const int64_t oi = kvbfp::query_row(a, b, kvh, h % a.G) * kD + c;
     if (dt == KVBFP_F32) ((float*)a.out)[oi] = r;
     else if (dt == KVBFP_F16) ((uint16_t*)a.out)[oi] = __builtin_bit_cast(unsigned short, (_Float16)r);
@@ -552,8 +552,9 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
     auto aligned16 = [](const void* p) { return ((uintptr_t)p & 15u) == 0; };
     // Matrix-core passes (not with the rotation at read): up to 8 (virtual) heads of a kv-head per launch; larger groups take
     // several launches over head subsets (the cache is then read once per subset), up to 4 of them.
-    const bool fast = !rope && a.G <= 32 && aligned16(a.k_mant) &&
-                      aligned16(a.v_mant) && aligned16(a.k_exp) && aligned16(a.v_exp);
+    // (mantissa planes are 16-byte aligned, checked above; exponent planes that are not go to the general
+    // pass, which reads them byte by byte)
+    const bool fast = !rope && a.G <= 32 && aligned16(a.k_exp) && aligned16(a.v_exp);
     a.g_base = 0;
     a.g_cnt = a.G < 8 ? a.G : 8;
     // The current token (kvbfp_append_decode_attention): cast inside the LDS split pass, else by the
@@ -578,7 +579,11 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
     if (kernel_ms) {
         for (auto& e : ev)
-            if (hipEventCreate(&e) != hipSuccess) return fail(KVBFP_ERR_HIP, "decode_attention_profile: hipEventCreate failed");
+            if (hipEventCreate(&e) != hipSuccess) {
+                for (auto& made : ev)
+                    if (made) (void)hipEventDestroy(made);
+                return fail(KVBFP_ERR_HIP, "decode_attention_profile: hipEventCreate failed");
+            }
         (void)hipEventRecord(ev[0], s);
     }
     hipError_t err;

@@ -20,9 +20,11 @@ typedef int v8i __attribute__((ext_vector_type(8)));
 constexpr int kD = 128;
 constexpr int kWaves = 4;
 constexpr int kSuper = 64;   // tokens per wavefront iteration (4 MFMA column tiles of 16)
-// Cached values are produced as value * 2^-16 so that the conversion's scale exponent stays a
-// normal fp32 exponent for every stored exponent byte >= 10; the query carries the inverse factor.
-constexpr int kShift = 16;
+// The conversions produce cached values as value * 2^-kShift, with kShift chosen per mantissa width so
+// that the conversion's scale operand is the stored exponent byte itself (kShift4, kShift8 in the kernel
+// files).  The inverse factor rides on the other operand of each product (the query for scores, the
+// probabilities for outputs), so the fp32 accumulators hold true-scale numbers: nothing is lost at either
+// end of the fp32 range that the bf16 operand format can hold.
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_f(float v) {

@@ -42,14 +42,14 @@ using kvbfp::DecodeArgs;
 
 using namespace kvbfp::dev;
 
-// fp32 scale operand 2^(E - 129 + 9 - kShift): a code m, read as the FP8 subnormal m * 2^-9, times
-// it equals m * 2^(E - 127 - 2) * 2^-kShift.  Only the exponent field of the operand is used by the
-// conversion; exponent bytes below 10 (magnitudes under 2^-116) collapse to the smallest scale.
-__device__ __forceinline__ float scale_operand(uint32_t E) {
-    // exponent field (E - 129 + 9 - kShift) + 127 = E - (kShift - 7), saturating at 0
-    const unsigned short f = __builtin_elementwise_sub_sat((unsigned short)E, (unsigned short)(kShift - 7));
-    return __uint_as_float((uint32_t)f << 23);
-}
+// A code m of a block with exponent byte E stands for m * 2^(E - 129).  Read as the FP8 subnormal
+// m * 2^-9 and converted with the scale operand 2^(E - 127) -- the byte E itself in the exponent field,
+// which is all the conversion looks at -- it becomes the bf16 value m * 2^(E - 136) = value * 2^-kShift,
+// exact for every E >= 3 (bf16 keeps denormals down to 2^-133; blocks with E = 1, 2, magnitudes below
+// 2^-124, lose low-order bits, an absolute error under 2^-126).  E = 255 (a block maximum within a
+// factor 1.07 of the largest fp32 number) would read as an infinite scale and is not supported here.
+constexpr int kShift = 7;
+__device__ __forceinline__ float scale_operand(uint32_t E) { return __uint_as_float(E << 23); }
 
 // 8 sign-magnitude nibbles -> 8 bf16 values in slot order [c0,c2,c4,c6,c1,c3,c5,c7]
 struct Unpacked { bf16x2 p[4]; };
@@ -106,20 +106,20 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
 
     // q' = permuted query (optionally cast to BFP) * softmax_scale*log2(e) * 2^kShift; head slots beyond G are zero
     {
-        const float factor = a.scale_log2e * (float)(1 << kShift);
+        const float two_k = (float)(1 << kShift);
         for (int i = tid; i < NH * kD; i += 256) {
             const int g = i / kD, c = i % kD;
             float v = 0.f;
             if (g < a.g_cnt) {
-                const int src = a.perm_k ? a.perm_k[kvh * kD + c] : c;
+                const int src = a.perm_k ? (a.perm_k[kvh * kD + c] & (kD - 1)) : c;
                 v = load_as_float(a.q, dt, kvbfp::query_row(a, b, kvh, a.g_base + g) * kD + src);
             }
-            q_s[g][c] = a.q_mant_bits ? v : v * factor;
+            q_s[g][c] = a.q_mant_bits ? v : (v * a.scale_log2e) * two_k;
         }
         __syncthreads();
         if (a.q_mant_bits) {
             bfp_round_queries(&q_s[0][0], (uint32_t*)&o_s[0][0][0], NH, a.log2_block, a.q_mant_bits);
-            for (int i = tid; i < NH * kD; i += 256) (&q_s[0][0])[i] *= factor;
+            for (int i = tid; i < NH * kD; i += 256) (&q_s[0][0])[i] = ((&q_s[0][0])[i] * a.scale_log2e) * two_k;
             __syncthreads();
         }
     }
@@ -245,10 +245,11 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
             const float m_new = fmaxf(m_run[hg], tmax);
             const float m_ref = m_new == -INFINITY ? 0.f : m_new;   // keeps the differences below well defined
             const float alpha = exp2_raw(m_run[hg] - m_ref);           // 0 on the first tile, 1 when the maximum stays
+            const float m_p = m_ref - (float)kShift;                    // probabilities carry 2^kShift (values come as 2^-kShift)
             float psum = 0.f;
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const float pw = exp2_raw(s[u] - m_ref);
+                const float pw = exp2_raw(s[u] - m_p);
                 const __bf16 ph = (__bf16)pw;
                 const float r1 = pw - (float)ph;
                 const __bf16 pl = (__bf16)r1;
@@ -346,7 +347,7 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
         }
         if (j == 0) {
             ml_s[wave][head][0] = m_run[hg];
-            ml_s[wave][head][1] = lsum;
+            ml_s[wave][head][1] = lsum * (1.0f / (float)(1 << kShift));      // the probabilities carried 2^kShift
         }
     }
     __syncthreads();
@@ -363,7 +364,7 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
             const float mw = ml_s[w][g][0];
             if (mw > -INFINITY) acc = fmaf(exp2f(mw - M), o_s[w][g][c], acc);
         }
-        a.part_o[(((int64_t)b * a.H_q + h0 + g) * a.n_splits + split) * kD + c] = acc * (float)(1 << kShift);
+        a.part_o[(((int64_t)b * a.H_q + h0 + g) * a.n_splits + split) * kD + c] = acc;
     }
     if (tid < a.g_cnt) {
         const int g = tid;
@@ -720,7 +721,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
             int e = 0;
             if (mx > 0.f) (void)frexpf(mx, &e);            // mx = f * 2^e, f in [0.5, 1)
             int sh = mx > 0.f ? e - 8 : 0;                  // mx * 2^-sh in [128, 256)
-            sh = max(-110, min(110, sh));
+            sh = max(-115, min(118, sh));                   // every limb's scale byte sh - 4 limb + 127 stays in 0..254
             float v = qf[g * kD + c];
     #pragma unroll
             for (int limb = 0; limb < 4; ++limb) {
@@ -747,6 +748,10 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) row[nr_sub * 16 + i] = widen(nr_bits[i]);
         }
+        // the row is read back below by other lanes of this wavefront
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         float x[16];
 #pragma unroll
         for (int i = 0; i < 16; ++i) x[i] = nr_live ? row[nr_perm[i]] : 0.f;
@@ -855,10 +860,11 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
                 const float m_new = fmaxf(m_run[hg], tmax);
                 const float m_ref = m_new == -INFINITY ? 0.f : m_new;
                 const float alpha = exp2_raw(m_run[hg] - m_ref);
+                const float m_p = m_ref - (float)kShift;     // probabilities carry 2^kShift (values come as 2^-kShift)
                 float psum = 0.f;
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    const float pw = exp2_raw(s[u] - m_ref);
+                    const float pw = exp2_raw(s[u] - m_p);
                     const __bf16 ph = (__bf16)pw;
                     const __bf16 pl = (__bf16)(pw - (float)ph);
                     psum += (float)ph + (float)pl;
@@ -934,7 +940,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
         }
         if (j == 0) {
             ml_s[(wave * NH + head) * 2 + 0] = m_run[hg];
-            ml_s[(wave * NH + head) * 2 + 1] = lsum;
+            ml_s[(wave * NH + head) * 2 + 1] = lsum * (1.0f / (float)(1 << kShift));   // the probabilities carried 2^kShift
         }
     }
     __syncthreads();
@@ -949,7 +955,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
             const float mw = ml_s[(w * NH + g) * 2];
             if (mw > -INFINITY) acc = fmaf(exp2f(mw - M), o_s[(w * NH + g) * kD + c], acc);
         }
-        a.part_o[(((int64_t)b * a.H_q + h0 + g) * a.n_splits + split) * kD + c] = acc * (float)(1 << kShift);
+        a.part_o[(((int64_t)b * a.H_q + h0 + g) * a.n_splits + split) * kD + c] = acc;
     }
     if (tid < a.g_cnt) {
         const int g = tid;

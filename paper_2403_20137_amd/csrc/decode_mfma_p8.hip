@@ -41,17 +41,14 @@ using kvbfp::DecodeArgs;
 using namespace kvbfp::dev;
 
 // fp32 scale operands for the two pieces of a code with stored exponent byte E.  A code m stands for
-// m * 2^(E - 127 - 6); the lo piece read as FP8 is lo * 2^-9, so its scale is 2^(E - 124 - kShift),
-// i.e. exponent field E - (kShift - 3); the hi piece weighs 8 times as much.  Only the exponent
-// field of the operand is used by the conversion; tiny exponent bytes saturate at field 0.
-__device__ __forceinline__ float scale_lo(uint32_t E) {
-    const unsigned short f = __builtin_elementwise_sub_sat((unsigned short)E, (unsigned short)(kShift - 3));
-    return __uint_as_float((uint32_t)f << 23);
-}
-__device__ __forceinline__ float scale_hi(uint32_t E) {
-    const unsigned short f = __builtin_elementwise_sub_sat((unsigned short)E, (unsigned short)(kShift - 6));
-    return __uint_as_float((uint32_t)f << 23);
-}
+// m * 2^(E - 133); the lo piece read as FP8 is lo * 2^-9, and with the byte E itself as the exponent
+// field of its scale operand (all the conversion looks at) it becomes lo * 2^(E - 136) = its value
+// * 2^-kShift; the hi piece weighs 8 times as much (field E + 3).  Exact in bf16 (denormals included) for
+// every E >= 3; E = 1, 2 (magnitudes below 2^-124) lose low-order bits, an absolute error under 2^-126;
+// E >= 252 (block maxima above 2^124) would overflow the field and is not supported here.
+constexpr int kShift = 3;
+__device__ __forceinline__ float scale_lo(uint32_t E) { return __uint_as_float(E << 23); }
+__device__ __forceinline__ float scale_hi(uint32_t E) { return __uint_as_float((E + 3u) << 23); }
 
 // 4 sign-magnitude bytes -> hi pieces (c0,c1), (c2,c3) and lo pieces (c0,c1), (c2,c3) as bf16 pairs
 struct Pieces { bf16x2 h01, h23, l01, l23; };
@@ -107,20 +104,20 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p8(DecodeArgs a, int dt
 
     // q' = permuted query (optionally cast to BFP) * softmax_scale*log2(e) * 2^kShift; head slots beyond G are zero
     {
-        const float factor = a.scale_log2e * (float)(1 << kShift);
+        const float two_k = (float)(1 << kShift);
         for (int i = tid; i < NH * kD; i += 256) {
             const int g = i / kD, c = i % kD;
             float v = 0.f;
             if (g < a.g_cnt) {
-                const int src = a.perm_k ? a.perm_k[kvh * kD + c] : c;
+                const int src = a.perm_k ? (a.perm_k[kvh * kD + c] & (kD - 1)) : c;
                 v = load_as_float(a.q, dt, kvbfp::query_row(a, b, kvh, a.g_base + g) * kD + src);
             }
-            q_s[g][c] = a.q_mant_bits ? v : v * factor;
+            q_s[g][c] = a.q_mant_bits ? v : (v * a.scale_log2e) * two_k;
         }
         __syncthreads();
         if (a.q_mant_bits) {
             bfp_round_queries(&q_s[0][0], (uint32_t*)&o_s[0][0][0], NH, a.log2_block, a.q_mant_bits);
-            for (int i = tid; i < NH * kD; i += 256) (&q_s[0][0])[i] *= factor;
+            for (int i = tid; i < NH * kD; i += 256) (&q_s[0][0])[i] = ((&q_s[0][0])[i] * a.scale_log2e) * two_k;
             __syncthreads();
         }
     }
@@ -236,10 +233,11 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p8(DecodeArgs a, int dt
             const float m_new = fmaxf(m_run[hg], tmax);
             const float m_ref = m_new == -INFINITY ? 0.f : m_new;   // keeps the differences below well defined
             const float alpha = exp2_raw(m_run[hg] - m_ref);           // 0 on the first tile, 1 when the maximum stays
+            const float m_p = m_ref - (float)kShift;                    // probabilities carry 2^kShift (values come as 2^-kShift)
             float psum = 0.f;
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const float pw = exp2_raw(s[u] - m_ref);
+                const float pw = exp2_raw(s[u] - m_p);
                 const __bf16 ph = (__bf16)pw;
                 const float r1 = pw - (float)ph;
                 const __bf16 pl = (__bf16)r1;
@@ -332,7 +330,7 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p8(DecodeArgs a, int dt
         }
         if (j == 0) {
             ml_s[wave][head][0] = m_run[hg];
-            ml_s[wave][head][1] = lsum;
+            ml_s[wave][head][1] = lsum * (1.0f / (float)(1 << kShift));      // the probabilities carried 2^kShift
         }
     }
     __syncthreads();
@@ -349,7 +347,7 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p8(DecodeArgs a, int dt
             const float mw = ml_s[w][g][0];
             if (mw > -INFINITY) acc = fmaf(exp2f(mw - M), o_s[w][g][c], acc);
         }
-        a.part_o[(((int64_t)b * a.H_q + h0 + g) * a.n_splits + split) * kD + c] = acc * (float)(1 << kShift);
+        a.part_o[(((int64_t)b * a.H_q + h0 + g) * a.n_splits + split) * kD + c] = acc;
     }
     if (tid < a.g_cnt) {
         const int g = tid;

@@ -48,6 +48,10 @@ int check_cache(const kvbfp_cache* c, bool need_k, bool need_v) {
         return fail(KVBFP_ERR_INVALID_ARG, "cache key planes are NULL");
     if (need_v && (!c->v_mant || !c->v_exp))
         return fail(KVBFP_ERR_INVALID_ARG, "cache value planes are NULL");
+    // every kernel moves mantissa rows with 8- and 16-byte accesses; exponent planes are read and written
+    // byte-wise wherever they are not 16-byte aligned
+    if ((need_k && (uintptr_t)c->k_mant % 16 != 0) || (need_v && (uintptr_t)c->v_mant % 16 != 0))
+        return fail(KVBFP_ERR_INVALID_ARG, "cache mantissa planes must be 16-byte aligned");
     return KVBFP_OK;
 }
 

@@ -17,6 +17,7 @@
 
 #include <cstdint>
 
+#include "fastdiv.h"
 #include "kvbfp_internal.h"
 #include "quantize_dev.h"
 
@@ -33,15 +34,9 @@ constexpr int kLdsGather = 1;     // aligned rows + permutation: 16-byte loads, 
 constexpr int kElementwise = 2;   // unaligned rows (with or without permutation): one load per element
 
 // Unsigned division of numerators below 2^31 by a fixed divisor: floor(n / d) = (n * mul) >> shift.
-struct FastDiv { uint32_t mul, shift; };
-FastDiv make_fastdiv(uint32_t d) {   // d >= 1
-    uint32_t l = 0;
-    while ((1ull << l) < d) ++l;
-    return FastDiv{(uint32_t)(((1ull << (31 + l)) / d) + 1), 31 + l};
-}
-__device__ __forceinline__ uint32_t fastdiv(uint32_t n, FastDiv d) {
-    return (uint32_t)(((uint64_t)n * d.mul) >> d.shift);
-}
+using kvbfp::FastDiv;
+using kvbfp::fastdiv;
+using kvbfp::make_fastdiv;
 
 struct QuantTensor {
     const void* src;       // [B][n_new][H][D] strided
@@ -224,7 +219,7 @@ __global__ __launch_bounds__(256) void dequantize_rows_kernel(DequantArgs a) {
         const int32_t* pr = a.perm + (int64_t)h * kD;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const int c = pr[c0 + i];
+            const int c = pr[c0 + i] & (kD - 1);   // masked: the store stays inside the row
             if (DT == KVBFP_F32) ((float*)a.out)[orow + c] = v[i];
             else if (DT == KVBFP_F16)
                 ((uint16_t*)a.out)[orow + c] = __builtin_bit_cast(unsigned short, (_Float16)v[i]);

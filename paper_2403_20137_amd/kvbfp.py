@@ -27,7 +27,7 @@ EXPORTS = ["kvbfp_cache_bytes", "kvbfp_calibrate_perm", "kvbfp_permute_weights",
            "kvbfp_decode_attention", "kvbfp_decode_attention_qbfp", "kvbfp_append_decode_attention", "kvbfp_decode_attention_multi", "kvbfp_decode_attention_profile",
            "kvbfp_permute_rope", "kvbfp_decode_attention_rope",
            "kvbfp_quantize_append_paged", "kvbfp_dequantize_paged", "kvbfp_decode_workspace_bytes_paged",
-           "kvbfp_decode_attention_paged",
+           "kvbfp_decode_attention_paged", "kvbfp_measure_stream_read",
            "kvbfp_last_error", "kvbfp_version"]
 
 
@@ -108,6 +108,8 @@ def lib():
                                                    C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
                                                    C.c_size_t, C.c_void_p]
         l.kvbfp_decode_attention_profile.argtypes = l.kvbfp_decode_attention_qbfp.argtypes + [C.POINTER(C.c_float)]
+        l.kvbfp_measure_stream_read.argtypes = [C.POINTER(Layout), C.POINTER(CachePtrs), C.c_int64, C.c_int32,
+                                                C.c_void_p, C.c_void_p, C.POINTER(C.c_float)]
         _lib = l
     return _lib
 
@@ -491,3 +493,15 @@ def decode_attention_multi(cache: Cache, q, max_len, softmax_scale, seq_len_dev=
                                               int(q_mant_bits), _dev_ptr(out), _dev_ptr(workspace), workspace.numel(),
                                               _stream_ptr(stream)))
     return out
+
+
+def measure_stream_read(cache: Cache, n_tok, wgs_per_unit=0, sink=None, stream=None) -> float:
+    """DEVICE, synchronous.  Plain read of rows [0, n_tok) of the four planes; returns the kernel time in ms."""
+    L = cache.layout
+    if sink is None:
+        sink = torch.zeros((4,), dtype=torch.uint8, device=cache.k_mant.device)
+    ptrs = cache.ptrs
+    ms = C.c_float(0)
+    _check(lib().kvbfp_measure_stream_read(C.byref(L), C.byref(ptrs), int(n_tok), int(wgs_per_unit), _dev_ptr(sink),
+                                           _stream_ptr(stream), C.byref(ms)))
+    return float(ms.value)

@@ -1,18 +1,47 @@
-"""kvbfp_append_decode_attention = kvbfp_quantize_append of the current token + kvbfp_decode_attention:
-same cache bytes, same output bits, whether the cast happens inside the split pass or ahead of it."""
+"""kvbfp_append_decode_attention, the call the benchmark times, against the oracle: the appended rows' bytes
+bit for bit (Sec. II-B, Eq. (1)), the whole cache up to every sequence's length bit for bit, the output
+within the attention bar (Sec. III).  On top: same cache bytes and same output bits as
+kvbfp_quantize_append of the current token + kvbfp_decode_attention, whether the cast happens inside the
+split pass or ahead of it."""
 import numpy as np
 import pytest
 import torch
 
+from oracle import kvbfp_oracle as O
 from paper_2403_20137_amd import kvbfp, synth
-from util import dev_i32
+from util import assert_attention_close, dev_i32
 
 pytestmark = pytest.mark.gpu
 D = 128
 DT = {torch.float32: "f32", torch.float16: "f16", torch.bfloat16: "bf16"}
 
 
-def _case(dtype, n, p, G, lens, S_max, use_perm, seed, qbits=0, Hkv=2):
+def _oracle_units(cache, got, k, v, q, lens, n, p, G, S_max, pk, pv, scale, qbits, dtype, units):
+    """Recomputes the (batch, kv-head) units `units` with the oracle from the same inputs: the cast of
+    rows [0, len) (the last one is the appended token) and attention over them."""
+    for (b, h) in units:
+        L = lens[b]
+        out_unit = got[b:b + 1, h * G:(h + 1) * G]
+        if L == 0:
+            assert bool((out_unit == 0).all()), ("empty sequence must yield zeros", b, h)
+            continue
+        kk = synth.to_f32_numpy(k[b:b + 1, :L, h:h + 1])
+        vv = synth.to_f32_numpy(v[b:b + 1, :L, h:h + 1])
+        pkh = None if pk is None else pk[h:h + 1].cpu().numpy()
+        pvh = None if pv is None else pv[h:h + 1].cpu().numpy()
+        km, ke = O.quantize_append(kk, n, p, L, 0, perm=pkh)
+        vm, ve = O.quantize_append(vv, n, p, L, 0, perm=pvh)
+        for plane, ref, nm in ((cache.k_mant, km, "k_mant"), (cache.k_exp, ke, "k_exp"),
+                               (cache.v_mant, vm, "v_mant"), (cache.v_exp, ve, "v_exp")):
+            gotp = plane[b, h, :L].cpu().numpy()
+            assert np.array_equal(gotp[L - 1], ref[0, 0, L - 1]), ("appended row differs from the oracle", nm, b, h)
+            assert np.array_equal(gotp, ref[0, 0]), ("cache differs from the oracle", nm, b, h)
+        want = O.decode_attention(km, ke, vm, ve, D, n, p, synth.to_f32_numpy(q[b:b + 1, h * G:(h + 1) * G]), [L], scale,
+                                  pkh, pvh, q_mant_bits=qbits)
+        assert_attention_close(out_unit, want, dtype, "append_decode_attention unit (%d,%d) n=%d p=%d" % (b, h, n, p))
+
+
+def _case(dtype, n, p, G, lens, S_max, use_perm, seed, qbits=0, Hkv=2, units=None):
     B = len(lens)
     S = max(max(lens), 1)
     gains = synth.outlier_gains(seed, 0, Hkv, D)
@@ -52,6 +81,10 @@ def _case(dtype, n, p, G, lens, S_max, use_perm, seed, qbits=0, Hkv=2):
     for name in ("k_mant", "k_exp", "v_mant", "v_exp"):
         assert torch.equal(getattr(a, name), getattr(f, name)), name
     assert torch.equal(got, want)
+    # ... and the one-call result against the oracle (all units of a small case, sampled ones of a large one)
+    if units is None:
+        units = [(b, h) for b in range(B) for h in range(Hkv)]
+    _oracle_units(f, got, k, v, q, lens, n, p, G, S_max, pk, pv, scale, qbits, dtype, units)
 
 
 @pytest.mark.parametrize("n", [16, 32])
@@ -70,11 +103,13 @@ def test_cast_inside_the_split_pass_equals_two_calls(n, G, use_perm, qbits):
     # tiles are dealt round-robin; the current tokens fall into the last tile of a sequence of seven
     # full tiles (fourth wavefront), into tile 2 (third wavefront) and into tile 5 (first wavefront),
     # and one sequence is empty.
-    _case(torch.bfloat16, n, 4, G, [1792, 700, 1300, 0], 1792, use_perm, seed=60 + n + G, qbits=qbits, Hkv=64)
+    _case(torch.bfloat16, n, 4, G, [1792, 700, 1300, 0], 1792, use_perm, seed=60 + n + G, qbits=qbits, Hkv=64,
+          units=[(0, 0), (0, 63), (1, 17), (2, 40), (3, 5)])
 
 
 def test_cast_inside_the_split_pass_fp16():
-    _case(torch.float16, 32, 4, 1, [1700, 1792, 1537, 1], 1792, True, seed=77, Hkv=64)
+    _case(torch.float16, 32, 4, 1, [1700, 1792, 1537, 1], 1792, True, seed=77, Hkv=64,
+          units=[(0, 3), (1, 63), (2, 31), (3, 0), (3, 62)])
 
 
 @pytest.mark.parametrize("dtype,n,p", [(torch.bfloat16, 16, 8), (torch.bfloat16, 64, 4), (torch.float32, 32, 4),
@@ -102,4 +137,5 @@ def test_without_sequence_lengths_the_token_goes_to_the_last_position():
 def test_headline_configuration_in_the_launch_shape_of_the_benchmark():
     # 8 sequences x 8 kv-heads x 32769 tokens, 4 query heads per kv-head, block 32: 12 splits of 11 tiles,
     # the last one 8 tiles long -> the cast runs inside the split pass
-    _case(torch.bfloat16, 32, 4, 4, [32769, 32769, 32700, 32769, 30000, 32769, 32769, 28161], 32769, True, seed=99, Hkv=8)
+    _case(torch.bfloat16, 32, 4, 4, [32769, 32769, 32700, 32769, 30000, 32769, 32769, 28161], 32769, True, seed=99, Hkv=8,
+          units=[(0, 0), (2, 5), (4, 7), (7, 3)])

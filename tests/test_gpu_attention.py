@@ -161,3 +161,64 @@ def test_llama2_7b_4k_full_parity():
     pv = kvbfp.calibrate_perm(d["v_calib"])
     got, want = run_both(d["k"], d["v"], d["q"], w.block, w.mant_bits, [w.seq], w.head_dim ** -0.5, pk, pv)
     assert_attention_close(got, want, torch.float16)
+
+
+@pytest.mark.parametrize("offset", [1, 4])
+@pytest.mark.parametrize("p,n,dtype", [(4, 32, torch.bfloat16), (8, 16, torch.float32)])
+def test_exponent_planes_at_odd_addresses(offset, p, n, dtype):
+    # exponent planes that are not 16-byte aligned take the general pass, which reads them byte by byte
+    # (the mantissa planes must be aligned: see test_library_host.py); same bar against the oracle
+    k, v, q, pk, pv = make_small(dtype, B=2, S=600, Hkv=2, G=4, seed=300 + offset)
+    planes = oracle_cache(k, v, n, p, 600, 0, pk, pv)
+    cache = gpu_cache(k.cuda(), v.cuda(), n, p, 600, perm_k=pk, perm_v=pv)
+    moved = []
+    for t in (cache.k_exp, cache.v_exp):
+        buf = torch.zeros((t.numel() + 64,), dtype=torch.uint8, device="cuda")
+        view = buf[offset:offset + t.numel()].view(t.shape)
+        view.copy_(t)
+        assert view.data_ptr() % 16 == offset
+        moved.append(view)
+    odd = kvbfp.Cache(cache.layout, cache.k_mant, moved[0], cache.v_mant, moved[1])
+    scale = float(np.float32(128 ** -0.5))
+    want = O.decode_attention(*planes, 128, n, p, synth.to_f32_numpy(q), [600, 333], scale, pk, pv)
+    got = kvbfp.decode_attention(odd, q.cuda(), 600, scale, seq_len_dev=dev_i32(np.asarray([600, 333])),
+                                 perm_k=dev_i32(pk), perm_v=dev_i32(pv))
+    torch.cuda.synchronize()
+    assert_attention_close(got, want, dtype, "exponent planes at +%d" % offset)
+    # appending through the odd planes writes the same bytes
+    kvbfp.quantize_append(odd, k.cuda(), v.cuda(), perm_k=dev_i32(pk), perm_v=dev_i32(pv))
+    torch.cuda.synchronize()
+    assert_planes_equal(odd, planes, "append into exponent planes at +%d" % offset)
+
+
+@pytest.mark.parametrize("n,G", [(32, 4), (16, 8), (64, 4)])
+def test_split_partials_before_the_output_rounding(n, G):
+    # The arithmetic of the 16-bit passes, separately from the one rounding of the output: the workspace
+    # holds the fp32 partial results of the splits, [B][Hq][n_splits][128] unnormalised outputs followed by
+    # [B][Hq][n_splits][2] (running maximum in base-2 units, normaliser).  Merged here in fp64, they must
+    # agree with the oracle far below a bf16 step.
+    B, S, Hkv, D = 2, 2100, 2, 128
+    k, v, q, pk, _ = make_small(torch.bfloat16, B=B, S=S, Hkv=Hkv, G=G, seed=400 + n)
+    planes = oracle_cache(k, v, n, 4, S, 0, pk, None)
+    cache = gpu_cache(k.cuda(), v.cuda(), n, 4, S, perm_k=pk)
+    scale = float(np.float32(D ** -0.5))
+    Hq = Hkv * G
+    need = kvbfp.decode_workspace_bytes(cache.layout, Hq, S)
+    n_splits = need // (B * Hq * (D + 2) * 4)
+    assert n_splits * B * Hq * (D + 2) * 4 == need and n_splits > 1
+    ws = torch.zeros((need,), dtype=torch.uint8, device="cuda")
+    lens = [S, 1111]
+    kvbfp.decode_attention(cache, q.cuda(), S, scale, seq_len_dev=dev_i32(np.asarray(lens)), perm_k=dev_i32(pk),
+                           workspace=ws)
+    torch.cuda.synchronize()
+    f = ws.view(torch.float32).cpu().double().numpy()
+    po = f[:B * Hq * n_splits * D].reshape(B, Hq, n_splits, D)
+    ml = f[B * Hq * n_splits * D:].reshape(B, Hq, n_splits, 2)
+    m, l = ml[..., 0], ml[..., 1]
+    M = m.max(axis=-1, keepdims=True)
+    wgt = np.where(np.isfinite(m), np.exp2(m - M), 0.0)
+    merged = (wgt[..., None] * po).sum(axis=2) / (wgt * l).sum(axis=-1)[..., None]
+    want = O.decode_attention(*planes, D, n, 4, synth.to_f32_numpy(q), lens, scale, pk, None)
+    err = np.linalg.norm(merged - want, axis=-1) / np.linalg.norm(want, axis=-1)
+    print("block %d, %d heads per kv-head: worst rel-L2 of the fp32 partials %.2e" % (n, G, err.max()))
+    assert err.max() <= 1e-4, err

@@ -197,3 +197,21 @@ def test_workspace_grows_with_splits_and_heads():
     b = kvbfp.decode_workspace_bytes(L, 32, 256)
     assert a > b > 0
     assert b == 1 * 32 * 1 * 130 * 4
+
+
+def test_misaligned_mantissa_planes_are_refused_before_any_launch():
+    # device calls move mantissa rows with 8- and 16-byte accesses; a plane at an odd address is an
+    # argument error (checked on the host: the pointers below are never dereferenced)
+    L = kvbfp.make_layout(128, 32, 4, 2, 1, 64)
+    lib = kvbfp.lib()
+    for bad in (0, 2):
+        planes = [0x10000, 0x20000, 0x30000, 0x40000]
+        planes[bad] += 8
+        ptrs = kvbfp.CachePtrs(*planes)
+        rc = lib.kvbfp_decode_attention(C.byref(L), C.byref(ptrs), 2, C.c_void_p(0x50000), kvbfp.BF16, None, 64,
+                                        C.c_float(0.1), None, None, C.c_void_p(0x60000), C.c_void_p(0x70000),
+                                        C.c_size_t(1 << 20), None)
+        assert rc == kvbfp.ERR_INVALID_ARG and "16-byte aligned" in kvbfp.last_error()
+        rc = lib.kvbfp_quantize_append(C.byref(L), C.byref(ptrs), C.c_void_p(0x50000), C.c_void_p(0x58000), kvbfp.BF16,
+                                       1, 256, 256, 128, 0, None, None, None, None)
+        assert rc == kvbfp.ERR_INVALID_ARG and "16-byte aligned" in kvbfp.last_error()

@@ -23,10 +23,22 @@ def dtype_round(want, dtype):
     return torch.from_numpy(np.ascontiguousarray(want)).to(dtype).to(torch.float64).numpy()
 
 
-# Kernel arithmetic (fp32 accumulation, fp16 operands in the fast paths) relative to the largest
+# Kernel arithmetic (fp32 accumulation, 16-bit probability limbs in the fast paths) relative to the largest
 # entry of a head's output; far below the 16-bit output step.
 ARITH_SLACK = {torch.float32: 1e-5, torch.float16: 3e-4, torch.bfloat16: 3e-4}
 MANT_BITS = {torch.float16: 10, torch.bfloat16: 7}
+
+# Every 16-bit comparison of a test run is recorded here and summed up at the end of the run
+# (tests/conftest.py): heads checked, heads above the flat 2e-3, the worst head.
+STATS = {}
+
+
+def _record(dtype, per_head, what):
+    st = STATS.setdefault(DT_NAME[dtype], {"heads": 0, "above_2e-3": 0, "worst": 0.0, "worst_case": ""})
+    st["heads"] += int(per_head.size)
+    st["above_2e-3"] += int((per_head > 2e-3).sum())
+    if per_head.size and float(per_head.max()) > st["worst"]:
+        st["worst"], st["worst_case"] = float(per_head.max()), str(what)
 
 
 def assert_attention_close(got, want, dtype, what=""):
@@ -34,24 +46,32 @@ def assert_attention_close(got, want, dtype, what=""):
 
     fp32 I/O: relative L2 error of every (batch, head) output vector <= 1e-5.
 
-    fp16 / bf16 I/O: the stated bar is 2e-3 relative L2.  One correct rounding of the exact result
-    to bf16 already costs up to 2^-8 = 3.9e-3 of a vector that is dominated by one entry (1.5e-3
-    on average), so per head the bar is max(2e-3, error of the correctly rounded oracle result +
-    kernel slack); over the whole tensor it is 2e-3; and element by element the result must be
-    the correctly rounded exact value up to the kernel's arithmetic slack:
-        |got - want| <= ulp(want)/2 + ARITH_SLACK * max|want_head|.
-    Returns (max per-head rel-L2, whole-tensor rel-L2)."""
+    fp16 I/O: relative L2 error of every head <= 2e-3, flat (rounding to fp16 costs ~2e-4).
+
+    bf16 I/O: the stated bar is 2e-3 relative L2, but one correct rounding of the exact result to
+    bf16 already costs up to 2^-8 = 3.9e-3 of a vector that is dominated by one entry (1.5e-3 on
+    average), so per head the bar is max(2e-3, error of the correctly rounded oracle result +
+    kernel slack), and over the whole tensor 2e-3.
+
+    Both 16-bit types, element by element: the result must be the correctly rounded exact value up
+    to the kernel's arithmetic slack, |got - want| <= ulp(want)/2 + ARITH_SLACK * max|want_head|.
+    Returns (max per-head rel-L2, whole-tensor rel-L2); the heads above the flat 2e-3 are counted in
+    STATS and reported at the end of the run."""
     g = got.detach().to("cpu").to(torch.float64).numpy()
     per_head = rel_l2_per_head(got, want)
     total = float(np.linalg.norm(g - want) / max(np.linalg.norm(want), 1e-300))
     if dtype == torch.float32:
         assert per_head.max() <= TOL[dtype], (what, per_head)
         return float(per_head.max()), total
-    ideal = rel_l2_per_head(torch.from_numpy(dtype_round(want, dtype)), want)
-    bar = np.maximum(TOL[dtype], ideal + ARITH_SLACK[dtype])
-    assert np.all(per_head <= bar), (what, per_head, bar)
-    assert total <= TOL[dtype] or total <= float(np.linalg.norm(dtype_round(want, dtype) - want) /
-                                                 np.linalg.norm(want)) + ARITH_SLACK[dtype], (what, total)
+    _record(dtype, per_head, what)
+    if dtype == torch.float16:
+        assert np.all(per_head <= TOL[dtype]), (what, per_head)
+    else:
+        ideal = rel_l2_per_head(torch.from_numpy(dtype_round(want, dtype)), want)
+        bar = np.maximum(TOL[dtype], ideal + ARITH_SLACK[dtype])
+        assert np.all(per_head <= bar), (what, per_head, bar)
+        assert total <= TOL[dtype] or total <= float(np.linalg.norm(dtype_round(want, dtype) - want) /
+                                                     np.linalg.norm(want)) + ARITH_SLACK[dtype], (what, total)
     mb = MANT_BITS[dtype]
     mag = np.maximum(np.abs(want), 2.0 ** -14 if dtype == torch.float16 else 2.0 ** -126)
     half_ulp = 0.5 * 2.0 ** (np.floor(np.log2(mag)) - mb)
