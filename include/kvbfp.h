@@ -343,6 +343,27 @@ int kvbfp_decode_attention_profile(const kvbfp_layout* layout, const kvbfp_cache
 int kvbfp_measure_stream_read(const kvbfp_layout* layout, const kvbfp_cache* cache, int64_t n_tok,
                               int32_t wgs_per_unit, void* sink, void* hip_stream, float* kernel_ms);
 
+/* DEVICE, asynchronous.  For callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The same launches and
+ * the same result as kvbfp_decode_attention_qbfp (same arguments, minus the workspace), with the partial
+ * results of the sequence splits kept in a fixed device array inside the library instead
+ * (KVBFP_NOALLOC_SCRATCH_BYTES per GPU, held from the first call on that GPU until the process ends).
+ * The call allocates and frees nothing, on the host side of HIP or on the device; the array's address
+ * on the current device is looked up once, on the first call made with that device current.
+ *   - A geometry whose kvbfp_decode_workspace_bytes(layout, n_q_heads, max_len) exceeds
+ *     KVBFP_NOALLOC_SCRATCH_BYTES is refused with KVBFP_ERR_WORKSPACE before anything is launched.
+ *   - All calls on one GPU share the one array: calls that may overlap on a GPU (different streams
+ *     without ordering between them) race on it and must be serialised by the caller.  Nothing in the
+ *     array has to start at zero and nothing of a previous call is read.
+ * Errors: as kvbfp_decode_attention_qbfp, plus WORKSPACE as above and HIP if the array's address
+ * cannot be obtained. */
+#define KVBFP_NOALLOC_SCRATCH_BYTES (4u << 20)
+int kvbfp_decode_attention_noalloc(const kvbfp_layout* layout, const kvbfp_cache* cache,
+                                   int32_t n_q_heads, const void* q, kvbfp_dtype dtype,
+                                   const int32_t* seq_len_dev, int64_t max_len, float softmax_scale,
+                                   const int32_t* perm_k, const int32_t* perm_v, int32_t q_mant_bits,
+                                   void* out, void* hip_stream);
+
 /* Message describing the last error on the calling thread ("" if none).  Static storage. */
 const char* kvbfp_last_error(void);
 

@@ -14,6 +14,7 @@
 
 #include <cmath>
 #include <cstdint>
+#include <mutex>
 
 #include "decode_args.h"
 #include "decode_dev.h"
@@ -718,6 +719,58 @@ int kvbfp_decode_attention_paged(const kvbfp_layout* pool, const kvbfp_cache* ca
     x.paging = &pg;
     return decode_impl(pool, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v, out,
                        workspace, workspace_bytes, hip_stream, x);
+}
+
+// ---- kvbfp_decode_attention_noalloc: the partial results of the splits live in a file-scope device
+// array instead of a caller's workspace.  Every GPU holds its own copy of the array; its address on a
+// device is asked for once, with that device current, and kept.
+static __device__ __align__(256) unsigned char scratch[KVBFP_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (nullptr + recorded error on failure).
+void* scratch_on_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        fail(KVBFP_ERR_HIP, "decode_attention_noalloc: cannot identify the current device");
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            fail(KVBFP_ERR_HIP, "decode_attention_noalloc: hipGetSymbolAddress: %s", hipGetErrorString(e));
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
+
+int kvbfp_decode_attention_noalloc(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t n_q_heads,
+                                   const void* q, kvbfp_dtype dtype, const int32_t* seq_len_dev,
+                                   int64_t max_len, float softmax_scale, const int32_t* perm_k,
+                                   const int32_t* perm_v, int32_t q_mant_bits, void* out, void* hip_stream) {
+    clear_error();
+    // the size check comes first: a geometry that does not fit is refused before anything else happens
+    const size_t need = kvbfp_decode_workspace_bytes(L, n_q_heads, max_len);
+    if (need == 0) return fail(KVBFP_ERR_INVALID_ARG, "decode_attention_noalloc: bad layout, n_q_heads or max_len");
+    if (need > (size_t)KVBFP_NOALLOC_SCRATCH_BYTES)
+        return fail(KVBFP_ERR_WORKSPACE,
+                    "decode_attention_noalloc: this geometry needs %zu bytes of split partials, the built-in "
+                    "scratch holds %zu; use kvbfp_decode_attention with a workspace",
+                    need, (size_t)KVBFP_NOALLOC_SCRATCH_BYTES);
+    void* const ws = scratch_on_current_device();
+    if (!ws) return KVBFP_ERR_HIP;
+    DecodeExtras x;
+    x.q_mant_bits = q_mant_bits;
+    return decode_impl(L, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v, out, ws,
+                       (size_t)KVBFP_NOALLOC_SCRATCH_BYTES, hip_stream, x);
 }
 
 int kvbfp_decode_attention_profile(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t n_q_heads,

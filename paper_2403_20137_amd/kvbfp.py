@@ -27,7 +27,7 @@ EXPORTS = ["kvbfp_cache_bytes", "kvbfp_calibrate_perm", "kvbfp_permute_weights",
            "kvbfp_decode_attention", "kvbfp_decode_attention_qbfp", "kvbfp_append_decode_attention", "kvbfp_decode_attention_multi", "kvbfp_decode_attention_profile",
            "kvbfp_permute_rope", "kvbfp_decode_attention_rope",
            "kvbfp_quantize_append_paged", "kvbfp_dequantize_paged", "kvbfp_decode_workspace_bytes_paged",
-           "kvbfp_decode_attention_paged", "kvbfp_measure_stream_read",
+           "kvbfp_decode_attention_paged", "kvbfp_decode_attention_noalloc", "kvbfp_measure_stream_read",
            "kvbfp_last_error", "kvbfp_version"]
 
 
@@ -110,6 +110,9 @@ def lib():
         l.kvbfp_decode_attention_profile.argtypes = l.kvbfp_decode_attention_qbfp.argtypes + [C.POINTER(C.c_float)]
         l.kvbfp_measure_stream_read.argtypes = [C.POINTER(Layout), C.POINTER(CachePtrs), C.c_int64, C.c_int32,
                                                 C.c_void_p, C.c_void_p, C.POINTER(C.c_float)]
+        l.kvbfp_decode_attention_noalloc.argtypes = [C.POINTER(Layout), C.POINTER(CachePtrs), C.c_int32, C.c_void_p,
+                                                     C.c_int, C.c_void_p, C.c_int64, C.c_float, C.c_void_p,
+                                                     C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
         _lib = l
     return _lib
 
@@ -492,6 +495,24 @@ def decode_attention_multi(cache: Cache, q, max_len, softmax_scale, seq_len_dev=
                                               _dev_ptr(perm_k, torch.int32), _dev_ptr(perm_v, torch.int32),
                                               int(q_mant_bits), _dev_ptr(out), _dev_ptr(workspace), workspace.numel(),
                                               _stream_ptr(stream)))
+    return out
+
+
+NOALLOC_SCRATCH_BYTES = 4 << 20
+
+
+def decode_attention_noalloc(cache: Cache, q, max_len, softmax_scale, out, q_mant_bits=0, seq_len_dev=None,
+                             perm_k=None, perm_v=None, stream=None):
+    """DEVICE, async.  decode_attention_qbfp without a workspace: the split partials live in a fixed device
+    array inside the library.  `out` is the caller's (nothing is allocated here either)."""
+    L = cache.layout
+    if q.dim() != 3 or not q.is_contiguous() or out.shape != q.shape or out.dtype != q.dtype or not out.is_contiguous():
+        raise ValueError("q and out must be contiguous [batch][n_q_heads][head_dim] tensors of one dtype")
+    ptrs = cache.ptrs
+    _check(lib().kvbfp_decode_attention_noalloc(C.byref(L), C.byref(ptrs), q.shape[1], _dev_ptr(q), _TORCH_DT[q.dtype],
+                                                _dev_ptr(seq_len_dev, torch.int32), int(max_len), float(softmax_scale),
+                                                _dev_ptr(perm_k, torch.int32), _dev_ptr(perm_v, torch.int32),
+                                                int(q_mant_bits), _dev_ptr(out), _stream_ptr(stream)))
     return out
 
 

@@ -215,3 +215,12 @@ def test_misaligned_mantissa_planes_are_refused_before_any_launch():
         rc = lib.kvbfp_quantize_append(C.byref(L), C.byref(ptrs), C.c_void_p(0x50000), C.c_void_p(0x58000), kvbfp.BF16,
                                        1, 256, 256, 128, 0, None, None, None, None)
         assert rc == kvbfp.ERR_INVALID_ARG and "16-byte aligned" in kvbfp.last_error()
+
+
+def test_noalloc_entry_rejects_what_does_not_fit_without_touching_the_gpu():
+    L = kvbfp.make_layout(128, 32, 4, 2, 64, 4096)
+    assert kvbfp.decode_workspace_bytes(L, 32, 4096) > kvbfp.NOALLOC_SCRATCH_BYTES
+    ptrs = kvbfp.CachePtrs(0x10000, 0x20000, 0x30000, 0x40000)
+    rc = kvbfp.lib().kvbfp_decode_attention_noalloc(C.byref(L), C.byref(ptrs), 32, C.c_void_p(0x50000), kvbfp.BF16, None,
+                                                    4096, C.c_float(0.1), None, None, 0, C.c_void_p(0x60000), None)
+    assert rc == kvbfp.ERR_WORKSPACE and "scratch" in kvbfp.last_error()
