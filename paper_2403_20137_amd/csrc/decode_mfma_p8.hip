@@ -200,8 +200,8 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p8(DecodeArgs a, int dt
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const uint32_t r = FULL ? (uint32_t)(16 * u + j) : (uint32_t)min(16 * u + j, left - 1);
-            const u32x4 raw0 = *(const u32x4*)(kp + r * 128u + kchunk);
-            const u32x4 raw1 = *(const u32x4*)(kp + r * 128u + kchunk + 64u);
+            const u32x4 raw0 = __builtin_nontemporal_load((const u32x4*)(kp + r * 128u + kchunk));   // streamed once
+            const u32x4 raw1 = __builtin_nontemporal_load((const u32x4*)(kp + r * 128u + kchunk + 64u));
             const uint32_t E0 = kep[r * NB + keb0];
             const uint32_t E1 = (N == 128) ? E0 : (uint32_t)kep[r * NB + keb1];
             const float sh0 = scale_hi(E0), sl0 = scale_lo(E0);
@@ -272,7 +272,9 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p8(DecodeArgs a, int dt
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const uint32_t r = FULL ? (uint32_t)(16 * u + 4 * kg + i) : (uint32_t)min(16 * u + 4 * kg + i, left - 1);
-                const uint2 w = *(const uint2*)(vp + r * 128u + 8u * (uint32_t)j);
+                typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                const u32x2 wv = __builtin_nontemporal_load((const u32x2*)(vp + r * 128u + 8u * (uint32_t)j));   // streamed once
+                const uint2 w = make_uint2(wv[0], wv[1]);
                 const uint32_t E = vep[r * NB + veb];
                 const float sh = scale_hi(E), sl = scale_lo(E);
                 va[i] = unpack4(w.x, sh, sl);

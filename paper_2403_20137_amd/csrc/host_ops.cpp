@@ -80,7 +80,10 @@ SplitPlan plan_splits(const kvbfp_layout* L, int32_t n_q_heads, int64_t max_len)
     const int64_t units = (int64_t)L->batch * L->n_kv_heads;
     const int64_t tiles = (max_len + kTokenTile - 1) / kTokenTile;
     const bool sixteen = L->mant_bits == 4 && L->block <= 32 && n_q_heads / L->n_kv_heads > 8;
-    const int64_t target_wgs = 256 * (sixteen ? 2 : 3);
+#ifndef KVBFP_EXP_WGS_PER_CU
+#define KVBFP_EXP_WGS_PER_CU 3
+#endif
+    const int64_t target_wgs = 256 * (sixteen ? 2 : KVBFP_EXP_WGS_PER_CU);
     int64_t want = (target_wgs + units - 1) / units;
     if (want > tiles) want = tiles;
     if (want < 1) want = 1;

@@ -105,7 +105,13 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(QuantArgs a) {
         if (MODE != kElementwise) {
 #pragma unroll
             for (int i = 0; i < ESZ * 16 / 16; ++i)
-                raw[k].v[i] = live[k] ? ((const uint4*)(srow[k] + c0 * ESZ))[i] : make_uint4(0u, 0u, 0u, 0u);
+                if (live[k]) {
+                    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+                    const u32x4_t t = *((const u32x4_t*)(srow[k] + c0 * ESZ) + i);
+                    raw[k].v[i] = make_uint4(t[0], t[1], t[2], t[3]);
+                } else {
+                    raw[k].v[i] = make_uint4(0u, 0u, 0u, 0u);
+                }
         }
     }
 
