@@ -421,38 +421,63 @@ __device__ __forceinline__ uint32_t lds_addr(const void* p) {
 
 // Reads of DMA-staged data are written in assembly: the compiler's wait-count pass half-knows about
 // LDS DMA and would otherwise put a full vmcnt(0) in front of some of these loads, which serialises
-// the whole pipeline.  Each block waits for its own LDS results before returning.
-template <int OFF_M, int OFF_E, bool E16>
-__device__ __forceinline__ void lds_read_key_stage(uint32_t m_addr, uint32_t e_addr, u32x4& raw, uint32_t& e) {
-    if (E16)
-        asm volatile("ds_read_b128 %0, %2 offset:%4\n\tds_read_u16 %1, %3 offset:%5\n\ts_waitcnt lgkmcnt(0)"
-                     : "=&v"(raw), "=&v"(e) : "v"(m_addr), "v"(e_addr), "n"(OFF_M), "n"(OFF_E) : "memory");
-    else
-        asm volatile("ds_read_b128 %0, %2 offset:%4\n\tds_read_u8 %1, %3 offset:%5\n\ts_waitcnt lgkmcnt(0)"
-                     : "=&v"(raw), "=&v"(e) : "v"(m_addr), "v"(e_addr), "n"(OFF_M), "n"(OFF_E) : "memory");
+// the whole pipeline.  They come as issue / wait pairs for the software pipeline of the main loop: the
+// registers named at the issue are written when the LDS answers; the wait comes before their first use
+// and names them again, so that the compiler keeps them where they are in between.
+template <int OFF>
+__device__ __forceinline__ void lds_issue_b128(uint32_t addr, u32x4& v) {
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(v) : "v"(addr), "n"(OFF) : "memory");
 }
 template <int OFF>
-__device__ __forceinline__ uint2 lds_read_b64(uint32_t addr) {
-    uint64_t v;
-    asm volatile("ds_read_b64 %0, %1 offset:%2\n\ts_waitcnt lgkmcnt(0)" : "=&v"(v) : "v"(addr), "n"(OFF) : "memory");
-    return make_uint2((uint32_t)v, (uint32_t)(v >> 32));
+__device__ __forceinline__ void lds_issue_b64(uint32_t addr, uint64_t& v) {
+    asm volatile("ds_read_b64 %0, %1 offset:%2" : "=&v"(v) : "v"(addr), "n"(OFF) : "memory");
 }
-// Value stage U: dwords at m_addr + 256*(4U+i), exponent bytes at e_addr + 256*U + NB*i, i = 0..3.
-template <int U, int NB>
-__device__ __forceinline__ void lds_read_val_stage(uint32_t m_addr, uint32_t e_addr, uint32_t (&w)[4], uint32_t (&e)[4]) {
-    uint64_t w01, w23;
-    asm volatile("ds_read2st64_b32 %0, %6 offset0:%8 offset1:%9\n\t"
-                 "ds_read2st64_b32 %1, %6 offset0:%10 offset1:%11\n\t"
-                 "ds_read_u8 %2, %7 offset:%12\n\t"
-                 "ds_read_u8 %3, %7 offset:%13\n\t"
-                 "ds_read_u8 %4, %7 offset:%14\n\t"
-                 "ds_read_u8 %5, %7 offset:%15\n\t"
-                 "s_waitcnt lgkmcnt(0)"
-                 : "=&v"(w01), "=&v"(w23), "=&v"(e[0]), "=&v"(e[1]), "=&v"(e[2]), "=&v"(e[3])
-                 : "v"(m_addr), "v"(e_addr), "n"(4 * U), "n"(4 * U + 1), "n"(4 * U + 2), "n"(4 * U + 3),
-                   "n"(256 * U), "n"(256 * U + NB), "n"(256 * U + 2 * NB), "n"(256 * U + 3 * NB)
-                 : "memory");
-    w[0] = (uint32_t)w01; w[1] = (uint32_t)(w01 >> 32); w[2] = (uint32_t)w23; w[3] = (uint32_t)(w23 >> 32);
+// four reads of one or two bytes, STRIDE apart
+template <int OFF, int STRIDE, bool E16>
+__device__ __forceinline__ void lds_issue_4(uint32_t addr, uint32_t (&e)[4]) {
+    if (E16)
+        asm volatile("ds_read_u16 %0, %4 offset:%5\n\tds_read_u16 %1, %4 offset:%6\n\tds_read_u16 %2, %4 offset:%7\n\tds_read_u16 %3, %4 offset:%8"
+                     : "=&v"(e[0]), "=&v"(e[1]), "=&v"(e[2]), "=&v"(e[3])
+                     : "v"(addr), "n"(OFF), "n"(OFF + STRIDE), "n"(OFF + 2 * STRIDE), "n"(OFF + 3 * STRIDE) : "memory");
+    else
+        asm volatile("ds_read_u8 %0, %4 offset:%5\n\tds_read_u8 %1, %4 offset:%6\n\tds_read_u8 %2, %4 offset:%7\n\tds_read_u8 %3, %4 offset:%8"
+                     : "=&v"(e[0]), "=&v"(e[1]), "=&v"(e[2]), "=&v"(e[3])
+                     : "v"(addr), "n"(OFF), "n"(OFF + STRIDE), "n"(OFF + 2 * STRIDE), "n"(OFF + 3 * STRIDE) : "memory");
+}
+// value mantissas of stage U: dwords at m_addr + 256 * (4U + i), i = 0..3
+template <int U>
+__device__ __forceinline__ void lds_issue_val_mant(uint32_t m_addr, uint64_t& w01, uint64_t& w23) {
+    asm volatile("ds_read2st64_b32 %0, %2 offset0:%3 offset1:%4\n\tds_read2st64_b32 %1, %2 offset0:%5 offset1:%6"
+                 : "=&v"(w01), "=&v"(w23) : "v"(m_addr), "n"(4 * U), "n"(4 * U + 1), "n"(4 * U + 2), "n"(4 * U + 3) : "memory");
+}
+__device__ __forceinline__ void lds_wait(u32x4& a) { asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a) : : "memory"); }
+__device__ __forceinline__ void lds_wait(u32x4& a, uint32_t (&e)[4]) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a), "+v"(e[0]), "+v"(e[1]), "+v"(e[2]), "+v"(e[3]) : : "memory");
+}
+template <int HG>
+__device__ __forceinline__ void lds_wait(uint64_t& w01, uint64_t& w23, uint64_t (&pp)[HG]) {
+    if constexpr (HG == 1) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(w01), "+v"(w23), "+v"(pp[0]) : : "memory");
+    else if constexpr (HG == 2) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(w01), "+v"(w23), "+v"(pp[0]), "+v"(pp[1]) : : "memory");
+    else asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(w01), "+v"(w23), "+v"(pp[0]), "+v"(pp[1]), "+v"(pp[2]), "+v"(pp[3]) : : "memory");
+}
+__device__ __forceinline__ void lds_wait(u32x4 (&e)[4]) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(e[0]), "+v"(e[1]), "+v"(e[2]), "+v"(e[3]) : : "memory");
+}
+__device__ __forceinline__ void lds_wait(uint32_t (&e)[16]) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(e[0]), "+v"(e[1]), "+v"(e[2]), "+v"(e[3]), "+v"(e[4]), "+v"(e[5]), "+v"(e[6]), "+v"(e[7]),
+                 "+v"(e[8]), "+v"(e[9]), "+v"(e[10]), "+v"(e[11]), "+v"(e[12]), "+v"(e[13]), "+v"(e[14]), "+v"(e[15]) : : "memory");
+}
+
+// max over the 16 lanes of a DPP row, the shuffle folded into the max instruction (two wait states between
+// a vector write and a DPP read of the same register)
+__device__ __forceinline__ float row_max_dpp(float v) {
+    float r;
+    asm volatile("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+                 "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+                 "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+                 "s_nop 1\n\tv_max_f32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf"
+                 : "=&v"(r) : "v"(v));
+    return r;
 }
 
 // Cache policy of the DMA loads: the "nt" bit.  The cache is read once per call, and a read-only stream
@@ -473,16 +498,20 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
     // per-wavefront staging area
     constexpr int kKm = 0;                         // 4 stages x 1024 B key mantissas
     constexpr int kVm = kKm + 4096;                // 4 stages x 1024 B value mantissas
-    constexpr int kKe = kVm + 4096;                // 4 stages x 64 lanes x 4 B key exponents (own dword per lane)
-    constexpr int kVe = kKe + 1024;                // 4 stages x 256 B: 16 tokens x NB value exponent bytes (+ duplicates)
-    constexpr int kWaveBytes = kVe + 1024;
+    constexpr int kEt = kTileTok * NB;             // exponent bytes of a whole 64-token tile: one DMA dword per lane and 256 B
+    constexpr int kKe = kVm + 4096;                // key exponents [64 tokens][NB]
+    constexpr int kVe = kKe + kEt;                 // value exponents [64 tokens][NB]
+    constexpr int kWaveBytes = kVe + kEt;
+    constexpr int kExpDma = kEt / 256;             // DMA instructions per exponent tile (1 for blocks of 32, 2 for 16)
     // Keys go to the scaled FP8 x FP4 MFMA as raw nibbles: a block of 32 is exactly its MX block; a
     // block of 16 takes two products per 32 channels, each with the other block's nibbles zeroed.
     constexpr int kRings = kWaves * kWaveBytes;
     static_assert(kWaves * NH * kD * 4 + kWaves * NH * 8 <= kRings, "merge buffers alias the staging area");
     // The DMA rings are an LDS object of their own: the compiler waits for every outstanding DMA
     // before it touches an object that a DMA may write, and the set-up must not wait for the first tile.
-    __shared__ __align__(16) uint8_t smem[kRings];
+    // (padded so that at most three workgroups fit a compute unit: with four, placement over the units gets uneven)
+    constexpr int kSmem = kRings + HG * 4096 + NH * 16 >= 42 * 1024 ? kRings : 42 * 1024 - HG * 4096 - NH * 16;
+    __shared__ __align__(16) uint8_t smem[kSmem];
     // probabilities of the current tile, bf16 hi/lo limbs: [wave][HG][2 limbs][4 heads][64 tokens].  A separate
     // LDS object, so the compiler can tell its reads apart from the DMA targets inside smem.
     __shared__ __align__(16) uint16_t p_lds[kWaves][HG * 2 * 4 * kTileTok];
@@ -598,47 +627,40 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
     const int kd_row = lane >> 2, kd_chunk = (lane & 3) ^ ((lane >> 4) & 3);            // DMA lane -> (row, chunk)
     const uint32_t k_src = (uint32_t)kd_row * 64u + (uint32_t)kd_chunk * 16u;
     const uint32_t v_src = (uint32_t)vrow_of_slot * 64u + (uint32_t)vp_c * 16u;
-    const uint32_t ke_src = (uint32_t)j * NB + (N == 16 ? 4u * (uint32_t)(kg >> 1) : 0u);   // dword holding this lane's byte(s)
-    // value exponents: the stage needs 16*NB bytes = 4*NB dwords; all 64 lanes fetch (lanes beyond
-    // 4*NB repeat earlier dwords into the unused rest of the 256-byte stage area) so that no lane
-    // masking is needed
-    const uint32_t ve_src = (uint32_t)(lane & (4 * NB - 1)) * 4u;
+    const uint32_t e_src = (uint32_t)lane * 4u;     // exponents: dword `lane` (+64 per further instruction) of the tile's rows
 
-    // Fills stage u (keys or values) with the 16 tokens starting at token t of the split, which is row
-    // `row` of the planes (tile_row of its tile plus its offset inside the tile).  `left` is
-    // wave-uniform, so the ragged case is a scalar branch; rows past the last cached token re-read
-    // that token (left - 1 may be negative: earlier rows of the split are cached too).
-    auto fill_keys = [&](const int u, const int t, const int64_t row) {
-        const int left = n_tok - t;
-        const uint8_t* __restrict__ mp = k_mant + row * 64;
-        const uint8_t* __restrict__ ep = k_exp + row * NB;
-        uint8_t* const lm = wbase + kKm + u * 1024;
-        uint8_t* const le = wbase + kKe + u * 256;
-        if (left >= 16) {
-            __builtin_amdgcn_global_load_lds(KVBFP_GPTR(mp + k_src), KVBFP_LPTR(lm), 16, 0, kStreamAux);
-            __builtin_amdgcn_global_load_lds(KVBFP_GPTR(ep + ke_src), KVBFP_LPTR(le), 4, 0, kStreamAux);
+    // Re-fills of the staging area.  Mantissas: stage u of a tile that starts at token t of the split = plane
+    // row `row` (tile_row of the tile).  A full tile takes the immediate-offset form (the offset applies to the
+    // global and to the LDS address alike, 1024 bytes per stage in both); in a ragged one rows past the last
+    // cached token re-read that token.  `left` values are wave-uniform, so these are scalar branches.
+    auto fill_mant = [&](auto U, const bool keys, const bool tile_full, const int t, const int64_t row) {
+        constexpr int u = decltype(U)::value;
+        const uint8_t* __restrict__ mp = (keys ? k_mant : v_mant) + row * 64;
+        uint8_t* const lm = wbase + (keys ? kKm : kVm);
+        if (tile_full) {
+            __builtin_amdgcn_global_load_lds(KVBFP_GPTR(mp + (keys ? k_src : v_src)), KVBFP_LPTR(lm), 16, u * 1024, kStreamAux);
         } else {
-            const int mo = min(kd_row, left - 1) * 64 + kd_chunk * 16;
-            const int eo = min(j, left - 1) * NB + (N == 16 ? 4 * (kg >> 1) : 0);
-            __builtin_amdgcn_global_load_lds(KVBFP_GPTR(mp + mo), KVBFP_LPTR(lm), 16, 0, kStreamAux);
-            __builtin_amdgcn_global_load_lds(KVBFP_GPTR(ep + eo), KVBFP_LPTR(le), 4, 0, kStreamAux);
+            const int left = n_tok - (t + 16 * u);       // may be <= 0: then every lane re-reads the last cached token
+            const int r = keys ? kd_row : vrow_of_slot, c = keys ? kd_chunk : vp_c;
+            const int mo = (16 * u + min(r, left - 1)) * 64 + c * 16;
+            __builtin_amdgcn_global_load_lds(KVBFP_GPTR(mp + mo), KVBFP_LPTR(lm + u * 1024), 16, 0, kStreamAux);
         }
     };
-    auto fill_vals = [&](const int u, const int t, const int64_t row) {
-        const int left = n_tok - t;
-        const uint8_t* __restrict__ mp = v_mant + row * 64;
-        const uint8_t* __restrict__ ep = v_exp + row * NB;
-        uint8_t* const lm = wbase + kVm + u * 1024;
-        uint8_t* const le = wbase + kVe + u * 256;
-        if (left >= 16) {
-            __builtin_amdgcn_global_load_lds(KVBFP_GPTR(mp + v_src), KVBFP_LPTR(lm), 16, 0, kStreamAux);
-            __builtin_amdgcn_global_load_lds(KVBFP_GPTR(ep + ve_src), KVBFP_LPTR(le), 4, 0, kStreamAux);
+    // Exponents of a whole tile, [64 tokens][NB] as they lie in the plane.
+    auto fill_exp = [&](const bool keys, const bool tile_full, const int t, const int64_t row) {
+        const uint8_t* __restrict__ ep = (keys ? k_exp : v_exp) + row * NB;
+        uint8_t* const le = wbase + (keys ? kKe : kVe);
+        if (tile_full) {
+            __builtin_amdgcn_global_load_lds(KVBFP_GPTR(ep + e_src), KVBFP_LPTR(le), 4, 0, kStreamAux);
+            if (kExpDma == 2) __builtin_amdgcn_global_load_lds(KVBFP_GPTR(ep + e_src), KVBFP_LPTR(le), 4, 256, kStreamAux);
         } else {
-            const int mo = min(vrow_of_slot, left - 1) * 64 + vp_c * 16;
-            const int tok = min((int)(ve_src / NB), left - 1);
-            const int eo = tok * NB + (int)(ve_src % NB);
-            __builtin_amdgcn_global_load_lds(KVBFP_GPTR(mp + mo), KVBFP_LPTR(lm), 16, 0, kStreamAux);
-            __builtin_amdgcn_global_load_lds(KVBFP_GPTR(ep + eo), KVBFP_LPTR(le), 4, 0, kStreamAux);
+            const int left = n_tok - t;                    // >= 1
+#pragma unroll
+            for (int x = 0; x < kExpDma; ++x) {
+                const int byte = (int)e_src + 256 * x;
+                const int eo = min(byte / NB, left - 1) * NB + byte % NB;
+                __builtin_amdgcn_global_load_lds(KVBFP_GPTR(ep + eo), KVBFP_LPTR(le + 256 * x), 4, 0, kStreamAux);
+            }
         }
     };
 
@@ -680,10 +702,15 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
     const bool has_work = T_first < n_tok;
     if (has_work) {
         const int64_t row0 = tile_row(T_first);
-#pragma unroll
-        for (int u = 0; u < 4; ++u) fill_keys(u, T_first + 16 * u, row0 + 16 * u);
-#pragma unroll
-        for (int u = 0; u < 4; ++u) fill_vals(u, T_first + 16 * u, row0 + 16 * u);
+        const bool full0 = n_tok - T_first >= kTileTok;
+        static_for<4>([&](auto U) {
+            fill_mant(U, true, full0, T_first, row0);
+            if (decltype(U)::value == 0) fill_exp(true, full0, T_first, row0);
+        });
+        static_for<4>([&](auto U) {
+            fill_mant(U, false, full0, T_first, row0);
+            if (decltype(U)::value == 0) fill_exp(false, full0, T_first, row0);
+        });
     }
 
     // ---- query operand of the score product to LDS (whole workgroup) -------------------------------
@@ -725,7 +752,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
             int e = 0;
             if (mx > 0.f) (void)frexpf(mx, &e);            // mx = f * 2^e, f in [0.5, 1)
             int sh = mx > 0.f ? e - 8 : 0;                  // mx * 2^-sh in [128, 256)
-            sh = max(-115, min(118, sh));                   // every limb's scale byte sh - 4 limb + 127 stays in 0..254
+            sh = max(-114, min(118, sh));                   // every limb's scale byte sh - 4 limb + 127 - 1 stays in 0..254
             float v = qf[g * kD + c];
     #pragma unroll
             for (int limb = 0; limb < 4; ++limb) {
@@ -742,7 +769,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
             const u32x4 lo = *(const u32x4*)(q8 + (hg * 16 + j) * kD + kg * 32);
             const u32x4 hi = *(const u32x4*)(q8 + (hg * 16 + j) * kD + kg * 32 + 16);
             aq8[hg] = v8i{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
-            sa8[hg] = qsc[(hg * 16 + j) * 4 + kg];
+            sa8[hg] = qsc[(hg * 16 + j) * 4 + kg] - 1;      // - 1: the key operand below is magnitude / 2 at the block's own exponent byte
         }
         lds_barrier();                                    // the buffer goes over to the probabilities
     }
@@ -778,73 +805,140 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
 
     // ---- LDS read offsets of this lane inside a stage --------------------------------------------
     const uint32_t kq = lds_addr(wbase + kKm + (4 * j + (kg ^ ((j >> 2) & 3))) * 16);       // row j, chunk kg
-    const uint32_t keq = lds_addr(wbase + kKe + lane * 4 + (N == 32 ? kg : 2 * (kg & 1))); // own exponent byte(s)
+    const uint32_t keq = lds_addr(wbase + kKe + j * NB + (N == 32 ? kg : 2 * kg));         // + 16 NB per stage: own exponent byte(s)
     const uint32_t vq = lds_addr(wbase + kVm + kg * 64 + j * 4);                           // + i*256: row 4kg+i sits at position 4i+kg
-    const uint32_t veq = lds_addr(wbase + kVe + (4 * kg) * NB + (8 * j) / N);              // + u*256 + i*NB
+    // value exponents: blocks of 32 -> the 16 bytes of tokens 4kg..4kg+3 in one read per stage, this lane's block is
+    // byte j/4 of each dword; blocks of 16 -> byte (4kg + i) NB + j/2, one read each
+    const uint32_t veq = lds_addr(wbase + kVe + (4 * kg) * NB + (N == 32 ? 0 : (8 * j) / N));
+    const uint32_t ve_rot = (uint32_t)((8 * (j >> 2) + 32 - 23) & 31);   // rotation that brings byte j/4 to the exponent field
     uint16_t* const ps = &p_lds[wave][0];
     const uint32_t ps_rd = lds_addr(&p_lds[wave][(a_limb * 4 + a_head) * kTileTok + 4 * kg]);   // + head group and column tile
 
     if (has_work) {
+        // Software pipeline over the eight stages of a tile (K0..K3, V0..V3): the LDS reads of a stage are issued
+        // one stage ahead of its arithmetic, so their latency is covered by the arithmetic of the stage before,
+        // and a stage is re-filled for the wavefront's next tile as soon as its reads have returned.  The
+        // exponent bytes of a whole tile are read with its first stage (and re-filled right after).
         const int kStep = a.n_splits * kWaves * kTileTok;      // this workgroup's next 256-token tile
+        // (Where registers are short -- four head groups, or two with blocks of 32, which keep three wavefronts per
+        // SIMD -- every stage issues its own reads and waits for them; the probabilities look ahead with one group only.)
+        constexpr bool kPipe = HG == 1 || (HG == 2 && N == 16), kPipeP = HG == 1;
+        u32x4 rawk[kPipe ? 2 : 1];
+        uint32_t kexp[4];
+        uint64_t vw01[kPipe ? 2 : 1], vw23[kPipe ? 2 : 1], ppv[kPipeP ? 2 : 1][HG];
+        u32x4 vexp32[4];          // blocks of 32: per stage the exponent dwords of tokens 4kg..4kg+3
+        uint32_t vexp16[16];      // blocks of 16: per (stage, token) this lane's exponent byte
+        // DMA completes in issue order; per tile that is K0, key exponents, K1..K3, V0, value exponents, V1..V3.
+        // "The oldest stage still outstanding has landed" = at most (instructions issued after it) outstanding:
+        // 7 + kExpDma after the first stage of a plane (it ends with the exponents), 7 + 2 kExpDma after any other,
+        // while the next tile is being requested; on the last tile only what is left of the tile itself.
+        auto wait_dma = [&](const bool refilling, auto steady_tag, auto tail_tag) {
+            __builtin_amdgcn_sched_barrier(0);
+            if (refilling) __builtin_amdgcn_s_waitcnt(vmcnt_imm(decltype(steady_tag)::value));
+            else __builtin_amdgcn_s_waitcnt(vmcnt_imm(decltype(tail_tag)::value));
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        constexpr int kAfterFirst = 7 + kExpDma, kAfterOther = 7 + 2 * kExpDma;
+        auto issue_k0 = [&] {
+            lds_issue_b128<0>(kq, rawk[0]);
+            lds_issue_4<0, 16 * NB, N == 16>(keq, kexp);
+        };
+        // wait for the DMA of a stage and issue its LDS reads (`more`: the next tile is being requested meanwhile)
+        auto start_k = [&](auto U, const bool more) {             // key stage U >= 1
+            constexpr int u = decltype(U)::value;
+            wait_dma(more, std::integral_constant<int, kAfterOther>{}, std::integral_constant<int, 7 + kExpDma - u>{});
+            lds_issue_b128<u * 1024>(kq, rawk[kPipe ? (u & 1) : 0]);
+        };
+        auto start_v0 = [&](const bool more) {                    // value stage 0 and the tile's value exponents
+            wait_dma(more, std::integral_constant<int, kAfterFirst>{}, std::integral_constant<int, 3>{});
+            lds_issue_val_mant<0>(vq, vw01[0], vw23[0]);
+            if (N == 32) {
+                lds_issue_b128<0>(veq, vexp32[0]); lds_issue_b128<64>(veq, vexp32[1]);
+                lds_issue_b128<128>(veq, vexp32[2]); lds_issue_b128<192>(veq, vexp32[3]);
+            } else {
+                static_for<4>([&](auto V) {
+                    constexpr int v = decltype(V)::value;
+                    lds_issue_4<v * 16 * NB, NB, false>(veq, *(uint32_t(*)[4])&vexp16[4 * v]);
+                });
+            }
+        };
+        auto issue_p = [&](auto U, auto BUF) {                    // probabilities of value stage U
+            static_for<HG>([&](auto HGI) {
+                constexpr int hg = decltype(HGI)::value;
+                lds_issue_b64<(hg * 2 * 4 * kTileTok + 16 * decltype(U)::value) * 2>(ps_rd, ppv[decltype(BUF)::value][hg]);
+            });
+        };
+        auto start_v = [&](auto U, const bool more) {             // value stage U >= 1
+            constexpr int u = decltype(U)::value;
+            wait_dma(more, std::integral_constant<int, kAfterOther>{}, std::integral_constant<int, 3 - u>{});
+            lds_issue_val_mant<u>(vq, vw01[kPipe ? (u & 1) : 0], vw23[kPipe ? (u & 1) : 0]);
+            if constexpr (kPipeP) issue_p(U, std::integral_constant<int, u & 1>{});
+        };
         for (int T0 = T_first; T0 < n_tok; T0 += kStep) {
+            // the first stage of a tile is read here and not ahead, at the end of the tile before: a register with a
+            // read pending must not be live across the loop's back edge (the compiler may copy it there)
+            wait_dma(true, std::integral_constant<int, kAfterFirst>{}, std::integral_constant<int, 0>{});
+            issue_k0();
             const int T1 = T0 + kStep;
             const bool more = T1 < n_tok;            // wave-uniform
             const int64_t row1 = more ? tile_row(T1) : 0;
+            const bool full1 = n_tok - T1 >= kTileTok;       // the next tile is complete
             if (appends && more && T1 + kStep >= n_tok) {      // next comes the tile with the new row: its stores first
                 __builtin_amdgcn_sched_barrier(0);
                 __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
                 __builtin_amdgcn_sched_barrier(0);
             }
             const int left = n_tok - T0;
+            // masking is needed only where the tile is ragged or a head must not see all of it (several query tokens)
+            bool masked = left < kTileTok;
+#pragma unroll
+            for (int hg = 0; hg < HG; ++hg) masked = masked || __builtin_amdgcn_ballot_w64(lim[hg] - T0 < kTileTok) != 0;
 
             // ---------------- scores
             f32x4 s_acc[HG][4];
             static_for<4>([&](auto U) {
                 constexpr int u = decltype(U)::value;
+                constexpr int cur = kPipe ? (u & 1) : 0;
+                if constexpr (!kPipe && u > 0) start_k(U, more);
+                if (u == 0) lds_wait(rawk[0], kexp); else lds_wait(rawk[cur]);
                 __builtin_amdgcn_sched_barrier(0);
-                if (more) __builtin_amdgcn_s_waitcnt(vmcnt_imm(14)); else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+                if (more) {
+                    fill_mant(U, true, full1, T1, row1);
+                    if (u == 0) fill_exp(true, full1, T1, row1);
+                }
+                if constexpr (kPipe) {
+                    if constexpr (u < 3) start_k(std::integral_constant<int, u + 1>{}, more); else start_v0(more);
+                }
                 __builtin_amdgcn_sched_barrier(0);
-                u32x4 raw;
-                uint32_t kexp;
-                lds_read_key_stage<u * 1024, u * 256, N == 16>(kq, keq, raw, kexp);
+                const u32x4 raw = rawk[cur];
 #pragma unroll
                 for (int hg = 0; hg < HG; ++hg) s_acc[hg][u] = f32x4{0.f, 0.f, 0.f, 0.f};
-                {
-                    // magnitude/2 = FP4(s,0,m1,m0) + FP4(s,m2,0,0): two masked copies of the raw nibbles
-                    // are the B operands; the block's exponent byte (minus one for the halving) is
-                    // their E8M0 scale.
-                    if (N == 32) {
-                        const int sb = (int)__builtin_elementwise_sub_sat((unsigned short)kexp, (unsigned short)1);
-                        const v8i b1 = {(int)(raw[0] & 0xBBBBBBBBu), (int)(raw[1] & 0xBBBBBBBBu), (int)(raw[2] & 0xBBBBBBBBu),
-                                        (int)(raw[3] & 0xBBBBBBBBu), 0, 0, 0, 0};
-                        const v8i b2 = {(int)(raw[0] & 0xCCCCCCCCu), (int)(raw[1] & 0xCCCCCCCCu), (int)(raw[2] & 0xCCCCCCCCu),
-                                        (int)(raw[3] & 0xCCCCCCCCu), 0, 0, 0, 0};
-                        __builtin_amdgcn_sched_barrier(0);
-                        if (more) fill_keys(u, T1 + 16 * u, row1 + 16 * u);
-                        __builtin_amdgcn_sched_barrier(0);
+                // magnitude/2 = FP4(s,0,m1,m0) + FP4(s,m2,0,0): two masked copies of the raw nibbles are the B
+                // operands and the block's exponent byte is their E8M0 scale (the halving sits in the query's scale).
+                if (N == 32) {
+                    const int sb = (int)kexp[u];
+                    const v8i b1 = {(int)(raw[0] & 0xBBBBBBBBu), (int)(raw[1] & 0xBBBBBBBBu), (int)(raw[2] & 0xBBBBBBBBu),
+                                    (int)(raw[3] & 0xBBBBBBBBu), 0, 0, 0, 0};
+                    const v8i b2 = {(int)(raw[0] & 0xCCCCCCCCu), (int)(raw[1] & 0xCCCCCCCCu), (int)(raw[2] & 0xCCCCCCCCu),
+                                    (int)(raw[3] & 0xCCCCCCCCu), 0, 0, 0, 0};
 #pragma unroll
-                        for (int hg = 0; hg < HG; ++hg) {
-                            s_acc[hg][u] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aq8[hg], b1, s_acc[hg][u], 0, 4, 0, sa8[hg], 0, sb);
-                            s_acc[hg][u] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aq8[hg], b2, s_acc[hg][u], 0, 4, 0, sa8[hg], 0, sb);
-                        }
-                    } else {
-                        // the lane's 32 nibbles are two blocks of 16 (dwords 0-1 and 2-3) with an exponent each
-                        const int sb0 = (int)__builtin_elementwise_sub_sat((unsigned short)(kexp & 0xFFu), (unsigned short)1);
-                        const int sb1 = (int)__builtin_elementwise_sub_sat((unsigned short)(kexp >> 8), (unsigned short)1);
-                        const v8i lo1 = {(int)(raw[0] & 0xBBBBBBBBu), (int)(raw[1] & 0xBBBBBBBBu), 0, 0, 0, 0, 0, 0};
-                        const v8i lo2 = {(int)(raw[0] & 0xCCCCCCCCu), (int)(raw[1] & 0xCCCCCCCCu), 0, 0, 0, 0, 0, 0};
-                        const v8i hi1 = {0, 0, (int)(raw[2] & 0xBBBBBBBBu), (int)(raw[3] & 0xBBBBBBBBu), 0, 0, 0, 0};
-                        const v8i hi2 = {0, 0, (int)(raw[2] & 0xCCCCCCCCu), (int)(raw[3] & 0xCCCCCCCCu), 0, 0, 0, 0};
-                        __builtin_amdgcn_sched_barrier(0);
-                        if (more) fill_keys(u, T1 + 16 * u, row1 + 16 * u);
-                        __builtin_amdgcn_sched_barrier(0);
+                    for (int hg = 0; hg < HG; ++hg) {
+                        s_acc[hg][u] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aq8[hg], b1, s_acc[hg][u], 0, 4, 0, sa8[hg], 0, sb);
+                        s_acc[hg][u] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aq8[hg], b2, s_acc[hg][u], 0, 4, 0, sa8[hg], 0, sb);
+                    }
+                } else {
+                    // the lane's 32 nibbles are two blocks of 16 (dwords 0-1 and 2-3) with an exponent each
+                    const int sb0 = (int)(kexp[u] & 0xFFu), sb1 = (int)(kexp[u] >> 8);
+                    const v8i lo1 = {(int)(raw[0] & 0xBBBBBBBBu), (int)(raw[1] & 0xBBBBBBBBu), 0, 0, 0, 0, 0, 0};
+                    const v8i lo2 = {(int)(raw[0] & 0xCCCCCCCCu), (int)(raw[1] & 0xCCCCCCCCu), 0, 0, 0, 0, 0, 0};
+                    const v8i hi1 = {0, 0, (int)(raw[2] & 0xBBBBBBBBu), (int)(raw[3] & 0xBBBBBBBBu), 0, 0, 0, 0};
+                    const v8i hi2 = {0, 0, (int)(raw[2] & 0xCCCCCCCCu), (int)(raw[3] & 0xCCCCCCCCu), 0, 0, 0, 0};
 #pragma unroll
-                        for (int hg = 0; hg < HG; ++hg) {
-                            s_acc[hg][u] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aq8[hg], lo1, s_acc[hg][u], 0, 4, 0, sa8[hg], 0, sb0);
-                            s_acc[hg][u] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aq8[hg], lo2, s_acc[hg][u], 0, 4, 0, sa8[hg], 0, sb0);
-                            s_acc[hg][u] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aq8[hg], hi1, s_acc[hg][u], 0, 4, 0, sa8[hg], 0, sb1);
-                            s_acc[hg][u] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aq8[hg], hi2, s_acc[hg][u], 0, 4, 0, sa8[hg], 0, sb1);
-                        }
+                    for (int hg = 0; hg < HG; ++hg) {
+                        s_acc[hg][u] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aq8[hg], lo1, s_acc[hg][u], 0, 4, 0, sa8[hg], 0, sb0);
+                        s_acc[hg][u] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aq8[hg], lo2, s_acc[hg][u], 0, 4, 0, sa8[hg], 0, sb0);
+                        s_acc[hg][u] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aq8[hg], hi1, s_acc[hg][u], 0, 4, 0, sa8[hg], 0, sb1);
+                        s_acc[hg][u] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aq8[hg], hi2, s_acc[hg][u], 0, 4, 0, sa8[hg], 0, sb1);
                     }
                 }
             });
@@ -853,14 +947,14 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
 #pragma unroll
             for (int hg = 0; hg < HG; ++hg) {
                 float s[4];
-                float tmax = -INFINITY;
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const float v = (s_acc[hg][u][0] + s_acc[hg][u][1]) + (s_acc[hg][u][2] + s_acc[hg][u][3]);   // the limb rows
-                    s[u] = (16 * u + j < min(left, lim[hg] - T0)) ? v : -INFINITY;
-                    tmax = fmaxf(tmax, s[u]);
+                for (int u = 0; u < 4; ++u) s[u] = (s_acc[hg][u][0] + s_acc[hg][u][1]) + (s_acc[hg][u][2] + s_acc[hg][u][3]);   // the limb rows
+                if (masked) {
+                    const int vis = min(left, lim[hg] - T0);
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) s[u] = (16 * u + j < vis) ? s[u] : -INFINITY;
                 }
-                tmax = row_max(tmax);       // -inf only if this head sees none of the tile (several query tokens)
+                const float tmax = row_max_dpp(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])));   // -inf only if this head sees none of the tile
                 const float m_new = fmaxf(m_run[hg], tmax);
                 const float m_ref = m_new == -INFINITY ? 0.f : m_new;
                 const float alpha = exp2_raw(m_run[hg] - m_ref);
@@ -868,11 +962,12 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
                 float psum = 0.f;
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
+                    // two bf16 limbs: the upper half of the fp32 pattern as it is, and the rest rounded
                     const float pw = exp2_raw(s[u] - m_p);
-                    const __bf16 ph = (__bf16)pw;
-                    const __bf16 pl = (__bf16)(pw - (float)ph);
-                    psum += (float)ph + (float)pl;
-                    ps[((hg * 2 + 0) * 4 + kg) * kTileTok + 16 * u + j] = __builtin_bit_cast(unsigned short, ph);
+                    const uint32_t hi_bits = __float_as_uint(pw) & 0xFFFF0000u;
+                    const __bf16 pl = (__bf16)(pw - __uint_as_float(hi_bits));
+                    psum += pw;
+                    ps[((hg * 2 + 0) * 4 + kg) * kTileTok + 16 * u + j] = (uint16_t)(hi_bits >> 16);
                     ps[((hg * 2 + 1) * 4 + kg) * kTileTok + 16 * u + j] = __builtin_bit_cast(unsigned short, pl);
                 }
                 l_run[hg] = l_run[hg] * alpha + psum;
@@ -885,33 +980,43 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (kPipeP) issue_p(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
 
             // ---------------- values
             static_for<4>([&](auto U) {
                 constexpr int u = decltype(U)::value;
+                constexpr int cur = kPipe ? (u & 1) : 0;
+                constexpr int pc = kPipeP ? (u & 1) : 0;
+                if constexpr (!kPipe) { if constexpr (u == 0) start_v0(more); else start_v(U, more); }
+                if constexpr (!kPipeP) issue_p(U, std::integral_constant<int, 0>{});
+                lds_wait<HG>(vw01[cur], vw23[cur], ppv[pc]);
+                if (u == 0) { if (N == 32) lds_wait(vexp32); else lds_wait(vexp16); }
                 __builtin_amdgcn_sched_barrier(0);
-                if (more) __builtin_amdgcn_s_waitcnt(vmcnt_imm(14)); else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+                if (more) {
+                    fill_mant(U, false, full1, T1, row1);
+                    if (u == 0) fill_exp(false, full1, T1, row1);
+                }
+                if constexpr (kPipe && u < 3) start_v(std::integral_constant<int, u + 1>{}, more);
                 __builtin_amdgcn_sched_barrier(0);
-                uint32_t vw[4], ve[4];
-                lds_read_val_stage<u, NB>(vq, veq, vw, ve);
-                uint2 pp[HG];
-                static_for<HG>([&](auto HGI) {
-                    constexpr int hg = decltype(HGI)::value;
-                    pp[hg] = lds_read_b64<(hg * 2 * 4 * kTileTok + 16 * u) * 2>(ps_rd);
-                });
-                __builtin_amdgcn_sched_barrier(0);
-                if (more) fill_vals(u, T1 + 16 * u, row1 + 16 * u);
-                __builtin_amdgcn_sched_barrier(0);
+                const uint32_t vw[4] = {(uint32_t)vw01[cur], (uint32_t)(vw01[cur] >> 32), (uint32_t)vw23[cur], (uint32_t)(vw23[cur] >> 32)};
                 Unpacked vv[4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) vv[i] = unpack8(vw[i], scale_operand(ve[i]));
+                for (int i = 0; i < 4; ++i) {
+                    // scale operand: the exponent byte in the exponent field (the conversion looks at nothing else:
+                    // for blocks of 32 the other bytes of the dword stay where the rotation leaves them)
+                    const float sc = N == 32 ? __uint_as_float(__builtin_amdgcn_alignbit(vexp32[u][i], vexp32[u][i], ve_rot))
+                                             : scale_operand(vexp16[4 * u + i]);
+                    vv[i] = unpack8(vw[i], sc);
+                }
 #pragma unroll
                 for (int hg = 0; hg < HG; ++hg) {
+                    const uint32_t px = (uint32_t)ppv[pc][hg], py = (uint32_t)(ppv[pc][hg] >> 32);
                     uint32_t ar[4];
-                    ar[0] = __builtin_amdgcn_perm(pp[hg].x, pp[hg].x, sel_even);
-                    ar[1] = __builtin_amdgcn_perm(pp[hg].x, pp[hg].x, sel_odd);
-                    ar[2] = __builtin_amdgcn_perm(pp[hg].y, pp[hg].y, sel_even);
-                    ar[3] = __builtin_amdgcn_perm(pp[hg].y, pp[hg].y, sel_odd);
+                    ar[0] = __builtin_amdgcn_perm(px, px, sel_even);
+                    ar[1] = __builtin_amdgcn_perm(px, px, sel_odd);
+                    ar[2] = __builtin_amdgcn_perm(py, py, sel_even);
+                    ar[3] = __builtin_amdgcn_perm(py, py, sel_odd);
                     const bf16x8 ap = __builtin_bit_cast(bf16x8, u32x4{ar[0], ar[1], ar[2], ar[3]});
 #pragma unroll
                     for (int m = 0; m < 4; ++m) {
@@ -920,9 +1025,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
                     }
                 }
             });
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            // (the next tile writes its probabilities after its score phase; every read of this tile's has returned)
         }
     }
 
