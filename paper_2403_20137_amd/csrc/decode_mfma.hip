@@ -678,8 +678,13 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
         const int64_t idx = kvbfp::query_row(a, b, kvh, a.g_base + min(g, a.g_cnt - 1)) * kD + c;   // clamped: rows beyond the count are zeroed below
         q_bits[k] = dt == KVBFP_F32 ? ((const uint32_t*)a.q)[idx] : (uint32_t)((const uint16_t*)a.q)[idx];
     }
-    int perm_c = 0;
-    if (a.perm_k && tid < kD) perm_c = a.perm_k[kvh * kD + tid];
+    // This thread builds the operand bytes at position `qpos` of the heads tid / 128 + 2k.  FP8 operand layout
+    // (measured): byte i of lane-group g is channel 64*(i/16) + 16*g + i%16, and the E8M0 scale of channel block kb
+    // (32 consecutive channels) is taken from lane-group kb.
+    const int qpos = tid & (kD - 1);
+    const int qchan = (qpos & 16) ? 64 + 16 * (qpos >> 5) + (qpos & 15) : 16 * (qpos >> 5) + (qpos & 15);
+    int perm_c = qchan;                 // source channel of cache channel qchan
+    if (a.perm_k) perm_c = a.perm_k[kvh * kD + qchan];
     auto lds_barrier = [] { lds_only_barrier(); };
     // The permuted (and, on request, BFP-cast) queries wait in the probability buffer, which is free
     // until the main loop; the operand builders below read them from there.  The raw values go to LDS
@@ -696,7 +701,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
         else f = __uint_as_float(q_bits[k] << 16);
         qr[tid + 256 * k] = g < a.g_cnt ? f : 0.f;
     }
-    if (a.perm_k && tid < kD) scratch[tid] = perm_c & (kD - 1);   // a valid permutation is unchanged; keeps LDS reads in range
+    perm_c &= kD - 1;                   // a valid permutation is unchanged; keeps LDS reads in range
 
     const int T_first = wave * kTileTok;
     const bool has_work = T_first < n_tok;
@@ -713,58 +718,57 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
         });
     }
 
-    // ---- query operand of the score product to LDS (whole workgroup) -------------------------------
+    // ---- query operand of the score product (whole workgroup) ---------------------------------------
     v8i aq8[HG];           // row 4*head + limb (4 FP8 limbs), one MFMA of 128 channels
     int sa8[HG];           // E8M0 scale of this lane's 32 query values
-    if (a.perm_k) {
-        float q_perm[kQPerThread];
-        lds_barrier();
+    {
+        // Each block of 32 query values shares a power-of-two scale 2^sh chosen so that the largest lands in
+        // [128, 256); limb l holds the FP8 rounding of the residual at scale 2^(sh - 4l), so four limbs carry 16
+        // bits relative to the block's maximum.  A wavefront holds 64 consecutive operand positions of one head:
+        // the 16-lane rows r and r + 2 are the two halves of one block of 32 channels, so the block maximum is a
+        // DPP row reduction and one exchange across 32 lanes.
+        float qv[kQPerThread];             // q'[head][qchan] * softmax_scale * log2(e)
+        lds_barrier();                     // the raw queries are in LDS
+        if (a.q_mant_bits) {               // query cast to BFP: reorder in LDS, cast there (blocks may span wavefronts)
+            float q_perm[kQPerThread];
+#pragma unroll
+            for (int k = 0; k < kQPerThread; ++k) q_perm[k] = qr[((tid + 256 * k) / kD) * kD + perm_c];
+            lds_barrier();
+#pragma unroll
+            for (int k = 0; k < kQPerThread; ++k) qr[((tid + 256 * k) / kD) * kD + qchan] = q_perm[k];
+            lds_barrier();
+            bfp_round_queries(qr, (uint32_t*)scratch, NH, a.log2_block, a.q_mant_bits);
+#pragma unroll
+            for (int k = 0; k < kQPerThread; ++k) qv[k] = qr[((tid + 256 * k) / kD) * kD + qchan] * a.scale_log2e;
+            lds_barrier();                 // the limbs below overwrite the scratch area
+        } else {
+#pragma unroll
+            for (int k = 0; k < kQPerThread; ++k) qv[k] = qr[((tid + 256 * k) / kD) * kD + perm_c] * a.scale_log2e;
+        }
+        uint8_t* q8 = (uint8_t*)(qr + NH * kD);           // [NH * 4 limb rows][kD positions], beside the fp32 values
+        uint8_t* qsc = qsc_lds;
+        const int kb = qchan >> 5;
 #pragma unroll
         for (int k = 0; k < kQPerThread; ++k) {
-            const int i = tid + 256 * k;
-            q_perm[k] = qr[(i / kD) * kD + scratch[i % kD]];
-        }
-        lds_barrier();
-#pragma unroll
-        for (int k = 0; k < kQPerThread; ++k) qr[tid + 256 * k] = q_perm[k];
-    }
-    lds_barrier();
-    if (a.q_mant_bits) bfp_round_queries(qr, (uint32_t*)scratch, NH, a.log2_block, a.q_mant_bits);
-    {
-        // FP8 operand layout (measured): byte i of lane-group g is channel 64*(i/16) + 16*g + i%16, while
-        // the E8M0 scale of channel block kb (32 consecutive channels) is taken from lane-group kb.
-        // Each block of 32 query values shares a power-of-two scale 2^sh chosen so that the largest
-        // lands in [128, 256); limb l holds the FP8 rounding of the residual at scale 2^(sh - 4l), so four
-        // limbs carry 16 bits relative to the block's maximum.
-        float* qf = qr;                                   // scaled in place
-        uint8_t* q8 = (uint8_t*)(qr + NH * kD);           // over the scratch area, which is done with
-        uint8_t* qsc = qsc_lds;
-        for (int i = tid; i < NH * kD; i += 256) {
-            qf[i] = qr[i] * a.scale_log2e;
-        }
-        lds_barrier();
-        for (int i = tid; i < NH * kD; i += 256) {
-            const int g = i / kD, pos = i % kD, ga = pos >> 5, ii = pos & 31;
-            const int c = ii < 16 ? 16 * ga + ii : 64 + 16 * ga + (ii - 16);
-            const int kb = c >> 5;
-            float mx = 0.f;
-            for (int t = 0; t < 32; ++t) mx = fmaxf(mx, fabsf(qf[g * kD + 32 * kb + t]));
+            const int g = (tid + 256 * k) / kD;
+            float mx = row_max(fabsf(qv[k]));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
             int e = 0;
             if (mx > 0.f) (void)frexpf(mx, &e);            // mx = f * 2^e, f in [0.5, 1)
             int sh = mx > 0.f ? e - 8 : 0;                  // mx * 2^-sh in [128, 256)
             sh = max(-114, min(118, sh));                   // every limb's scale byte sh - 4 limb + 127 - 1 stays in 0..254
-            float v = qf[g * kD + c];
-    #pragma unroll
+            float v = qv[k];
+#pragma unroll
             for (int limb = 0; limb < 4; ++limb) {
                 const int sl = sh - 4 * limb;
                 const uint32_t packed = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(ldexpf(v, -sl), 0.f, 0, false);
                 v -= ldexpf(__builtin_amdgcn_cvt_f32_fp8((int)packed, 0), sl);
-                q8[(4 * g + limb) * kD + pos] = (uint8_t)(packed & 0xFFu);
-                if ((c & 31) == 0) qsc[(4 * g + limb) * 4 + kb] = (uint8_t)(sl + 127);
+                q8[(4 * g + limb) * kD + qpos] = (uint8_t)(packed & 0xFFu);
+                if ((qchan & 31) == 0) qsc[(4 * g + limb) * 4 + kb] = (uint8_t)(sl + 127);
             }
         }
         lds_barrier();
-    #pragma unroll
+#pragma unroll
         for (int hg = 0; hg < HG; ++hg) {
             const u32x4 lo = *(const u32x4*)(q8 + (hg * 16 + j) * kD + kg * 32);
             const u32x4 hi = *(const u32x4*)(q8 + (hg * 16 + j) * kD + kg * 32 + 16);
