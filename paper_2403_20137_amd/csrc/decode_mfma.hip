@@ -878,25 +878,19 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
             lds_issue_val_mant<u>(vq, vw01[kPipe ? (u & 1) : 0], vw23[kPipe ? (u & 1) : 0]);
             if constexpr (kPipeP) issue_p(U, std::integral_constant<int, u & 1>{});
         };
-        for (int T0 = T_first; T0 < n_tok; T0 += kStep) {
+        // One tile.  STEADY: this tile is complete and seen whole by every head, and a complete next tile is being
+        // requested -- the common case, compiled without the ragged-tile branches, clamps and masks.
+        auto tile_body = [&](auto steady_tag, const int T0, const int T1, const bool more_rt, const bool full1_rt,
+                             const bool masked_rt, const int64_t row1) {
+            constexpr bool STEADY = decltype(steady_tag)::value;
+            const bool more = STEADY ? true : more_rt;
+            const bool full1 = STEADY ? true : full1_rt;
+            const bool masked = STEADY ? false : masked_rt;
+            const int left = n_tok - T0;
             // the first stage of a tile is read here and not ahead, at the end of the tile before: a register with a
             // read pending must not be live across the loop's back edge (the compiler may copy it there)
             wait_dma(true, std::integral_constant<int, kAfterFirst>{}, std::integral_constant<int, 0>{});
             issue_k0();
-            const int T1 = T0 + kStep;
-            const bool more = T1 < n_tok;            // wave-uniform
-            const int64_t row1 = more ? tile_row(T1) : 0;
-            const bool full1 = n_tok - T1 >= kTileTok;       // the next tile is complete
-            if (appends && more && T1 + kStep >= n_tok) {      // next comes the tile with the new row: its stores first
-                __builtin_amdgcn_sched_barrier(0);
-                __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            const int left = n_tok - T0;
-            // masking is needed only where the tile is ragged or a head must not see all of it (several query tokens)
-            bool masked = left < kTileTok;
-#pragma unroll
-            for (int hg = 0; hg < HG; ++hg) masked = masked || __builtin_amdgcn_ballot_w64(lim[hg] - T0 < kTileTok) != 0;
 
             // ---------------- scores
             f32x4 s_acc[HG][4];
@@ -1030,6 +1024,23 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
                 }
             });
             // (the next tile writes its probabilities after its score phase; every read of this tile's has returned)
+        };
+        for (int T0 = T_first; T0 < n_tok; T0 += kStep) {
+            const int T1 = T0 + kStep;
+            const bool more = T1 < n_tok;            // wave-uniform
+            const int64_t row1 = more ? tile_row(T1) : 0;
+            const bool full1 = n_tok - T1 >= kTileTok;       // the next tile is complete
+            if (appends && more && T1 + kStep >= n_tok) {      // next comes the tile with the new row: its stores first
+                __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // masking is needed only where the tile is ragged or a head must not see all of it (several query tokens)
+            bool masked = n_tok - T0 < kTileTok;
+#pragma unroll
+            for (int hg = 0; hg < HG; ++hg) masked = masked || __builtin_amdgcn_ballot_w64(lim[hg] - T0 < kTileTok) != 0;
+            if (more && full1 && !masked) tile_body(std::true_type{}, T0, T1, true, true, false, row1);
+            else tile_body(std::false_type{}, T0, T1, more, full1, masked, row1);
         }
     }
 
