@@ -98,6 +98,19 @@ class LayerRing:
             self.append(i)
             self.decode(i)
 
+    def split_pass_ring_us(self, n_launches, q_mant_bits=0):
+        """The split pass launched n_launches times back to back over the ring (HIP events on the stream around
+        the batch, inside the library): average (split us, combine us) per launch."""
+        _, split_ms, combine_ms = kvbfp.decode_attention_profile_ring(
+            self.caches, n_launches, self.q, self.S_max, self.scale, q_mant_bits, perm_k=self.perm_k, perm_v=self.perm_v,
+            out=self.out, workspace=self.workspace)
+        return split_ms * 1e3, combine_ms * 1e3
+
+    def stream_read_us(self, i):
+        """Plain read of exactly the cache bytes one decode call streams (no arithmetic): the machine's ceiling."""
+        units = self.w.batch * self.w.n_kv_heads                      # three workgroups per compute unit, like the split pass
+        return kvbfp.measure_stream_read(self.caches[i % len(self.caches)], self.S_max, max(1, 768 // units)) * 1e3
+
     def decode_kernels(self, i, q_mant_bits=0):
         """The same decode call with HIP events around each of its two kernels: (split us, combine us)."""
         _, split_ms, combine_ms = kvbfp.decode_attention_profile(
@@ -248,6 +261,51 @@ def bulk_quantize_rate(device="cuda", reps=5):
             "with_perm_us_median": float(np.median(us_perm)), "with_perm_gelem_s": elems / np.median(us_perm) / 1e3}
 
 
+def profile_counters():
+    """Counters taken from the tracked rocprofv3 summaries (profiles/counters.json): HBM traffic of the split pass
+    (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy) and its vector-ALU busy fraction.  Not measured by this run."""
+    path = os.path.join(ROOT, "profiles", "counters.json")
+    try:
+        return json.load(open(path))
+    except Exception:
+        return {}
+
+
+def workload_entry(name, steps, batches=5):
+    """One workload: split pass (ring of caches, back-to-back launches), whole call, plain streaming read."""
+    w = synth.WORKLOADS[name]
+    n_layers = min(64, max(2, -(-1_100_000_000 // w.cache_bytes(w.seq + 1))))
+    ring = LayerRing(w, n_layers)
+    dec_bytes, _ = algorithmic_bytes(w, w.seq + 1)
+    n = max(n_layers, min(steps, 32))
+    ring.split_pass_ring_us(n)                                   # warm-up
+    runs = np.array([ring.split_pass_ring_us(n) for _ in range(batches)])
+    split, combine = runs[:, 0], runs[:, 1]
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(max(steps, 12))]
+    for i, (e0, e1) in enumerate(ev):
+        e0.record()
+        ring.decode(i)
+        e1.record()
+    torch.cuda.synchronize()
+    call = np.array([a.elapsed_time(b) for a, b in ev])[2:] * 1e3
+    stream = np.array([ring.stream_read_us(i) for i in range(10)])[2:]
+    counters = profile_counters().get(name, {})
+    entry = {"algorithmic_bytes": dec_bytes, "layer_caches_in_ring": n_layers,
+             "split_pass_us_avg": float(split.mean()), "split_pass_us_min": float(split.min()),
+             "combine_pass_us_avg": float(combine.mean()),
+             "split_pass_gb_s": dec_bytes / float(split.mean()) / 1e3,
+             "split_pass_frac_of_hbm_peak": dec_bytes / float(split.mean()) / 1e3 / HBM_PEAK_GBS,
+             "whole_call_us_median": float(np.median(call)), "whole_call_us_min": float(call.min()),
+             "whole_call_gb_s": dec_bytes / float(np.median(call)) / 1e3,
+             "whole_call_frac_of_hbm_peak": dec_bytes / float(np.median(call)) / 1e3 / HBM_PEAK_GBS,
+             "stream_read_us_median": float(np.median(stream)),
+             "stream_read_gb_s": dec_bytes / float(np.median(stream)) / 1e3,
+             "valu_busy_from_profile": counters.get("valu_busy"), "hbm_traffic_bytes_from_profile": counters.get("traffic")}
+    del ring
+    torch.cuda.empty_cache()
+    return entry
+
+
 def device_info():
     """Name, compute units and current clocks of the GPU the numbers were taken on.  The clocks are read from
     the driver's sysfs files (the level marked '*' in pp_dpm_sclk / pp_dpm_mclk); no other program is started."""
@@ -328,24 +386,31 @@ def main():
         sec_per_step = time_graph_steps(ring, capture_step_graphs(ring), args.steps, args.warmup)
     value = (dec_bytes + app_bytes) / sec_per_step / 1e9
 
-    # The kernel that streams the cache (split pass), timed by itself with HIP events on its stream.
+    # The kernel that streams the cache (split pass): `steps` launches back to back over the ring, HIP events on the
+    # launch stream around the batch (inside the library), several batches; its average duration per launch.
+    # Beside it: events around single launches (each interval then holds one launch latency), and a plain read of
+    # the same bytes with no arithmetic -- what a read-only kernel of this size reaches on this machine.
+    n_batch = max(n_layers, args.steps)
+    ring.split_pass_ring_us(n_batch)
+    batch_runs = np.array([ring.split_pass_ring_us(n_batch) for _ in range(6)])
+    split_avg_us, combine_avg_us = float(batch_runs[:, 0].mean()), float(batch_runs[:, 1].mean())
     kern = np.array([ring.decode_kernels(args.warmup + i) for i in range(args.steps)])
-    split_us, combine_us = kern[:, 0], kern[:, 1]
-    split_avg_s = float(split_us.mean()) * 1e-6
-    roofline = {"bound": "hbm", "achieved": dec_bytes / split_avg_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": dec_bytes / split_avg_s / 1e9 / HBM_PEAK_GBS, "traffic": None,
+    single_us = kern[:, 0]
+    stream_us = np.array([ring.stream_read_us(i) for i in range(14)])[2:]
+    counters = profile_counters().get(w.name, {})
+    roofline = {"bound": "hbm", "achieved": dec_bytes / split_avg_us / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": dec_bytes / split_avg_us / 1e3 / HBM_PEAK_GBS, "traffic": counters.get("traffic"),
                 "kernel": "decode attention split pass (the kernel that reads the packed cache)",
-                "bytes_per_launch": dec_bytes, "avg_launch_us": float(split_us.mean()),
-                "median_launch_us": float(np.median(split_us)), "min_launch_us": float(split_us.min()),
-                "combine_pass_avg_us": float(combine_us.mean()),
+                "bytes_per_launch": dec_bytes, "avg_launch_us": split_avg_us,
+                "launches_timed": int(6 * n_batch), "min_batch_avg_us": float(batch_runs[:, 0].min()),
+                "single_launch_event_interval_us_median": float(np.median(single_us)),
+                "combine_pass_avg_us": combine_avg_us,
                 "whole_call_avg_us": float(dec_us.mean()),
-                "whole_call_frac": dec_bytes / (float(dec_us.mean()) * 1e-6) / 1e9 / HBM_PEAK_GBS}
-    traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(traffic_file):
-        try:
-            roofline["traffic"] = json.load(open(traffic_file)).get(w.name)
-        except Exception:
-            pass
+                "whole_call_frac": dec_bytes / (float(dec_us.mean()) * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                "stream_read_us_median": float(np.median(stream_us)),
+                "stream_read_gb_s": dec_bytes / float(np.median(stream_us)) / 1e3,
+                "frac_of_stream_read": float(np.median(stream_us)) / split_avg_us,
+                "valu_busy_from_profile": counters.get("valu_busy")}
 
     result = {
         "metric": "BFP-KV decode attention HBM GB/s (% of peak); quantize-append Gelem/s",
@@ -364,9 +429,17 @@ def main():
         "roofline": roofline,
     }
     if not args.no_extra:
-        try:
-            q8 = np.array([ring.decode_kernels(i, q_mant_bits=8)[0] for i in range(min(args.steps, 20))])
-            result["decode_split_us_median_query_bfp8"] = float(np.median(q8))
+        def extra(key, fn):
+            """Every extra figure stands for itself: a failure is reported under its own key, never hidden."""
+            try:
+                result[key] = fn()
+            except Exception as e:
+                result[key] = {"error": repr(e)}
+
+        def query_bfp8():
+            return float(np.median([ring.decode_kernels(i, q_mant_bits=8)[0] for i in range(min(args.steps, 20))]))
+
+        def single_cache_hot():
             # the same call over ONE cache again and again: whatever of it stays in the 256 MB last-level
             # cache is not read from HBM, so this figure is LLC-assisted and not a bandwidth claim
             hot = []
@@ -377,7 +450,9 @@ def main():
                 e1.record()
                 hot.append((e0, e1))
             torch.cuda.synchronize()
-            result["decode_us_median_single_cache_llc_assisted"] = float(np.median([a.elapsed_time(b) for a, b in hot][2:]) * 1e3)
+            return float(np.median([a.elapsed_time(b) for a, b in hot][2:]) * 1e3)
+
+        def four_query_tokens():
             # four query tokens per sequence (G * 4 virtual heads per kv-head) over the same caches
             q4 = torch.stack([ring.q] * 4, dim=1).contiguous()
             ws4 = torch.empty((kvbfp.decode_workspace_bytes(ring.layout, w.n_q_heads * 4, ring.S_max),), dtype=torch.uint8,
@@ -390,7 +465,9 @@ def main():
                                              perm_v=ring.perm_v, out=out4, workspace=ws4)
                 e1.record()
             torch.cuda.synchronize()
-            result["decode_4_query_tokens_us_median"] = float(np.median([a.elapsed_time(b) for a, b in ev][2:]) * 1e3)
+            return float(np.median([a.elapsed_time(b) for a, b in ev][2:]) * 1e3)
+
+        def rotary_at_read():
             # the same caches read as if their keys had been stored before the rotary embedding: rotation at
             # read with the reordered parameters (Alg. 1 step 5), split pass only, HIP events inside the call
             theta = (10000.0 ** (-np.arange(w.head_dim // 2, dtype=np.float64) / (w.head_dim // 2))).astype(np.float32)
@@ -399,15 +476,30 @@ def main():
             rope_us = [kvbfp.decode_attention_rope(ring.caches[i % len(ring.caches)], ring.q, ring.S_max, ring.scale, *rp,
                                                    perm_k=ring.perm_k, perm_v=ring.perm_v, out=ring.out,
                                                    workspace=ring.workspace, profile=True)[1] * 1e3 for i in range(8)]
-            result["decode_split_us_median_rotary_at_read"] = float(np.median(rope_us[2:]))
-            result["decode_split_us_median_paged_256"] = paged_split_us(ring)
-            result["quantize_append_bulk"] = bulk_quantize_rate()
-        except Exception as e:      # reported, never hidden
-            result["quantize_append_bulk"] = {"error": repr(e)}
+            return float(np.median(rope_us[2:]))
+
+        extra("decode_split_us_median_query_bfp8", query_bfp8)
+        extra("decode_us_median_single_cache_llc_assisted", single_cache_hot)
+        extra("decode_4_query_tokens_us_median", four_query_tokens)
+        extra("decode_split_us_median_rotary_at_read", rotary_at_read)
+        extra("decode_split_us_median_paged_256", lambda: paged_split_us(ring))
+        extra("quantize_append_bulk", bulk_quantize_rate)
     result["device"] = device_info()
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(ring)
-    print(json.dumps(result))
+    if not args.no_extra:
+        # the other workloads of the contract, decode attention only (the timed region of `value` is the headline's)
+        del ring
+        torch.cuda.empty_cache()
+        result["workloads"] = {}
+        for name in ("llama2_7b_4k", "batched_8k_p4", "batched_8k_p8", "long_128k"):
+            if name == w.name:
+                continue
+            try:
+                result["workloads"][name] = workload_entry(name, args.steps)
+            except Exception as e:
+                result["workloads"][name] = {"error": repr(e)}
+    print(json.dumps(result, default=float))
 
 
 if __name__ == "__main__":

@@ -330,6 +330,22 @@ int kvbfp_decode_attention_profile(const kvbfp_layout* layout, const kvbfp_cache
                                    void* out, void* workspace, size_t workspace_bytes,
                                    void* hip_stream, float* kernel_ms);
 
+/* DEVICE, SYNCHRONOUS, for measurement.  As kvbfp_decode_attention_profile, over a ring of caches of one
+ * layout: the split pass (Sec. III; the kernel that streams the cache) is launched n_launches times back to
+ * back, launch i over caches[i % n_caches], between two HIP events on `hip_stream`; then the combine pass
+ * n_launches times between two more.  kernel_ms[0] and [1] are the two totals divided by n_launches: average
+ * durations per launch that contain the dispatch gaps between successive launches but not the latency of the
+ * first one.  A ring larger than the last-level cache keeps every launch reading from memory.  `out` holds
+ * the result for the last cache launched.  n_launches = 1 with one cache is kvbfp_decode_attention_profile.
+ *   caches : HOST array of n_caches structs of DEVICE plane pointers.
+ * Errors: as kvbfp_decode_attention_profile, plus INVALID_ARG for n_caches < 1 or n_launches outside 1..4096. */
+int kvbfp_decode_attention_profile_ring(const kvbfp_layout* layout, const kvbfp_cache* caches, int32_t n_caches,
+                                        int32_t n_launches, int32_t n_q_heads, const void* q, kvbfp_dtype dtype,
+                                        const int32_t* seq_len_dev, int64_t max_len, float softmax_scale,
+                                        const int32_t* perm_k, const int32_t* perm_v, int32_t q_mant_bits,
+                                        void* out, void* workspace, size_t workspace_bytes, void* hip_stream,
+                                        float* kernel_ms);
+
 /* DEVICE, SYNCHRONOUS, for measurement.  Reads rows [0, n_tok) of the four planes of every (batch,
  * kv-head) once -- the bytes one kvbfp_decode_attention call over n_tok cached tokens streams (Sec. III:
  * the cached keys and values are read back each step) -- with plain 16-byte loads and no arithmetic, and

@@ -468,6 +468,11 @@ struct DecodeExtras {
     const int32_t* rope_partner = nullptr;
     const float* rope_sign = nullptr;
     const Paging* paging = nullptr;          // L is a pool of pages (kvbfp_decode_attention_paged)
+    // kvbfp_decode_attention_profile_ring: with kernel_ms, the split pass is launched `reps` times back to back over
+    // the caches ring[0], ring[1], ... (cyclically) between the first two events, then the combine pass `reps`
+    // times between the last two; the durations returned are per launch.
+    const kvbfp_cache* ring = nullptr;
+    int32_t ring_len = 0, reps = 1;
 };
 
 static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t n_q_heads,
@@ -587,32 +592,41 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
             }
         (void)hipEventRecord(ev[0], s);
     }
-    hipError_t err;
-    if (fast) {
-        err = hipSuccess;
-        // heads per launch: 8, or 16 where the LDS pipeline applies and more than 8 are left (its
-        // sixteen-head variant keeps two workgroups per CU resident instead of three)
-        const bool lds_path = dtype != KVBFP_F32 && L->mant_bits == 4 && L->block <= 32;
-        for (int g0 = 0; g0 < a.G && err == hipSuccess; g0 += a.g_cnt) {
-            const int left = a.G - g0;
-            a.g_base = g0;
-            a.g_cnt = (lds_path && left > 8) ? (left < 16 ? left : 16) : (left < 8 ? left : 8);
-            err = L->mant_bits == 4 ? launch_decode_split_mfma(a, (int)dtype, L->block, L->batch, s)
-                                    : launch_decode_split_mfma_p8(a, (int)dtype, L->block, L->batch, s);
-            a.k_new = a.v_new = nullptr;       // the current token is cast by the first launch only
-        }
-    } else {
-        if (rope) {
-            if (L->mant_bits == 4) decode_split_generic<4, true><<<grid1, kTile, 0, s>>>(a, (int)dtype);
-            else decode_split_generic<8, true><<<grid1, kTile, 0, s>>>(a, (int)dtype);
+    hipError_t err = hipSuccess;
+    auto launch_split = [&]() {
+        if (fast) {
+            // heads per launch: 8, or 16 where the LDS pipeline applies and more than 8 are left (its
+            // sixteen-head variant keeps two workgroups per CU resident instead of three)
+            const bool lds_path = dtype != KVBFP_F32 && L->mant_bits == 4 && L->block <= 32;
+            for (int g0 = 0; g0 < a.G && err == hipSuccess; g0 += a.g_cnt) {
+                const int left = a.G - g0;
+                a.g_base = g0;
+                a.g_cnt = (lds_path && left > 8) ? (left < 16 ? left : 16) : (left < 8 ? left : 8);
+                err = L->mant_bits == 4 ? launch_decode_split_mfma(a, (int)dtype, L->block, L->batch, s)
+                                        : launch_decode_split_mfma_p8(a, (int)dtype, L->block, L->batch, s);
+                a.k_new = a.v_new = nullptr;       // the current token is cast by the first launch only
+            }
         } else {
-            if (L->mant_bits == 4) decode_split_generic<4, false><<<grid1, kTile, 0, s>>>(a, (int)dtype);
-            else decode_split_generic<8, false><<<grid1, kTile, 0, s>>>(a, (int)dtype);
+            if (rope) {
+                if (L->mant_bits == 4) decode_split_generic<4, true><<<grid1, kTile, 0, s>>>(a, (int)dtype);
+                else decode_split_generic<8, true><<<grid1, kTile, 0, s>>>(a, (int)dtype);
+            } else {
+                if (L->mant_bits == 4) decode_split_generic<4, false><<<grid1, kTile, 0, s>>>(a, (int)dtype);
+                else decode_split_generic<8, false><<<grid1, kTile, 0, s>>>(a, (int)dtype);
+            }
+            err = hipGetLastError();
         }
-        err = hipGetLastError();
+    };
+    const int reps = (kernel_ms && x.ring && x.ring_len > 0 && x.reps > 1) ? x.reps : 1;
+    for (int r = 0; r < reps && err == hipSuccess; ++r) {
+        if (reps > 1) {
+            const kvbfp_cache& c = x.ring[r % x.ring_len];
+            a.k_mant = c.k_mant; a.k_exp = c.k_exp; a.v_mant = c.v_mant; a.v_exp = c.v_exp;
+        }
+        launch_split();
     }
     if (kernel_ms) (void)hipEventRecord(ev[1], s);
-    if (err == hipSuccess) {
+    for (int r = 0; r < reps && err == hipSuccess; ++r) {
         const dim3 grid2((unsigned)n_q_heads, (unsigned)L->batch, 1);
         if (sp.n_splits <= 8 * kCombineSlices) decode_combine<8><<<grid2, kD * kCombineSlices, 0, s>>>(a, (int)dtype);
         else decode_combine<32><<<grid2, kD * kCombineSlices, 0, s>>>(a, (int)dtype);
@@ -623,6 +637,8 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
         hipError_t e2 = hipEventSynchronize(ev[2]);
         if (e2 == hipSuccess) e2 = hipEventElapsedTime(&kernel_ms[0], ev[0], ev[1]);
         if (e2 == hipSuccess) e2 = hipEventElapsedTime(&kernel_ms[1], ev[1], ev[2]);
+        kernel_ms[0] /= (float)reps;
+        kernel_ms[1] /= (float)reps;
         for (auto& e : ev) (void)hipEventDestroy(e);
         if (err == hipSuccess) err = e2;
     }
@@ -786,6 +802,25 @@ int kvbfp_decode_attention_profile(const kvbfp_layout* L, const kvbfp_cache* cac
     x.q_mant_bits = q_mant_bits;
     x.kernel_ms = kernel_ms;
     return decode_impl(L, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v, out,
+                       workspace, workspace_bytes, hip_stream, x);
+}
+
+int kvbfp_decode_attention_profile_ring(const kvbfp_layout* L, const kvbfp_cache* caches, int32_t n_caches,
+                                        int32_t n_launches, int32_t n_q_heads, const void* q, kvbfp_dtype dtype,
+                                        const int32_t* seq_len_dev, int64_t max_len, float softmax_scale,
+                                        const int32_t* perm_k, const int32_t* perm_v, int32_t q_mant_bits, void* out,
+                                        void* workspace, size_t workspace_bytes, void* hip_stream, float* kernel_ms) {
+    clear_error();
+    if (!kernel_ms) return fail(KVBFP_ERR_INVALID_ARG, "decode_attention_profile_ring: kernel_ms is NULL");
+    if (!caches || n_caches <= 0 || n_launches <= 0 || n_launches > 4096)
+        return fail(KVBFP_ERR_INVALID_ARG, "decode_attention_profile_ring: caches / n_caches / n_launches (1..4096)");
+    for (int i = 0; i < n_caches; ++i)
+        if (int rc = check_cache(&caches[i], true, true)) return rc;
+    DecodeExtras x;
+    x.q_mant_bits = q_mant_bits;
+    x.kernel_ms = kernel_ms;
+    x.ring = caches; x.ring_len = n_caches; x.reps = n_launches;
+    return decode_impl(L, &caches[0], n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v, out,
                        workspace, workspace_bytes, hip_stream, x);
 }
 

@@ -27,7 +27,7 @@ EXPORTS = ["kvbfp_cache_bytes", "kvbfp_calibrate_perm", "kvbfp_permute_weights",
            "kvbfp_decode_attention", "kvbfp_decode_attention_qbfp", "kvbfp_append_decode_attention", "kvbfp_decode_attention_multi", "kvbfp_decode_attention_profile",
            "kvbfp_permute_rope", "kvbfp_decode_attention_rope",
            "kvbfp_quantize_append_paged", "kvbfp_dequantize_paged", "kvbfp_decode_workspace_bytes_paged",
-           "kvbfp_decode_attention_paged", "kvbfp_decode_attention_noalloc", "kvbfp_measure_stream_read",
+           "kvbfp_decode_attention_paged", "kvbfp_decode_attention_noalloc", "kvbfp_measure_stream_read", "kvbfp_decode_attention_profile_ring",
            "kvbfp_last_error", "kvbfp_version"]
 
 
@@ -108,6 +108,10 @@ def lib():
                                                    C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
                                                    C.c_size_t, C.c_void_p]
         l.kvbfp_decode_attention_profile.argtypes = l.kvbfp_decode_attention_qbfp.argtypes + [C.POINTER(C.c_float)]
+        l.kvbfp_decode_attention_profile_ring.argtypes = [C.POINTER(Layout), C.POINTER(CachePtrs), C.c_int32, C.c_int32,
+                                                          C.c_int32, C.c_void_p, C.c_int, C.c_void_p, C.c_int64,
+                                                          C.c_float, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+                                                          C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_float)]
         l.kvbfp_measure_stream_read.argtypes = [C.POINTER(Layout), C.POINTER(CachePtrs), C.c_int64, C.c_int32,
                                                 C.c_void_p, C.c_void_p, C.POINTER(C.c_float)]
         l.kvbfp_decode_attention_noalloc.argtypes = [C.POINTER(Layout), C.POINTER(CachePtrs), C.c_int32, C.c_void_p,
@@ -526,3 +530,18 @@ def measure_stream_read(cache: Cache, n_tok, wgs_per_unit=0, sink=None, stream=N
     _check(lib().kvbfp_measure_stream_read(C.byref(L), C.byref(ptrs), int(n_tok), int(wgs_per_unit), _dev_ptr(sink),
                                            _stream_ptr(stream), C.byref(ms)))
     return float(ms.value)
+
+
+def decode_attention_profile_ring(caches, n_launches, q, max_len, softmax_scale, q_mant_bits=0, seq_len_dev=None,
+                                  perm_k=None, perm_v=None, out=None, workspace=None, stream=None):
+    """DEVICE, synchronous.  The split pass n_launches times back to back over `caches` (a list of Cache objects of
+    one layout, used cyclically), then the combine pass as often; returns (out, split_ms, combine_ms) per launch."""
+    L, n_q_heads, out, workspace = _decode_common(caches[0], q, max_len, out, workspace)
+    arr = (CachePtrs * len(caches))(*[c.ptrs for c in caches])
+    ms = (C.c_float * 2)()
+    _check(lib().kvbfp_decode_attention_profile_ring(C.byref(L), arr, len(caches), int(n_launches), n_q_heads, _dev_ptr(q),
+                                                     _TORCH_DT[q.dtype], _dev_ptr(seq_len_dev, torch.int32), int(max_len),
+                                                     float(softmax_scale), _dev_ptr(perm_k, torch.int32),
+                                                     _dev_ptr(perm_v, torch.int32), int(q_mant_bits), _dev_ptr(out),
+                                                     _dev_ptr(workspace), workspace.numel(), _stream_ptr(stream), ms))
+    return out, float(ms[0]), float(ms[1])
