@@ -489,20 +489,27 @@ constexpr int vmcnt_imm(int n) { return (n & 0xF) | (0x7 << 4) | (0xF << 8) | ((
 // PAGED: the planes are a pool of pages and every 64-token tile looks up its page (a scalar load, issued a
 // tile ahead of the requests that need it); a separate instantiation, so the contiguous case is untouched.
 template <int N, int HG, bool PAGED>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(HG == 4 ? 2 : ((N == 16 && HG == 2) ? 2 : 3), 4)))
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(HG == 4 ? 2 : ((N != 32 && HG == 2) ? 2 : 3), 4)))
 void decode_split_lds_p4(DecodeArgs a, int dt) {
-    static_assert(N == 16 || N == 32, "LDS pipeline is built for blocks of 16 or 32");
+    static_assert(N == 16 || N == 32 || N == 64 || N == 128, "block sizes of the format");
+    static_assert(HG < 4 || N <= 32, "the sixteen-head variant is built for blocks of 16 and 32");
     constexpr int NB = kD / N;
     constexpr int NH = HG * 4;
     constexpr int kTileTok = 64;
     // per-wavefront staging area
     constexpr int kKm = 0;                         // 4 stages x 1024 B key mantissas
     constexpr int kVm = kKm + 4096;                // 4 stages x 1024 B value mantissas
-    constexpr int kEt = kTileTok * NB;             // exponent bytes of a whole 64-token tile: one DMA dword per lane and 256 B
-    constexpr int kKe = kVm + 4096;                // key exponents [64 tokens][NB]
-    constexpr int kVe = kKe + kEt;                 // value exponents [64 tokens][NB]
+    // Exponents of a whole 64-token tile: [64 tokens][kExpRow bytes] in LDS.  Blocks of 16 / 32: the 8 / 4 bytes of a
+    // token as they lie in the plane, fetched as dwords (two DMA instructions / one).  Blocks of 64 / 128: a token has
+    // 2 / 1 bytes, the plane's rows are not dword-aligned, so each lane fetches its token's bytes with a 2- / 1-byte
+    // DMA element, which lands zero-extended in the lane's own dword.
+    constexpr int kExpRow = NB >= 4 ? NB : 4;
+    constexpr int kExpElt = NB >= 4 ? 4 : NB;      // bytes per lane and DMA instruction
+    constexpr int kEt = kTileTok * kExpRow;
+    constexpr int kKe = kVm + 4096;
+    constexpr int kVe = kKe + kEt;
     constexpr int kWaveBytes = kVe + kEt;
-    constexpr int kExpDma = kEt / 256;             // DMA instructions per exponent tile (1 for blocks of 32, 2 for 16)
+    constexpr int kExpDma = kEt / 256;             // DMA instructions per exponent tile (2 for blocks of 16, else 1)
     // Keys go to the scaled FP8 x FP4 MFMA as raw nibbles: a block of 32 is exactly its MX block; a
     // block of 16 takes two products per 32 channels, each with the other block's nibbles zeroed.
     constexpr int kRings = kWaves * kWaveBytes;
@@ -627,7 +634,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
     const int kd_row = lane >> 2, kd_chunk = (lane & 3) ^ ((lane >> 4) & 3);            // DMA lane -> (row, chunk)
     const uint32_t k_src = (uint32_t)kd_row * 64u + (uint32_t)kd_chunk * 16u;
     const uint32_t v_src = (uint32_t)vrow_of_slot * 64u + (uint32_t)vp_c * 16u;
-    const uint32_t e_src = (uint32_t)lane * 4u;     // exponents: dword `lane` (+64 per further instruction) of the tile's rows
+    const uint32_t e_src = (uint32_t)lane * kExpElt;   // exponents: element `lane` (+64 per further instruction) of the tile's rows
 
     // Re-fills of the staging area.  Mantissas: stage u of a tile that starts at token t of the split = plane
     // row `row` (tile_row of the tile).  A full tile takes the immediate-offset form (the offset applies to the
@@ -651,15 +658,19 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
         const uint8_t* __restrict__ ep = (keys ? k_exp : v_exp) + row * NB;
         uint8_t* const le = wbase + (keys ? kKe : kVe);
         if (tile_full) {
-            __builtin_amdgcn_global_load_lds(KVBFP_GPTR(ep + e_src), KVBFP_LPTR(le), 4, 0, kStreamAux);
+            if constexpr (NB >= 4) __builtin_amdgcn_global_load_lds(KVBFP_GPTR(ep + e_src), KVBFP_LPTR(le), 4, 0, kStreamAux);
+            else if constexpr (NB == 2) __builtin_amdgcn_global_load_lds(KVBFP_GPTR(ep + e_src), KVBFP_LPTR(le), 2, 0, kStreamAux);
+            else __builtin_amdgcn_global_load_lds(KVBFP_GPTR(ep + e_src), KVBFP_LPTR(le), 1, 0, kStreamAux);
             if (kExpDma == 2) __builtin_amdgcn_global_load_lds(KVBFP_GPTR(ep + e_src), KVBFP_LPTR(le), 4, 256, kStreamAux);
         } else {
             const int left = n_tok - t;                    // >= 1
 #pragma unroll
             for (int x = 0; x < kExpDma; ++x) {
-                const int byte = (int)e_src + 256 * x;
+                const int byte = (int)e_src + 256 * x;      // offset in the tile's exponent rows
                 const int eo = min(byte / NB, left - 1) * NB + byte % NB;
-                __builtin_amdgcn_global_load_lds(KVBFP_GPTR(ep + eo), KVBFP_LPTR(le + 256 * x), 4, 0, kStreamAux);
+                if constexpr (NB >= 4) __builtin_amdgcn_global_load_lds(KVBFP_GPTR(ep + eo), KVBFP_LPTR(le + 256 * x), 4, 0, kStreamAux);
+                else if constexpr (NB == 2) __builtin_amdgcn_global_load_lds(KVBFP_GPTR(ep + eo), KVBFP_LPTR(le + 256 * x), 2, 0, kStreamAux);
+                else __builtin_amdgcn_global_load_lds(KVBFP_GPTR(ep + eo), KVBFP_LPTR(le + 256 * x), 1, 0, kStreamAux);
             }
         }
     };
@@ -809,11 +820,12 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
 
     // ---- LDS read offsets of this lane inside a stage --------------------------------------------
     const uint32_t kq = lds_addr(wbase + kKm + (4 * j + (kg ^ ((j >> 2) & 3))) * 16);       // row j, chunk kg
-    const uint32_t keq = lds_addr(wbase + kKe + j * NB + (N == 32 ? kg : 2 * kg));         // + 16 NB per stage: own exponent byte(s)
+    // own exponent byte(s): the block of channels 32 kg .. 32 kg + 31 (two blocks of 16: a 16-bit read)
+    const uint32_t keq = lds_addr(wbase + kKe + j * kExpRow + (N == 16 ? 2 * kg : (32 * kg) / N));   // + 16 kExpRow per stage
     const uint32_t vq = lds_addr(wbase + kVm + kg * 64 + j * 4);                           // + i*256: row 4kg+i sits at position 4i+kg
     // value exponents: blocks of 32 -> the 16 bytes of tokens 4kg..4kg+3 in one read per stage, this lane's block is
     // byte j/4 of each dword; blocks of 16 -> byte (4kg + i) NB + j/2, one read each
-    const uint32_t veq = lds_addr(wbase + kVe + (4 * kg) * NB + (N == 32 ? 0 : (8 * j) / N));
+    const uint32_t veq = lds_addr(wbase + kVe + (4 * kg) * kExpRow + (N == 32 ? 0 : (8 * j) / N));
     const uint32_t ve_rot = (uint32_t)((8 * (j >> 2) + 32 - 23) & 31);   // rotation that brings byte j/4 to the exponent field
     uint16_t* const ps = &p_lds[wave][0];
     const uint32_t ps_rd = lds_addr(&p_lds[wave][(a_limb * 4 + a_head) * kTileTok + 4 * kg]);   // + head group and column tile
@@ -826,7 +838,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
         const int kStep = a.n_splits * kWaves * kTileTok;      // this workgroup's next 256-token tile
         // (Where registers are short -- four head groups, or two with blocks of 32, which keep three wavefronts per
         // SIMD -- every stage issues its own reads and waits for them; the probabilities look ahead with one group only.)
-        constexpr bool kPipe = HG == 1 || (HG == 2 && N == 16), kPipeP = HG == 1;
+        constexpr bool kPipe = HG == 1 || (HG == 2 && N != 32), kPipeP = HG == 1;
         u32x4 rawk[kPipe ? 2 : 1];
         uint32_t kexp[4];
         uint64_t vw01[kPipe ? 2 : 1], vw23[kPipe ? 2 : 1], ppv[kPipeP ? 2 : 1][HG];
@@ -845,7 +857,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
         constexpr int kAfterFirst = 7 + kExpDma, kAfterOther = 7 + 2 * kExpDma;
         auto issue_k0 = [&] {
             lds_issue_b128<0>(kq, rawk[0]);
-            lds_issue_4<0, 16 * NB, N == 16>(keq, kexp);
+            lds_issue_4<0, 16 * kExpRow, N == 16>(keq, kexp);
         };
         // wait for the DMA of a stage and issue its LDS reads (`more`: the next tile is being requested meanwhile)
         auto start_k = [&](auto U, const bool more) {             // key stage U >= 1
@@ -862,7 +874,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
             } else {
                 static_for<4>([&](auto V) {
                     constexpr int v = decltype(V)::value;
-                    lds_issue_4<v * 16 * NB, NB, false>(veq, *(uint32_t(*)[4])&vexp16[4 * v]);
+                    lds_issue_4<v * 16 * kExpRow, kExpRow, false>(veq, *(uint32_t(*)[4])&vexp16[4 * v]);
                 });
             }
         };
@@ -913,7 +925,7 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
                 for (int hg = 0; hg < HG; ++hg) s_acc[hg][u] = f32x4{0.f, 0.f, 0.f, 0.f};
                 // magnitude/2 = FP4(s,0,m1,m0) + FP4(s,m2,0,0): two masked copies of the raw nibbles are the B
                 // operands and the block's exponent byte is their E8M0 scale (the halving sits in the query's scale).
-                if (N == 32) {
+                if (N >= 32) {                 // one exponent byte per 32 channels (the same byte for wider blocks)
                     const int sb = (int)kexp[u];
                     const v8i b1 = {(int)(raw[0] & 0xBBBBBBBBu), (int)(raw[1] & 0xBBBBBBBBu), (int)(raw[2] & 0xBBBBBBBBu),
                                     (int)(raw[3] & 0xBBBBBBBBu), 0, 0, 0, 0};
@@ -1096,28 +1108,27 @@ void decode_split_lds_p4(DecodeArgs a, int dt) {
     }
 }
 
-// 16-bit I/O: blocks of 16 and 32 go through the LDS pipeline, blocks of 64 and 128 through the
-// register-staged pass with two probability limbs.  fp32 I/O: the register-staged pass with three
-// probability limbs and the three-limb bf16 query for every block size (the FP8 query limbs of the LDS
-// pipeline carry 16 bits, too few for the 1e-5 bar).
-template <int HG, int PL, bool PAGED>
+// 16-bit I/O: the LDS pipeline, every block size.  fp32 I/O: the register-staged pass with three probability
+// limbs and the three-limb bf16 query (the FP8 query limbs of the LDS pipeline carry 16 bits, too few for the
+// 1e-5 bar).
+template <int HG, bool PAGED>
 hipError_t launch_reg(const DecodeArgs& a, int dt, int block, dim3 grid, hipStream_t s) {
-    if constexpr (PL == 3) {      // fp32 I/O: every block size; 16-bit I/O comes here with blocks of 64 and 128 only
-        if (block == 16) { decode_split_mfma_p4<16, HG, PL, PAGED><<<grid, 256, 0, s>>>(a, dt); return hipGetLastError(); }
-        if (block == 32) { decode_split_mfma_p4<32, HG, PL, PAGED><<<grid, 256, 0, s>>>(a, dt); return hipGetLastError(); }
-    }
-    if (block == 64) decode_split_mfma_p4<64, HG, PL, PAGED><<<grid, 256, 0, s>>>(a, dt);
-    else if (block == 128) decode_split_mfma_p4<128, HG, PL, PAGED><<<grid, 256, 0, s>>>(a, dt);
+    if (block == 16) decode_split_mfma_p4<16, HG, 3, PAGED><<<grid, 256, 0, s>>>(a, dt);
+    else if (block == 32) decode_split_mfma_p4<32, HG, 3, PAGED><<<grid, 256, 0, s>>>(a, dt);
+    else if (block == 64) decode_split_mfma_p4<64, HG, 3, PAGED><<<grid, 256, 0, s>>>(a, dt);
+    else if (block == 128) decode_split_mfma_p4<128, HG, 3, PAGED><<<grid, 256, 0, s>>>(a, dt);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 
 template <int HG, bool PAGED>
 hipError_t launch_n(const DecodeArgs& a, int dt, int block, dim3 grid, hipStream_t s) {
-    if (dt == KVBFP_F32) return launch_reg<HG, 3, PAGED>(a, dt, block, grid, s);
-    if (block > 32) return launch_reg<HG, 2, PAGED>(a, dt, block, grid, s);
+    if (dt == KVBFP_F32) return launch_reg<HG, PAGED>(a, dt, block, grid, s);
     if (block == 16) decode_split_lds_p4<16, HG, PAGED><<<grid, 256, 0, s>>>(a, dt);
-    else decode_split_lds_p4<32, HG, PAGED><<<grid, 256, 0, s>>>(a, dt);
+    else if (block == 32) decode_split_lds_p4<32, HG, PAGED><<<grid, 256, 0, s>>>(a, dt);
+    else if (block == 64) decode_split_lds_p4<64, HG, PAGED><<<grid, 256, 0, s>>>(a, dt);
+    else if (block == 128) decode_split_lds_p4<128, HG, PAGED><<<grid, 256, 0, s>>>(a, dt);
+    else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 

@@ -59,6 +59,10 @@ WORKLOADS = {
     "long_128k": Workload("long_128k", 1, 32, 8, 128, 131072, "bf16", 16, 4, (2, 6), (20.0, 20.0)),
     # not one of the contract's configurations: 8 query heads per kv-head (two MFMA row groups per pass)
     "gqa8_32k": Workload("gqa8_32k", 8, 64, 8, 128, 32768, "bf16", 32, 4, (2, 6), (20.0, 20.0)),
+    # the headline shapes with the paper's other block sizes (Table I) and with 8-bit mantissas
+    "gqa_32k_n64": Workload("gqa_32k_n64", 8, 32, 8, 128, 32768, "bf16", 64, 4, (2, 6), (20.0, 20.0)),
+    "gqa_32k_n128": Workload("gqa_32k_n128", 8, 32, 8, 128, 32768, "bf16", 128, 4, (2, 6), (20.0, 20.0)),
+    "gqa_32k_p8n16": Workload("gqa_32k_p8n16", 8, 32, 8, 128, 32768, "bf16", 16, 8, (2, 6), (20.0, 20.0)),
     "prefill_bulk": Workload("prefill_bulk", 32, 8, 8, 128, 4096, "bf16", 16, 4, (2, 6), (10.0, 50.0),
                              extra={"note": "32 layers x 8 KV heads x 4096 tokens, layer index plays the batch role"}),
 }

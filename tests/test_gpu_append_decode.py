@@ -95,8 +95,9 @@ def test_small_caches_equal_two_calls(n, G, use_perm):
     _case(torch.bfloat16, n, 4, G, [1025, 700, 1, 0], 1100, use_perm, seed=30 + n + G)
 
 
-@pytest.mark.parametrize("n", [16, 32])
-@pytest.mark.parametrize("G,use_perm,qbits", [(1, False, 0), (2, True, 0), (2, True, 8), (12, True, 0)])
+@pytest.mark.parametrize("n,G,use_perm,qbits", [(n, *rest) for n in (16, 32) for rest in
+                                                 [(1, False, 0), (2, True, 0), (2, True, 8), (12, True, 0)]] +
+                         [(64, 4, True, 0), (64, 6, False, 8), (128, 1, True, 0), (128, 8, True, 0)])
 def test_cast_inside_the_split_pass_equals_two_calls(n, G, use_perm, qbits):
     # In the LDS pipeline the wavefront whose 64-token tiles hold the last token casts and stores the new
     # rows itself.  4 x 64 = 256 (batch, kv-head) units ask for 3 splits (2 with 12 heads per kv-head),
