@@ -315,6 +315,26 @@ int kvbfp_decode_attention_paged(const kvbfp_layout* pool, const kvbfp_cache* ca
                                  float softmax_scale, const int32_t* perm_k, const int32_t* perm_v,
                                  int32_t q_mant_bits, void* out, void* workspace, size_t workspace_bytes,
                                  void* hip_stream, float* kernel_ms);
+/* kvbfp_append_decode_attention and kvbfp_decode_attention_multi over a pool of pages (Sec. III: the
+ * current token's K/V rows are cast and written, then read with the rest; Alg. 1 steps 4-6).  The
+ * arguments are those of the calls without `_paged`, with the pool, block_table, table_stride and
+ * batch as above.  The page that holds position seq_len[b] - 1 (the appended row) must be in the
+ * block table before the call.  workspace: kvbfp_decode_workspace_bytes_paged(pool, table_stride,
+ * batch, n_q_heads [* n_q_tokens], max_len).  Same bytes in the cache and same values in `out` as the
+ * contiguous calls.  DEVICE, async.  Errors: as those calls and as kvbfp_decode_attention_paged. */
+int kvbfp_append_decode_attention_paged(const kvbfp_layout* pool, const kvbfp_cache* cache,
+                                        const int32_t* block_table, int64_t table_stride, int32_t batch,
+                                        int32_t n_q_heads, const void* k_new, const void* v_new,
+                                        int64_t new_stride_b, int64_t new_stride_h, const void* q, kvbfp_dtype dtype,
+                                        const int32_t* seq_len_dev, int64_t max_len, float softmax_scale,
+                                        const int32_t* perm_k, const int32_t* perm_v, int32_t q_mant_bits, void* out,
+                                        void* workspace, size_t workspace_bytes, void* hip_stream);
+int kvbfp_decode_attention_multi_paged(const kvbfp_layout* pool, const kvbfp_cache* cache,
+                                       const int32_t* block_table, int64_t table_stride, int32_t batch,
+                                       int32_t n_q_heads, int32_t n_q_tokens, const void* q, kvbfp_dtype dtype,
+                                       const int32_t* seq_len_dev, int64_t max_len, float softmax_scale,
+                                       const int32_t* perm_k, const int32_t* perm_v, int32_t q_mant_bits, void* out,
+                                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* DEVICE, SYNCHRONOUS, for measurement.  Enqueues exactly the launches of
  * kvbfp_decode_attention_qbfp (Sec. III; same arguments, same result in `out`) with HIP events

@@ -493,8 +493,6 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
     kvbfp_layout logical;
     const kvbfp_layout* pool = L;
     if (paging) {
-        if (k_new || v_new || n_q_tokens != 1)
-            return fail(KVBFP_ERR_UNSUPPORTED, "decode_attention_paged: plain single-token decode only");
         if (int rc = check_paging(pool, *paging, &logical)) return rc;
         L = &logical;             // from here on: what the sequences look like
     }
@@ -576,8 +574,9 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
         if (in_kernel) {
             a.k_new = k_new; a.v_new = v_new; a.new_stride_b = new_stride_b; a.new_stride_h = new_stride_h;
         } else {
-            if (int rc = kvbfp::quantize_append_impl(L, cache, k_new, v_new, dtype, 1, new_stride_b, 0, new_stride_h,
-                                                     max_len - 1, seq_len_dev, max_len, perm_k, perm_v, hip_stream))
+            if (int rc = kvbfp::quantize_append_impl(pool, cache, k_new, v_new, dtype, 1, new_stride_b, 0, new_stride_h,
+                                                     max_len - 1, seq_len_dev, max_len, perm_k, perm_v, hip_stream,
+                                                     paging))
                 return rc;
         }
     }
@@ -732,6 +731,41 @@ int kvbfp_decode_attention_paged(const kvbfp_layout* pool, const kvbfp_cache* ca
     DecodeExtras x;
     x.q_mant_bits = q_mant_bits;
     x.kernel_ms = kernel_ms;
+    x.paging = &pg;
+    return decode_impl(pool, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v, out,
+                       workspace, workspace_bytes, hip_stream, x);
+}
+
+int kvbfp_append_decode_attention_paged(const kvbfp_layout* pool, const kvbfp_cache* cache,
+                                        const int32_t* block_table, int64_t table_stride, int32_t batch,
+                                        int32_t n_q_heads, const void* k_new, const void* v_new,
+                                        int64_t new_stride_b, int64_t new_stride_h, const void* q, kvbfp_dtype dtype,
+                                        const int32_t* seq_len_dev, int64_t max_len, float softmax_scale,
+                                        const int32_t* perm_k, const int32_t* perm_v, int32_t q_mant_bits, void* out,
+                                        void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!k_new || !v_new) {
+        clear_error();
+        return fail(KVBFP_ERR_INVALID_ARG, "append_decode_attention_paged: k_new/v_new is NULL");
+    }
+    const Paging pg{block_table, table_stride, batch};
+    DecodeExtras x;
+    x.q_mant_bits = q_mant_bits;
+    x.k_new = k_new; x.v_new = v_new; x.new_stride_b = new_stride_b; x.new_stride_h = new_stride_h;
+    x.paging = &pg;
+    return decode_impl(pool, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v, out,
+                       workspace, workspace_bytes, hip_stream, x);
+}
+
+int kvbfp_decode_attention_multi_paged(const kvbfp_layout* pool, const kvbfp_cache* cache,
+                                       const int32_t* block_table, int64_t table_stride, int32_t batch,
+                                       int32_t n_q_heads, int32_t n_q_tokens, const void* q, kvbfp_dtype dtype,
+                                       const int32_t* seq_len_dev, int64_t max_len, float softmax_scale,
+                                       const int32_t* perm_k, const int32_t* perm_v, int32_t q_mant_bits, void* out,
+                                       void* workspace, size_t workspace_bytes, void* hip_stream) {
+    const Paging pg{block_table, table_stride, batch};
+    DecodeExtras x;
+    x.q_mant_bits = q_mant_bits;
+    x.n_q_tokens = n_q_tokens;
     x.paging = &pg;
     return decode_impl(pool, cache, n_q_heads, q, dtype, seq_len_dev, max_len, softmax_scale, perm_k, perm_v, out,
                        workspace, workspace_bytes, hip_stream, x);

@@ -27,7 +27,8 @@ EXPORTS = ["kvbfp_cache_bytes", "kvbfp_calibrate_perm", "kvbfp_permute_weights",
            "kvbfp_decode_attention", "kvbfp_decode_attention_qbfp", "kvbfp_append_decode_attention", "kvbfp_decode_attention_multi", "kvbfp_decode_attention_profile",
            "kvbfp_permute_rope", "kvbfp_decode_attention_rope",
            "kvbfp_quantize_append_paged", "kvbfp_dequantize_paged", "kvbfp_decode_workspace_bytes_paged",
-           "kvbfp_decode_attention_paged", "kvbfp_decode_attention_noalloc", "kvbfp_measure_stream_read", "kvbfp_decode_attention_profile_ring",
+           "kvbfp_decode_attention_paged", "kvbfp_append_decode_attention_paged", "kvbfp_decode_attention_multi_paged",
+           "kvbfp_decode_attention_noalloc", "kvbfp_measure_stream_read", "kvbfp_decode_attention_profile_ring",
            "kvbfp_last_error", "kvbfp_version"]
 
 
@@ -87,6 +88,13 @@ def lib():
                                                    C.c_int32, C.c_int32, C.c_void_p, C.c_int, C.c_void_p, C.c_int64,
                                                    C.c_float, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
                                                    C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+        _paged = [C.POINTER(Layout), C.POINTER(CachePtrs), C.c_void_p, C.c_int64, C.c_int32]
+        l.kvbfp_append_decode_attention_paged.argtypes = _paged + [
+            C.c_int32, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int, C.c_void_p, C.c_int64,
+            C.c_float, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        l.kvbfp_decode_attention_multi_paged.argtypes = _paged + [
+            C.c_int32, C.c_int32, C.c_void_p, C.c_int, C.c_void_p, C.c_int64, C.c_float, C.c_void_p, C.c_void_p,
+            C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         l.kvbfp_quantize_append.argtypes = [C.POINTER(Layout), C.POINTER(CachePtrs), C.c_void_p, C.c_void_p,
                                             C.c_int, C.c_int32, C.c_int64, C.c_int64, C.c_int64, C.c_int64,
                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -439,6 +447,62 @@ def decode_attention_paged(pool: Cache, block_table, q, max_len, softmax_scale, 
                                               _dev_ptr(perm_v, torch.int32), int(q_mant_bits), _dev_ptr(out),
                                               _dev_ptr(workspace), workspace.numel(), _stream_ptr(stream), ms))
     return (out, float(ms[0]), float(ms[1])) if profile else out
+
+
+def append_decode_attention_paged(pool: Cache, block_table, k_new, v_new, q, max_len, softmax_scale, seq_len_dev=None,
+                                  perm_k=None, perm_v=None, q_mant_bits=0, out=None, workspace=None, stream=None):
+    """DEVICE, async.  append_decode_attention over a pool of pages."""
+    L = pool.layout
+    if q.dim() != 3 or not q.is_contiguous():
+        raise ValueError("q must be a contiguous [batch][n_q_heads][head_dim] tensor")
+    _check_table(block_table, q.shape[0])
+    if k_new.dim() == 4:
+        k_new, v_new = k_new[:, 0], v_new[:, 0]
+    if k_new.dim() != 3 or k_new.stride(2) != 1 or k_new.shape != v_new.shape or k_new.stride() != v_new.stride() \
+            or k_new.dtype != q.dtype or v_new.dtype != q.dtype:
+        raise ValueError("k_new/v_new must be [batch][n_kv_heads][head_dim], channel-contiguous, same strides, q's dtype")
+    if k_new.shape != (q.shape[0], L.n_kv_heads, L.head_dim):
+        raise ValueError("k_new/v_new shape does not match the layout")
+    n_q_heads = q.shape[1]
+    if out is None:
+        out = torch.empty_like(q)
+    if workspace is None:
+        need = decode_workspace_bytes_paged(L, block_table.shape[1], q.shape[0], n_q_heads, max_len)
+        if need == 0:
+            _check(ERR_INVALID_ARG)
+        workspace = torch.empty((need,), dtype=torch.uint8, device=q.device)
+    ptrs = pool.ptrs
+    _check(lib().kvbfp_append_decode_attention_paged(
+        C.byref(L), C.byref(ptrs), _dev_ptr(block_table, torch.int32), block_table.shape[1], q.shape[0], n_q_heads,
+        _dev_ptr(k_new), _dev_ptr(v_new), k_new.stride(0), k_new.stride(1), _dev_ptr(q), _TORCH_DT[q.dtype],
+        _dev_ptr(seq_len_dev, torch.int32), int(max_len), float(softmax_scale), _dev_ptr(perm_k, torch.int32),
+        _dev_ptr(perm_v, torch.int32), int(q_mant_bits), _dev_ptr(out), _dev_ptr(workspace), workspace.numel(),
+        _stream_ptr(stream)))
+    return out
+
+
+def decode_attention_multi_paged(pool: Cache, block_table, q, max_len, softmax_scale, seq_len_dev=None, perm_k=None,
+                                 perm_v=None, q_mant_bits=0, out=None, workspace=None, stream=None):
+    """DEVICE, async.  decode_attention_multi over a pool of pages; q: [batch][n_q_tokens][n_q_heads][head_dim]."""
+    L = pool.layout
+    if q.dim() != 4 or not q.is_contiguous():
+        raise ValueError("q must be a contiguous [batch][n_q_tokens][n_q_heads][head_dim] tensor")
+    _check_table(block_table, q.shape[0])
+    n_tok, n_q_heads = q.shape[1], q.shape[2]
+    if out is None:
+        out = torch.empty_like(q)
+    if workspace is None:
+        need = decode_workspace_bytes_paged(L, block_table.shape[1], q.shape[0], n_q_heads * n_tok, max_len)
+        if need == 0:
+            _check(ERR_INVALID_ARG)
+        workspace = torch.empty((need,), dtype=torch.uint8, device=q.device)
+    ptrs = pool.ptrs
+    _check(lib().kvbfp_decode_attention_multi_paged(
+        C.byref(L), C.byref(ptrs), _dev_ptr(block_table, torch.int32), block_table.shape[1], q.shape[0], n_q_heads,
+        n_tok, _dev_ptr(q), _TORCH_DT[q.dtype], _dev_ptr(seq_len_dev, torch.int32), int(max_len),
+        float(softmax_scale), _dev_ptr(perm_k, torch.int32), _dev_ptr(perm_v, torch.int32), int(q_mant_bits),
+        _dev_ptr(out), _dev_ptr(workspace), workspace.numel(), _stream_ptr(stream)))
+    return out
 
 
 def decode_attention_profile(cache: Cache, q, max_len, softmax_scale, q_mant_bits=0, seq_len_dev=None, perm_k=None,

@@ -153,3 +153,85 @@ def test_paged_argument_errors():
     x = torch.zeros(1, 2, 2, D, device="cuda", dtype=torch.bfloat16)
     with pytest.raises(kvbfp.KvbfpError):
         kvbfp.quantize_append_paged(pool, table, x, x, pos0=511)
+
+
+@pytest.mark.parametrize("dtype,p,n,G,page,Hkv", [
+    (torch.bfloat16, 4, 32, 4, 256, 64),    # 64 kv-heads: several splits, the cast runs inside the split pass
+    (torch.bfloat16, 4, 16, 2, 64, 64),
+    (torch.float16, 4, 64, 1, 128, 64),
+    (torch.bfloat16, 4, 128, 8, 512, 2),
+    (torch.bfloat16, 8, 16, 2, 256, 2),     # 8-bit mantissas and fp32 I/O: the cache-write kernel goes first
+    (torch.float32, 4, 32, 2, 128, 2),
+])
+def test_current_token_appended_and_attended_on_pages(dtype, p, n, G, page, Hkv):
+    # the current tokens: the first row of a fresh page (1025 = 4 x 256 + 1 = 16 x 64 + 1), mid-page, the very
+    # first token of a sequence, and an empty sequence that must stay untouched
+    lens = [1025, 700, 1, 0]
+    B, S = 4, 1025
+    k, v, q, pk, pv = make_small(dtype, B=B, S=S, Hkv=Hkv, G=G, seed=210 + n + G)
+    pages_per_seq = -(-S // page) + 1
+    before = [max(l - 1, 0) for l in lens]
+    # before the call: every sequence holds all but its current token (an empty one gets a page anyway)
+    pool, table, need = make_pool(B, Hkv, n, p, page, pages_per_seq, [max(l, 1) for l in lens], seed=n + page)
+    table_dev = dev_i32(table)
+    kd, vd = k.cuda(), v.cuda()
+    for b in range(B):
+        if before[b]:
+            kvbfp.quantize_append_paged(pool, table_dev[b:b + 1].contiguous(), kd[b:b + 1, :before[b]],
+                                        vd[b:b + 1, :before[b]], pos0=0, perm_k=dev_i32(pk), perm_v=dev_i32(pv))
+    idx = torch.tensor([max(l - 1, 0) for l in lens])
+    k_new = torch.stack([k[b, idx[b]] for b in range(B)]).cuda()           # [B][Hkv][D]
+    v_new = torch.stack([v[b, idx[b]] for b in range(B)]).cuda()
+    scale = float(np.float32(0.09))
+    got = kvbfp.append_decode_attention_paged(pool, table_dev, k_new, v_new, q.cuda(), S, scale,
+                                              seq_len_dev=dev_i32(lens), perm_k=dev_i32(pk), perm_v=dev_i32(pv))
+    torch.cuda.synchronize()
+    S_max = pages_per_seq * page
+    planes = None
+    for b in range(B):
+        take = max(lens[b], 1)           # an empty sequence: cast one token, then wipe it again
+        one = oracle_cache(k[b:b + 1, :take], v[b:b + 1, :take], n, p, S_max, 0, pk, pv, fill=SENTINEL)
+        if lens[b] == 0:
+            for x in one:
+                x[:] = SENTINEL
+        planes = [x.copy() for x in one] if planes is None else [np.concatenate([a, c]) for a, c in zip(planes, one)]
+    have = gather_pages(pool, table, need, B, S_max, page)
+    for name, g, w in zip(("k_mant", "k_exp", "v_mant", "v_exp"), have, planes):
+        for b in range(B):
+            assert np.array_equal(g[b, :, :lens[b]], w[b, :, :lens[b]]), (name, b)
+            assert np.all(g[b, :, lens[b]:need[b] * page] == SENTINEL), (name, b, "rows after the current token")
+    units = None if Hkv <= 2 else [(0, 0), (0, Hkv - 1), (1, 17), (2, 40), (3, 5)]
+    if units is None:
+        want = O.decode_attention(*planes, D, n, p, synth.to_f32_numpy(q), lens, scale, pk, pv)
+        assert_attention_close(got, want, dtype, "p=%d n=%d G=%d page=%d" % (p, n, G, page))
+    else:           # the oracle on a few (sequence, kv-head) units
+        qf = synth.to_f32_numpy(q).reshape(B, Hkv, G, D)
+        for b, h in units:
+            sub = [x[b:b + 1, h:h + 1] for x in planes]
+            want = O.decode_attention(*sub, D, n, p, qf[b:b + 1, h], [lens[b]], scale,
+                                      None if pk is None else pk[h:h + 1], None if pv is None else pv[h:h + 1])
+            assert_attention_close(got.reshape(B, Hkv, G, D)[b:b + 1, h], want, dtype, "unit %s" % ((b, h),))
+    assert bool((got[3] == 0).all())
+
+
+@pytest.mark.parametrize("dtype,p,n,G,Tq,page", [
+    (torch.bfloat16, 4, 32, 2, 4, 256),
+    (torch.float16, 4, 16, 1, 8, 64),
+    (torch.bfloat16, 8, 32, 3, 7, 128),     # 21 virtual heads: three launches over head subsets
+    (torch.bfloat16, 4, 64, 4, 9, 256),     # 36 virtual heads: general pass
+])
+def test_several_query_tokens_on_pages(dtype, p, n, G, Tq, page):
+    lens = [830, max(Tq - 2, 1), 257 + Tq // 2]
+    k, v, q0, pk, pv = make_small(dtype, B=3, S=830, Hkv=2, G=G, seed=230 + Tq)
+    pool, table, planes = fill_both(k, v, n, p, page, -(-830 // page) + 1, lens, pk, pv, seed=Tq + page)
+    name = {torch.bfloat16: "bf16", torch.float16: "f16", torch.float32: "f32"}[dtype]
+    q = torch.stack([synth.queries(3, 2 * G, D, name, 231 + 10 * i, 4) for i in range(Tq)], dim=1)
+    scale = float(np.float32(0.09))
+    got = kvbfp.decode_attention_multi_paged(pool, table, q.cuda(), 830, scale, seq_len_dev=dev_i32(lens),
+                                             perm_k=dev_i32(pk), perm_v=dev_i32(pv))
+    torch.cuda.synchronize()
+    assert got.shape == q.shape
+    for i in range(Tq):
+        seen = [max(l - (Tq - 1 - i), 0) for l in lens]
+        want = O.decode_attention(*planes, D, n, p, synth.to_f32_numpy(q[:, i]), seen, scale, pk, pv)
+        assert_attention_close(got[:, i], want, dtype, "query token %d of %d sees %s" % (i, Tq, seen))
