@@ -116,6 +116,18 @@ int kvbfp_permute_weights(const void* w_in, void* w_out, kvbfp_dtype dtype, int3
                           int32_t head_dim, int64_t row_len, int32_t heads_per_perm,
                           const int32_t* perm);
 
+/* HOST.  Sec. III, last paragraph: the projection that consumes the attention output has its COLUMNS
+ * reordered to match the value permutation, so that the output can stay in cache order.
+ *   w_in, w_out : HOST [n_rows][n_heads*head_dim] row-major, same dtype, must not overlap (W_o: n_rows =
+ *   model width, n_heads = query heads).
+ *   out column (h, j) = in column (h, perm[h / heads_per_perm][j]);  perm as in kvbfp_permute_weights.
+ * With W_v's rows reordered by the same permutation, w_out . (reordered attention output) equals
+ * w_in . (attention output in the original order): nothing is gathered or scattered at run time.
+ * Errors: as kvbfp_permute_weights. */
+int kvbfp_permute_weight_columns(const void* w_in, void* w_out, kvbfp_dtype dtype, int64_t n_rows,
+                                 int32_t n_heads, int32_t head_dim, int32_t heads_per_perm,
+                                 const int32_t* perm);
+
 /* DEVICE, asynchronous.  Cast new key/value rows to BFP (Sec. II-B) and store them in the cache
  * (Sec. III: the keys of each head are kept in block format; values likewise).
  *   k_new, v_new : DEVICE [batch][n_new][n_kv_heads][head_dim] of `dtype`, channel stride 1,

@@ -180,6 +180,19 @@ int kvo_permute_weights(const float* w_in, float* w_out, int32_t n_heads, int32_
     return 0;
 }
 
+// Sec. III, last paragraph: the projection after attention takes the value permutation on its columns:
+// out[r][(h, j)] = in[r][(h, perm[h / heads_per_perm][j])].
+int kvo_permute_weight_columns(const float* w_in, float* w_out, int64_t n_rows, int32_t n_heads, int32_t D,
+                               int32_t heads_per_perm, const int32_t* perm) {
+    if (!w_in || !w_out || !perm || n_rows <= 0 || n_heads <= 0 || D <= 0 || heads_per_perm <= 0) return -1;
+    for (int64_t r = 0; r < n_rows; ++r)
+        for (int h = 0; h < n_heads; ++h)
+            for (int j = 0; j < D; ++j)
+                w_out[(r * n_heads + h) * D + j] =
+                    w_in[(r * n_heads + h) * D + perm[(int64_t)(h / heads_per_perm) * D + j]];
+    return 0;
+}
+
 // ---------------------------------------------------------------------------
 // Cast rows to BFP (Sec. II-B) and place them in the packed cache.
 //   x        : [B][n_new][H][D] fp32, contiguous

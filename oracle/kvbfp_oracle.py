@@ -33,7 +33,7 @@ def lib():
     if _lib is None:
         build()
         _lib = C.CDLL(_SO)
-        for name in ("kvo_calibrate_perm", "kvo_permute_weights", "kvo_quantize_append",
+        for name in ("kvo_calibrate_perm", "kvo_permute_weights", "kvo_permute_weight_columns", "kvo_quantize_append",
                      "kvo_dequantize", "kvo_decode_attention", "kvo_scores", "kvo_permute_rope",
                      "kvo_decode_attention_rope"):
             getattr(_lib, name).restype = C.c_int
@@ -93,6 +93,19 @@ def permute_weights(w, n_heads, D, perm, heads_per_perm=1):
                                    _p(perm, C.c_int32))
     if rc != 0:
         raise ValueError("kvo_permute_weights rc=%d" % rc)
+    return out
+
+
+def permute_weight_columns(w, n_heads, D, perm, heads_per_perm=1):
+    """w: [n_rows][n_heads*D]; Sec. III, last paragraph."""
+    w = _f32(w)
+    perm = np.ascontiguousarray(perm, dtype=np.int32)
+    out = np.empty_like(w)
+    rc = lib().kvo_permute_weight_columns(_p(w, C.c_float), _p(out, C.c_float), C.c_int64(w.shape[0]),
+                                          C.c_int32(n_heads), C.c_int32(D), C.c_int32(heads_per_perm),
+                                          _p(perm, C.c_int32))
+    if rc != 0:
+        raise ValueError("kvo_permute_weight_columns rc=%d" % rc)
     return out
 
 

@@ -223,6 +223,49 @@ int kvbfp_permute_weights(const void* w_in, void* w_out, kvbfp_dtype dtype, int3
     return KVBFP_OK;
 }
 
+int kvbfp_permute_weight_columns(const void* w_in, void* w_out, kvbfp_dtype dtype, int64_t n_rows,
+                                 int32_t n_heads, int32_t head_dim, int32_t heads_per_perm,
+                                 const int32_t* perm) {
+    clear_error();
+    if (!w_in || !w_out || !perm) return fail(KVBFP_ERR_INVALID_ARG, "permute_weight_columns: NULL pointer");
+    const int esz = dtype_size(dtype);
+    if (esz == 0) return fail(KVBFP_ERR_INVALID_ARG, "permute_weight_columns: unknown dtype %d", (int)dtype);
+    if (n_rows <= 0 || n_heads <= 0 || head_dim <= 0 || heads_per_perm <= 0)
+        return fail(KVBFP_ERR_INVALID_ARG, "permute_weight_columns: sizes must be positive");
+    if (n_heads % heads_per_perm != 0)
+        return fail(KVBFP_ERR_INVALID_ARG, "permute_weight_columns: n_heads %d not divisible by heads_per_perm %d",
+                    n_heads, heads_per_perm);
+    const size_t row_bytes = (size_t)n_heads * (size_t)head_dim * (size_t)esz;
+    const size_t total = (size_t)n_rows * row_bytes;
+    const char* a = (const char*)w_in;
+    char* b = (char*)w_out;
+    if (!(a + total <= b || b + total <= a))
+        return fail(KVBFP_ERR_INVALID_ARG, "permute_weight_columns: w_in and w_out overlap");
+    const int32_t n_perms = n_heads / heads_per_perm;
+    std::vector<uint8_t> seen((size_t)head_dim);
+    for (int32_t g = 0; g < n_perms; ++g) {
+        std::fill(seen.begin(), seen.end(), 0);
+        for (int32_t j = 0; j < head_dim; ++j) {
+            const int32_t c = perm[(int64_t)g * head_dim + j];
+            if (c < 0 || c >= head_dim || seen[(size_t)c])
+                return fail(KVBFP_ERR_INVALID_ARG, "permute_weight_columns: perm row %d is not a permutation", g);
+            seen[(size_t)c] = 1;
+        }
+    }
+    for (int64_t r = 0; r < n_rows; ++r) {
+        const char* src = a + (size_t)r * row_bytes;
+        char* dst = b + (size_t)r * row_bytes;
+        for (int32_t h = 0; h < n_heads; ++h) {
+            const int32_t* pi = perm + (int64_t)(h / heads_per_perm) * head_dim;
+            const size_t head_off = (size_t)h * (size_t)head_dim * (size_t)esz;
+            for (int32_t j = 0; j < head_dim; ++j)
+                std::memcpy(dst + head_off + (size_t)j * (size_t)esz, src + head_off + (size_t)pi[j] * (size_t)esz,
+                            (size_t)esz);
+        }
+    }
+    return KVBFP_OK;
+}
+
 int kvbfp_permute_rope(const float* theta, kvbfp_rope_pairs pairs, int32_t n_heads, int32_t head_dim,
                        const int32_t* perm, float* theta_out, int32_t* partner_out, float* sign_out) {
     clear_error();

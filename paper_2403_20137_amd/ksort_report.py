@@ -3,9 +3,10 @@
 Alg. 1: per KV head, rank the rows of W_k by Euclidean norm, reorder the rows of W_k and of W_q alike
 (Eq. (2)-(3): the scores do not change), and keep the keys in Block Floating Point.  Values are
 treated the same way with their own permutation (Sec. III, last paragraph); the output then stays
-in the reordered channel order, which stands for reordering the columns of the next projection.
-The reorder lives in the weights, so nothing is gathered at run time: both pipelines below call
-quantize_append / decode_attention without a permutation.
+in the reordered channel order and the projection after attention, W_o, gets its columns reordered
+to match.  The reorder lives in the weights, so nothing is gathered at run time: both pipelines
+below call quantize_append / decode_attention without a permutation, and both end in the same
+model-width vector W_o . out.
 
 Table I reports perplexity for the original and the sorted channel order at block sizes 128, 64, 32.
 Perplexity needs the model's weights and a corpus; what this report measures instead, on synthetic
@@ -43,6 +44,13 @@ def synthetic_projections(n_kv_heads, group, d_model, n_outlier_rows, gain, seed
             rows = torch.randperm(D, generator=g)[:n_outlier_rows]
             w[h * D + rows] *= gain
     return wq, wk, wv
+
+
+def synthetic_output_projection(n_kv_heads, group, d_model, seed):
+    """W_o [d_model][Hq*D] ~ N(0, 1/(Hq*D)): the projection that consumes the attention output."""
+    g = torch.Generator().manual_seed(seed + 2)
+    hq = n_kv_heads * group
+    return torch.randn(d_model, hq * D, generator=g) / (hq * D) ** 0.5
 
 
 def project(x, w, n_heads, dtype):
@@ -89,6 +97,10 @@ def run(tokens=4096, n_kv_heads=8, group=4, d_model=1024, n_outlier_rows=4, gain
     wq_s = kvbfp.permute_weights(wq, n_kv_heads * group, D, perm_k, heads_per_perm=group)
     wk_s = kvbfp.permute_weights(wk, n_kv_heads, D, perm_k)
     wv_s = kvbfp.permute_weights(wv, n_kv_heads, D, perm_v)
+    # Sec. III, last paragraph: the value permutation goes into the columns of the next projection
+    wo = synthetic_output_projection(n_kv_heads, group, d_model, seed)
+    wo_s = kvbfp.permute_weight_columns(wo, n_kv_heads * group, D, perm_v, heads_per_perm=group)
+    w_out = {"original": wo.double().to(device), "sorted": wo_s.double().to(device)}
 
     g = torch.Generator().manual_seed(seed + 1)
     x = torch.randn(tokens, d_model, generator=g).to(device)
@@ -108,14 +120,21 @@ def run(tokens=4096, n_kv_heads=8, group=4, d_model=1024, n_outlier_rows=4, gain
     for h in range(n_kv_heads * group):
         ref_s_unperm[h, pv[h // group]] = ref_s[h]
     invariance = rel_err(ref_s_unperm, ref_o)
+    # ... and after W_o (columns reordered for the sorted pipeline) the two end in the same vector
+    y_ref = {name: w_out[name] @ pipes[name][3].reshape(-1) for name in pipes}
+    invariance_y = rel_err(y_ref["sorted"], y_ref["original"])
     for n in blocks:
         row = {"block": n, "mant_bits": mant_bits}
         for name, (q, k, v, ref) in pipes.items():
-            row[name] = rel_err(bfp_attention(q, k, v, n, mant_bits, scale, device), ref)
+            out = bfp_attention(q, k, v, n, mant_bits, scale, device)
+            row[name] = rel_err(out, ref)
+            # error of the model-width vector after the output projection, against the unquantized ORIGINAL pipeline
+            row[name + "_after_w_o"] = rel_err(w_out[name] @ out.reshape(-1), y_ref["original"])
         rows.append(row)
     return {"tokens": tokens, "n_kv_heads": n_kv_heads, "group": group, "d_model": d_model,
             "outlier_rows_per_head": n_outlier_rows, "gain": gain, "dtype": str(dtype).replace("torch.", ""),
-            "reorder_invariance_rel_err": invariance, "rows": rows}
+            "reorder_invariance_rel_err": invariance, "reorder_invariance_after_w_o_rel_err": invariance_y,
+            "rows": rows}
 
 
 def main():
@@ -135,9 +154,12 @@ def main():
           "%d planted rows x%.0f per head, %d-bit mantissas" % (r["tokens"], r["n_kv_heads"], r["group"],
                                                               r["outlier_rows_per_head"], r["gain"], args.mant_bits))
     print("reorder invariance of the unquantized attention (Eq. (2)-(3)): %.2e" % r["reorder_invariance_rel_err"])
-    print("%-12s %-12s %-12s" % ("block size", "original", "sorted"))
+    print("same after the output projection with reordered columns (Sec. III): %.2e"
+          % r["reorder_invariance_after_w_o_rel_err"])
+    print("%-12s %-12s %-12s %-20s %-20s" % ("block size", "original", "sorted", "original, after W_o", "sorted, after W_o"))
     for row in r["rows"]:
-        print("%-12d %-12.4f %-12.4f" % (row["block"], row["original"], row["sorted"]))
+        print("%-12d %-12.4f %-12.4f %-20.4f %-20.4f" % (row["block"], row["original"], row["sorted"],
+                                                     row["original_after_w_o"], row["sorted_after_w_o"]))
 
 
 if __name__ == "__main__":

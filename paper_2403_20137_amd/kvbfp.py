@@ -22,7 +22,7 @@ ROPE_PAIRS_ADJACENT, ROPE_PAIRS_HALF_SPLIT = 0, 1
 _TORCH_DT = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
 _NP_DT = {np.dtype(np.float32): F32, np.dtype(np.float16): F16}
 
-EXPORTS = ["kvbfp_cache_bytes", "kvbfp_calibrate_perm", "kvbfp_permute_weights",
+EXPORTS = ["kvbfp_cache_bytes", "kvbfp_calibrate_perm", "kvbfp_permute_weights", "kvbfp_permute_weight_columns",
            "kvbfp_quantize_append", "kvbfp_dequantize", "kvbfp_decode_workspace_bytes",
            "kvbfp_decode_attention", "kvbfp_decode_attention_qbfp", "kvbfp_append_decode_attention", "kvbfp_decode_attention_multi", "kvbfp_decode_attention_profile",
            "kvbfp_permute_rope", "kvbfp_decode_attention_rope",
@@ -69,6 +69,8 @@ def lib():
                                            C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_int32, C.c_void_p]
         l.kvbfp_permute_weights.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int32,
                                             C.c_int64, C.c_int32, C.c_void_p]
+        l.kvbfp_permute_weight_columns.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int32, C.c_int32,
+                                                   C.c_int32, C.c_void_p]
         l.kvbfp_permute_rope.argtypes = [C.c_void_p, C.c_int, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                          C.c_void_p, C.c_void_p]
         l.kvbfp_decode_attention_rope.argtypes = [C.POINTER(Layout), C.POINTER(CachePtrs), C.c_int32, C.c_void_p,
@@ -245,6 +247,21 @@ def permute_weights(w, n_heads, head_dim, perm, heads_per_perm=1):
     out = np.empty_like(arr)
     _check(lib().kvbfp_permute_weights(arr.ctypes.data, out.ctypes.data, dt, n_heads, head_dim,
                                        arr.shape[1], heads_per_perm, perm.ctypes.data))
+    if isinstance(w, torch.Tensor):
+        t = torch.from_numpy(out)
+        return t.view(torch.bfloat16) if w.dtype == torch.bfloat16 else t
+    return out
+
+
+def permute_weight_columns(w, n_heads, head_dim, perm, heads_per_perm=1):
+    """HOST, out of place.  w: [n_rows][n_heads*head_dim]; returns the copy with reordered columns."""
+    arr, dt = _host_array(w)
+    perm = np.ascontiguousarray(perm, dtype=np.int32)
+    if arr.ndim != 2 or arr.shape[1] != n_heads * head_dim:
+        raise ValueError("w must be [n_rows][n_heads*head_dim]")
+    out = np.empty_like(arr)
+    _check(lib().kvbfp_permute_weight_columns(arr.ctypes.data, out.ctypes.data, dt, arr.shape[0], n_heads, head_dim,
+                                              heads_per_perm, perm.ctypes.data))
     if isinstance(w, torch.Tensor):
         t = torch.from_numpy(out)
         return t.view(torch.bfloat16) if w.dtype == torch.bfloat16 else t

@@ -20,6 +20,8 @@ int kvo_calibrate_perm(const float* x, int64_t n_samples, int32_t n_heads, int32
                        int64_t head_stride, int64_t chan_stride, int32_t stat, int32_t descending, int32_t* perm_out);
 int kvo_permute_weights(const float* w_in, float* w_out, int32_t n_heads, int32_t D, int64_t row_len,
                         int32_t heads_per_perm, const int32_t* perm);
+int kvo_permute_weight_columns(const float* w_in, float* w_out, int64_t n_rows, int32_t n_heads, int32_t D,
+                               int32_t heads_per_perm, const int32_t* perm);
 int kvo_quantize_append(int32_t B, int32_t H, int32_t D, int32_t n, int32_t p, int64_t S_max, const float* x,
                         int32_t n_new, const int64_t* pos, const int32_t* perm, uint8_t* mant, uint8_t* exp);
 int kvo_dequantize(int32_t B, int32_t H, int32_t D, int32_t n, int32_t p, int64_t S_max, const uint8_t* mant,
@@ -92,6 +94,11 @@ int main() {
         EXPECT(kvbfp_permute_weights(w.data(), wl.data(), KVBFP_F32, H * G, D, row_len, G, po.data()) == KVBFP_OK);
         EXPECT(kvo_permute_weights(w.data(), wo.data(), H * G, D, row_len, G, po.data()) == 0);
         EXPECT(wl == wo);
+        // the same buffer read as [row_len][H*G*D]: columns
+        EXPECT(kvbfp_permute_weight_columns(w.data(), wl.data(), KVBFP_F32, row_len, H * G, D, G, po.data()) == KVBFP_OK);
+        EXPECT(kvo_permute_weight_columns(w.data(), wo.data(), row_len, H * G, D, G, po.data()) == 0);
+        EXPECT(wl == wo);
+        EXPECT(kvbfp_permute_weight_columns(w.data(), w.data() + 1, KVBFP_F32, row_len, H * G, D, G, po.data()) == KVBFP_ERR_INVALID_ARG);
         // error paths
         EXPECT(kvbfp_permute_weights(w.data(), w.data(), KVBFP_F32, H * G, D, row_len, G, po.data()) == KVBFP_ERR_INVALID_ARG);
         std::vector<int32_t> notperm(po);

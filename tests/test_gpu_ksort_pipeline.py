@@ -22,6 +22,14 @@ def test_reorder_leaves_unquantized_attention_alone(report):
     assert report["reorder_invariance_rel_err"] < 5e-3
 
 
+def test_reordered_output_projection_ends_in_the_same_vector(report):
+    # Sec. III, last paragraph: W_o with reordered columns consumes the output in cache order
+    assert report["reorder_invariance_after_w_o_rel_err"] < 5e-3
+    rows = {r["block"]: r for r in report["rows"]}
+    for n in (64, 32, 16):
+        assert rows[n]["sorted_after_w_o"] < 0.9 * rows[n]["original_after_w_o"], (n, rows[n])
+
+
 def test_sorting_lowers_the_error_below_the_full_row_block(report):
     rows = {r["block"]: r for r in report["rows"]}
     # Table I, n = 128: one block per row, the order inside it cannot matter
@@ -46,6 +54,9 @@ def test_sorted_pipeline_matches_oracle():
     wv_s = kvbfp.permute_weights(wv, hkv, R.D, perm_v)
     assert np.array_equal(wk_s.numpy(), O.permute_weights(wk.numpy(), hkv, R.D, perm_k))
     assert np.array_equal(wq_s.numpy(), O.permute_weights(wq.numpy(), hkv * grp, R.D, perm_k, grp))
+    wo = R.synthetic_output_projection(hkv, grp, dm, seed=11)
+    wo_s = kvbfp.permute_weight_columns(wo, hkv * grp, R.D, perm_v, heads_per_perm=grp)
+    assert np.array_equal(wo_s.numpy(), O.permute_weight_columns(wo.numpy(), hkv * grp, R.D, perm_v, grp))
     x = torch.randn(T, dm)
     xq = torch.randn(1, dm)
     k = R.project(x, wk_s, hkv, torch.bfloat16)

@@ -224,3 +224,25 @@ def test_noalloc_entry_rejects_what_does_not_fit_without_touching_the_gpu():
     rc = kvbfp.lib().kvbfp_decode_attention_noalloc(C.byref(L), C.byref(ptrs), 32, C.c_void_p(0x50000), kvbfp.BF16, None,
                                                     4096, C.c_float(0.1), None, None, 0, C.c_void_p(0x60000), None)
     assert rc == kvbfp.ERR_WORKSPACE and "scratch" in kvbfp.last_error()
+
+
+def test_permute_weight_columns_equals_oracle_and_rejects_bad_input():
+    rng = np.random.default_rng(21)
+    H, G, D, R = 2, 4, 128, 37
+    wo = rng.standard_normal((R, H * G * D)).astype(np.float32)
+    perm = np.stack([rng.permutation(D) for _ in range(H)]).astype(np.int32)
+    assert np.array_equal(kvbfp.permute_weight_columns(wo, H * G, D, perm, G),
+                          O.permute_weight_columns(wo, H * G, D, perm, G))
+    wo16 = torch.from_numpy(wo).to(torch.bfloat16)
+    out = kvbfp.permute_weight_columns(wo16, H * G, D, perm, G)
+    assert out.dtype == torch.bfloat16
+    assert np.array_equal(synth.to_f32_numpy(out), O.permute_weight_columns(synth.to_f32_numpy(wo16), H * G, D, perm, G))
+    bad = perm.copy()
+    bad[1, 5] = bad[1, 6]
+    with pytest.raises(kvbfp.KvbfpError):
+        kvbfp.permute_weight_columns(wo, H * G, D, bad, G)
+    with pytest.raises(kvbfp.KvbfpError):
+        kvbfp.permute_weight_columns(wo, H * G, D, perm, 3)
+    rc = kvbfp.lib().kvbfp_permute_weight_columns(wo.ctypes.data, wo.ctypes.data + 64, kvbfp.F32, R, H * G, D, G,
+                                                  perm.ctypes.data)
+    assert rc == kvbfp.ERR_INVALID_ARG and "overlap" in kvbfp.last_error()

@@ -110,3 +110,33 @@ def test_reorder_lowers_quantization_error_except_at_full_head_blocks(n):
         assert err1 == pytest.approx(err0, rel=1e-12)
     else:
         assert err1 < 0.9 * err0
+
+
+def test_permute_weight_columns_carries_the_value_permutation_into_the_next_projection():
+    # Sec. III, last paragraph: with W_v's rows and W_o's columns reordered alike, W_o' (P W_v' x) =
+    # W_o (P W_v x) for any mixing P over tokens; exact on integer-valued data.  Several query heads
+    # share a KV head's permutation.
+    rng = np.random.default_rng(5)
+    Hkv, G, D, F, T = 2, 3, 8, 6, 5
+    wv = rng.integers(-9, 10, size=(Hkv * D, F)).astype(np.float32)
+    wo = rng.integers(-9, 10, size=(F, Hkv * G * D)).astype(np.float32)
+    perm = np.stack([rng.permutation(D) for _ in range(Hkv)]).astype(np.int32)
+    wv_p = O.permute_weights(wv, Hkv, D, perm)
+    wo_p = O.permute_weight_columns(wo, Hkv * G, D, perm, heads_per_perm=G)
+    # written out: column (h, j) of the result is column (h, perm[h // G][j]) of the input
+    for h in range(Hkv * G):
+        for j in range(D):
+            assert np.array_equal(wo_p[:, h * D + j], wo[:, h * D + perm[h // G][j]])
+    x = rng.integers(-5, 6, size=(T, F)).astype(np.float64)
+    mix = rng.integers(0, 4, size=(Hkv * G, T)).astype(np.float64)          # one row of "probabilities" per query head
+    v = (x @ wv.T.astype(np.float64)).reshape(T, Hkv, D)
+    v_p = (x @ wv_p.T.astype(np.float64)).reshape(T, Hkv, D)
+    o = np.stack([mix[h] @ v[:, h // G] for h in range(Hkv * G)]).reshape(-1)
+    o_p = np.stack([mix[h] @ v_p[:, h // G] for h in range(Hkv * G)]).reshape(-1)
+    assert not np.array_equal(o, o_p)
+    assert np.array_equal(wo.astype(np.float64) @ o, wo_p.astype(np.float64) @ o_p)
+    # a transposed reading (scatter instead of gather) would break the product
+    wo_wrong = np.empty_like(wo)
+    for h in range(Hkv * G):
+        wo_wrong[:, h * D + perm[h // G]] = wo[:, h * D:(h + 1) * D]
+    assert not np.array_equal(wo_wrong.astype(np.float64) @ o_p, wo.astype(np.float64) @ o)
