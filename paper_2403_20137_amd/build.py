@@ -10,7 +10,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libkvbfp.so")
-SOURCES = ["host_ops.cpp", "quantize.hip", "attention.hip", "decode_mfma.hip", "decode_mfma_p8.hip", "measure.hip"]
+SOURCES = ["host_ops.cpp", "quantize.hip", "attention.hip", "decode_mfma.hip", "decode_mfma_p8.hip", "decode_rope.hip", "measure.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -559,6 +559,9 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
     // (mantissa planes are 16-byte aligned, checked above; exponent planes that are not go to the general
     // pass, which reads them byte by byte)
     const bool fast = !rope && a.G <= 32 && aligned16(a.k_exp) && aligned16(a.v_exp);
+    // rotation at read: the matrix-core pass takes 4-bit mantissas with 16-bit I/O, four heads per launch
+    const bool rope_fast = rope && dtype != KVBFP_F32 && L->mant_bits == 4 && a.G <= 32 && aligned16(a.k_exp) &&
+                           aligned16(a.v_exp);
     a.g_base = 0;
     a.g_cnt = a.G < 8 ? a.G : 8;
     // The current token (kvbfp_append_decode_attention): cast inside the LDS split pass, else by the
@@ -604,6 +607,12 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
                 err = L->mant_bits == 4 ? launch_decode_split_mfma(a, (int)dtype, L->block, L->batch, s)
                                         : launch_decode_split_mfma_p8(a, (int)dtype, L->block, L->batch, s);
                 a.k_new = a.v_new = nullptr;       // the current token is cast by the first launch only
+            }
+        } else if (rope_fast) {
+            for (int g0 = 0; g0 < a.G && err == hipSuccess; g0 += 4) {
+                a.g_base = g0;
+                a.g_cnt = a.G - g0 < 4 ? a.G - g0 : 4;
+                err = launch_decode_split_rope(a, (int)dtype, L->block, L->batch, s);
             }
         } else {
             if (rope) {

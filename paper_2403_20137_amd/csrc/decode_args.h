@@ -78,5 +78,7 @@ hipError_t launch_decode_split_mfma(const DecodeArgs& a, int dtype, int block, i
 // head subsets.)
 // The same for 8-bit mantissas (decode_mfma_p8.hip).
 hipError_t launch_decode_split_mfma_p8(const DecodeArgs& a, int dtype, int block, int batch, hipStream_t s);
+// Rotation at read on the matrix cores (decode_rope.hip): 4-bit mantissas, 16-bit I/O, a.g_cnt <= 4.
+hipError_t launch_decode_split_rope(const DecodeArgs& a, int dtype, int block, int batch, hipStream_t s);
 
 }  // namespace kvbfp
