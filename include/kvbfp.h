@@ -273,7 +273,7 @@ int kvbfp_permute_rope(const float* theta, kvbfp_rope_pairs pairs, int32_t n_hea
  * As kvbfp_decode_attention, except that the key of token t of a sequence enters the score as
  *     k_rot[j] = k'[j] cos(t Theta'[j]) + s'[j] k'[i'[j]] sin(t Theta'[j])      (k' = the cached row)
  * with the token index t = its position in the cache and the angle t * Theta'[j] taken exactly (the
- * kernel builds its sine/cosine tables in double precision).  q is used as given: the caller rotates the
+ * kernels start their sine/cosine phasors in double precision).  q is used as given: the caller rotates the
  * query at its own token index, in whatever order it keeps it (perm_k gathers it as usual).
  *   rope_theta, rope_sign : DEVICE float [n_kv_heads][head_dim];  rope_partner : DEVICE int32, same shape:
  *       what kvbfp_permute_rope returns for perm_k (identity permutation if the rows were never
@@ -282,10 +282,13 @@ int kvbfp_permute_rope(const float* theta, kvbfp_rope_pairs pairs, int32_t n_hea
  *       are memory-safe with an unspecified result.
  *   kernel_ms : HOST float[2] or NULL.  Non-NULL: the call waits for its kernels and returns the
  *       durations of the split pass and of the combine pass in milliseconds (HIP events).
- * One query token per sequence, query in its input type.  The rotation costs vector arithmetic per
- * cached key element that the plain path does not have; this pass is several times slower than
- * kvbfp_decode_attention on the same cache (a cache of already rotated keys, reordered at append time,
- * needs none of it).
+ * One query token per sequence, query in its input type.  4-bit mantissas with fp16/bf16 I/O take a
+ * matrix-core pass (the rotation is carried by the query operand per 64-token tile and by a table of
+ * cos/sin per token offset; same bars as kvbfp_decode_attention, any exponent bytes 3..254, queries
+ * and softmax_scale whose product stays finite in fp32); 8-bit mantissas and fp32 I/O take a vector-ALU
+ * pass that is several times slower.  Either way the rotation costs arithmetic per cached key element
+ * that the plain path does not have: about 2.6x the time of kvbfp_decode_attention on the same cache
+ * (a cache of already rotated keys, reordered at append time, needs none of it).
  * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP. */
 int kvbfp_decode_attention_rope(const kvbfp_layout* layout, const kvbfp_cache* cache, int32_t n_q_heads,
                                 const void* q, kvbfp_dtype dtype, const int32_t* seq_len_dev,

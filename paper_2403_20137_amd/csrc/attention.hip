@@ -560,8 +560,8 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
     // pass, which reads them byte by byte)
     const bool fast = !rope && a.G <= 32 && aligned16(a.k_exp) && aligned16(a.v_exp);
     // rotation at read: the matrix-core pass takes 4-bit mantissas with 16-bit I/O, four heads per launch
-    const bool rope_fast = rope && dtype != KVBFP_F32 && L->mant_bits == 4 && a.G <= 32 && aligned16(a.k_exp) &&
-                           aligned16(a.v_exp);
+    const bool rope_fast = rope && !paging && dtype != KVBFP_F32 && L->mant_bits == 4 && a.G <= 32 &&
+                           aligned16(a.k_exp) && aligned16(a.v_exp);
     a.g_base = 0;
     a.g_cnt = a.G < 8 ? a.G : 8;
     // The current token (kvbfp_append_decode_attention): cast inside the LDS split pass, else by the

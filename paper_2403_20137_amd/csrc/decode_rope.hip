@@ -46,6 +46,7 @@ using namespace kvbfp::dev;
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 // values: as in the plain pass, value * 2^-kShift in bf16 with the exponent byte as the scale operand
 constexpr int kShift = 7;
@@ -105,7 +106,7 @@ __device__ __forceinline__ void transpose_rows(u32x4& v) {
 
 constexpr int kHeadStride = kD + 4;     // fp32 words per head of the normalised queries: four heads hit different banks
 
-template <int N, bool PAGED>
+template <int N>
 __global__ __launch_bounds__(256) void decode_split_rope_p4(DecodeArgs a, int dt) {
     constexpr int NB = kD / N;
     constexpr int NH = 4;
@@ -127,7 +128,7 @@ __global__ __launch_bounds__(256) void decode_split_rope_p4(DecodeArgs a, int dt
     float (*o_s)[NH][kD] = reinterpret_cast<float (*)[NH][kD]>(tab_raw);
 
     const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;    // scalar: tile bases stay in SGPRs
     const int j = lane & 15, kg = lane >> 4;
     const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
     const int h0 = kvh * a.G + a.g_base;
@@ -222,7 +223,7 @@ __global__ __launch_bounds__(256) void decode_split_rope_p4(DecodeArgs a, int dt
     const uint32_t sel_even = a_par ? 0x01000c0cu : 0x0c0c0100u;
     const uint32_t sel_odd = a_par ? 0x03020c0cu : 0x0c0c0302u;
 
-    const int64_t base = PAGED ? 0 : ((int64_t)b * a.H_kv + kvh) * a.max_seq + t_begin;
+    const int64_t base = ((int64_t)b * a.H_kv + kvh) * a.max_seq + t_begin;
     const uint8_t* __restrict__ k_mant = a.k_mant + base * 64;
     const uint8_t* __restrict__ v_mant = a.v_mant + base * 64;
     const uint8_t* __restrict__ k_exp = a.k_exp + base * NB;
@@ -236,19 +237,50 @@ __global__ __launch_bounds__(256) void decode_split_rope_p4(DecodeArgs a, int dt
 
     const uint4* tab = reinterpret_cast<const uint4*>(tab_raw);
 
+    // The rows of one 64-token tile as this lane loads them: key chunk kg of rows 16u + j with the row's
+    // exponent bytes, requested before the tile's query operands are built; value dword j of rows
+    // 16u + 4kg + i with that dword's exponent byte, requested before the score phase.
+    struct KeyRows {
+        u32x4 kw[4];
+        uint32_t kex[4][N == 16 ? 2 : 1];
+    };
+    struct ValueRows {
+        uint32_t vw[16];
+        uint32_t vex[16];
+    };
+    auto fetch = [&](const int T0, auto full_tag, KeyRows& d) {
+        constexpr bool FULL = decltype(full_tag)::value;
+        const size_t R0 = (size_t)T0;   // wave-uniform
+        const uint8_t* __restrict__ kp = k_mant + R0 * 64;
+        const uint8_t* __restrict__ kep = k_exp + R0 * NB;
+        const int left = n_tok - T0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t r = FULL ? (uint32_t)(16 * u + j) : (uint32_t)min(16 * u + j, left - 1);
+            d.kw[u] = __builtin_nontemporal_load((const u32x4*)(kp + r * 64u + (uint32_t)kg * 16u));
+            if constexpr (N == 16) {
+                const u32x2 e2 = *(const u32x2*)(kep + r * 8u);
+                d.kex[u][0] = e2[0]; d.kex[u][1] = e2[1];
+            } else if constexpr (N == 32) {
+                d.kex[u][0] = *(const uint32_t*)(kep + r * 4u);
+            } else if constexpr (N == 64) {
+                d.kex[u][0] = *(const uint16_t*)(kep + r * 2u);
+            } else {
+                d.kex[u][0] = kep[r];
+            }
+        }
+    };
+
     auto tile = [&](const int T0, auto full_tag) {
         constexpr bool FULL = decltype(full_tag)::value;
-        const size_t R0 = PAGED ? (size_t)kvbfp::cache_row(a, b, kvh, t_begin + T0) : (size_t)T0;   // wave-uniform
-        const uint8_t* __restrict__ kp = k_mant + R0 * 64;
-        const uint8_t* __restrict__ vp = v_mant + R0 * 64;
-        const uint8_t* __restrict__ kep = k_exp + R0 * NB;
-        const uint8_t* __restrict__ vep = v_exp + R0 * NB;
         const int left = n_tok - T0;
-
+        KeyRows d;
+        fetch(T0, full_tag, d);          // the operand build below covers part of the wait
         // ---------------- the tile's query operands: row j = 4 * head + limb (two binary16 limbs, rows of limb 2, 3 zero)
         f16x8 A1[4], A2[4];
         {
             const int gi = j >> 2, limb = j & 3;
+            const uint32_t m_hi = limb == 0 ? 0xFFFFFFFFu : 0u, m_lo = limb == 1 ? 0xFFFFFFFFu : 0u;
 #pragma unroll
             for (int blk = 0; blk < 4; ++blk) {
                 const int at = blk * 32 + kg * 8;
@@ -264,15 +296,21 @@ __global__ __launch_bounds__(256) void decode_split_rope_p4(DecodeArgs a, int dt
                     c0[4 * h] = cv.x; c0[4 * h + 1] = cv.y; c0[4 * h + 2] = cv.z; c0[4 * h + 3] = cv.w;
                     s0[4 * h] = sv.x; s0[4 * h + 1] = sv.y; s0[4 * h + 2] = sv.z; s0[4 * h + 3] = sv.w;
                 }
+                uint32_t p1[4], p2[4];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const float a1 = fmaf(x[i], c0[i], y[i] * s0[i]);
-                    const float a2 = fmaf(y[i], c0[i], -(x[i] * s0[i]));
-                    const _Float16 h1 = (_Float16)a1, h2 = (_Float16)a2;
-                    const _Float16 l1 = (_Float16)(a1 - (float)h1), l2 = (_Float16)(a2 - (float)h2);
-                    A1[blk][i] = limb == 0 ? h1 : (limb == 1 ? l1 : (_Float16)0.0f);
-                    A2[blk][i] = limb == 0 ? h2 : (limb == 1 ? l2 : (_Float16)0.0f);
+                for (int i = 0; i < 8; i += 2) {          // two slots per register
+                    const f32x2 a1 = {fmaf(x[i], c0[i], y[i] * s0[i]), fmaf(x[i + 1], c0[i + 1], y[i + 1] * s0[i + 1])};
+                    const f32x2 a2 = {fmaf(y[i], c0[i], -(x[i] * s0[i])), fmaf(y[i + 1], c0[i + 1], -(x[i + 1] * s0[i + 1]))};
+                    const f16x2 h1 = __builtin_convertvector(a1, f16x2), h2 = __builtin_convertvector(a2, f16x2);
+                    const f16x2 l1 = __builtin_convertvector(a1 - __builtin_convertvector(h1, f32x2), f16x2);
+                    const f16x2 l2 = __builtin_convertvector(a2 - __builtin_convertvector(h2, f32x2), f16x2);
+                    // (masks, not selects: no branch around the low limb)
+                    p1[i / 2] = (__builtin_bit_cast(uint32_t, h1) & m_hi) | (__builtin_bit_cast(uint32_t, l1) & m_lo);
+                    p2[i / 2] = (__builtin_bit_cast(uint32_t, h2) & m_hi) | (__builtin_bit_cast(uint32_t, l2) & m_lo);
                 }
+                A1[blk] = __builtin_bit_cast(f16x8, u32x4{p1[0], p1[1], p1[2], p1[3]});
+                A2[blk] = __builtin_bit_cast(f16x8, u32x4{p2[0], p2[1], p2[2], p2[3]});
+                __builtin_amdgcn_sched_barrier(0);      // one chunk's worth of LDS reads in registers at a time
             }
             // everybody has read the phasor of this tile: advance it to the wavefront's next tile
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -288,35 +326,52 @@ __global__ __launch_bounds__(256) void decode_split_rope_p4(DecodeArgs a, int dt
             }
         }
 
-        // ---------------- scores of 64 tokens
-        float s[4];
+        ValueRows dv;
+        {
+            const size_t R0 = (size_t)T0;   // wave-uniform
+            const uint8_t* __restrict__ vp = v_mant + R0 * 64;
+            const uint8_t* __restrict__ vep = v_exp + R0 * NB;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const uint32_t r = FULL ? (uint32_t)(16 * u + j) : (uint32_t)min(16 * u + j, left - 1);
-            u32x4 w = __builtin_nontemporal_load((const u32x4*)(kp + r * 64u + (uint32_t)kg * 16u));
-            uint32_t ex[2] = {0u, 0u};          // the row's exponent bytes
-            if (N == 16) {
-                const u32x2 e2 = *(const u32x2*)(kep + r * 8u);
-                ex[0] = e2[0]; ex[1] = e2[1];
-            } else if (N == 32) {
-                ex[0] = *(const uint32_t*)(kep + r * 4u);
-            } else if (N == 64) {
-                ex[0] = *(const uint16_t*)(kep + r * 2u);
-            } else {
-                ex[0] = kep[r];
-            }
-            transpose_rows(w);                  // w[blk] = dword kg of chunk blk: channels 32 blk + 8 kg ..+7
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t r = FULL ? (uint32_t)(16 * u + 4 * kg + i) : (uint32_t)min(16 * u + 4 * kg + i, left - 1);
+                    dv.vw[4 * u + i] = __builtin_nontemporal_load((const uint32_t*)(vp + r * 64u + 4u * (uint32_t)j));
+                    dv.vex[4 * u + i] = vep[r * NB + (uint32_t)((8 * j) / N)];
+                }
+        }
+
+        // ---------------- scores of 64 tokens: sixteen (stage u, chunk blk) steps; the table entries of a step
+        // are read one step ahead, and the scheduling barriers keep later reads from piling up in registers
+        float s[4];
+        {
+            uint4 tb[2][4];
+            auto read_table = [&](const int c, uint4 (&t)[4]) {
+                const int e16 = (((c & 3) * 4 * 4 + kg) * 4 + (c >> 2)) * 16 + j;
+#pragma unroll
+                for (int kind = 0; kind < 4; ++kind) t[kind] = tab[e16 + kind * kKind];     // cos hi, sin hi, cos lo, sin lo
+            };
+            read_table(0, tb[0]);
+            u32x4 w = {0u, 0u, 0u, 0u};
             float acc_s = 0.f;
 #pragma unroll
-            for (int blk = 0; blk < 4; ++blk) {
+            for (int c = 0; c < 16; ++c) {
+                const int u = c >> 2, blk = c & 3;
+                if (c + 1 < 16) read_table(c + 1, tb[(c + 1) & 1]);
+                const uint32_t* ex = d.kex[u];      // the row's exponent bytes
+                if (blk == 0) {
+                    w = d.kw[u];
+                    transpose_rows(w);              // w[blk] = dword kg of chunk blk: channels 32 blk + 8 kg ..+7
+                    acc_s = 0.f;
+                }
                 uint32_t Ec;
-                float cvt_scale = 512.0f;       // FP8 subnormal m 2^-9 -> the integer m
+                float cvt_scale = 512.0f;           // FP8 subnormal m 2^-9 -> the integer m
                 if (N == 16) {
-                    const uint32_t pair = (ex[blk >> 1] >> (16 * (blk & 1))) & 0xFFFFu;
+                    const uint32_t pair = (ex[N == 16 ? (blk >> 1) : 0] >> (16 * (blk & 1))) & 0xFFFFu;
                     const uint32_t e0 = pair & 0xFFu, e1 = pair >> 8;
                     Ec = max(e0, e1);
-                    const uint32_t d = min(Ec - (kg < 2 ? e0 : e1), 40u);
-                    cvt_scale = __uint_as_float((136u - d) << 23);
+                    const uint32_t dd = min(Ec - (kg < 2 ? e0 : e1), 40u);
+                    cvt_scale = __uint_as_float((136u - dd) << 23);
                 } else if (N == 32) {
                     Ec = (ex[0] >> (8 * blk)) & 0xFFu;
                 } else if (N == 64) {
@@ -325,11 +380,10 @@ __global__ __launch_bounds__(256) void decode_split_rope_p4(DecodeArgs a, int dt
                     Ec = ex[0];
                 }
                 const UnpackedH m = unpack8_f16(w[blk], cvt_scale);
-                const int e16 = ((blk * 4 * 4 + kg) * 4 + u) * 16 + j;
                 f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int kind = 0; kind < 4; ++kind) {      // cos hi, sin hi, cos lo, sin lo
-                    const uint4 t = tab[e16 + kind * kKind];
+                for (int kind = 0; kind < 4; ++kind) {
+                    const uint4 t = tb[c & 1][kind];
                     const f16x8 kt = join_h(m.p[0] * __builtin_bit_cast(f16x2, t.x), m.p[1] * __builtin_bit_cast(f16x2, t.y),
                                             m.p[2] * __builtin_bit_cast(f16x2, t.z), m.p[3] * __builtin_bit_cast(f16x2, t.w));
                     acc = __builtin_amdgcn_mfma_f32_16x16x32_f16((kind & 1) ? A2[blk] : A1[blk], kt, acc, 0, 0, 0);
@@ -337,8 +391,9 @@ __global__ __launch_bounds__(256) void decode_split_rope_p4(DecodeArgs a, int dt
                 // code m of exponent byte E is m 2^(E - 129); the query was divided by 2^qe
                 const int F = min(max((int)Ec + qe[blk] - 2, 0), 254);
                 acc_s = fmaf(acc[0] + acc[1], __uint_as_float((uint32_t)F << 23), acc_s);
+                if (blk == 3) s[u] = (FULL || 16 * u + j < left) ? acc_s : -INFINITY;
+                __builtin_amdgcn_sched_barrier(0);
             }
-            s[u] = (FULL || 16 * u + j < left) ? acc_s : -INFINITY;
         }
 
         // ---------------- online softmax; lane (j, kg) owns head kg, tokens 16u + j
@@ -376,11 +431,7 @@ __global__ __launch_bounds__(256) void decode_split_rope_p4(DecodeArgs a, int dt
         for (int u = 0; u < 4; ++u) {
             UnpackedB vv[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const uint32_t r = FULL ? (uint32_t)(16 * u + 4 * kg + i) : (uint32_t)min(16 * u + 4 * kg + i, left - 1);
-                const uint32_t w = __builtin_nontemporal_load((const uint32_t*)(vp + r * 64u + 4u * (uint32_t)j));
-                vv[i] = unpack8_bf16(w, scale_operand(vep[r * NB + (uint32_t)((8 * j) / N)]));
-            }
+            for (int i = 0; i < 4; ++i) vv[i] = unpack8_bf16(dv.vw[4 * u + i], scale_operand(dv.vex[4 * u + i]));
             uint2 pp = *(const uint2*)&p_s[wave][a_limb][a_head][16 * u + 4 * kg];
             uint32_t ar[4];
             ar[0] = __builtin_amdgcn_perm(pp.x, pp.x, sel_even);
@@ -403,7 +454,7 @@ __global__ __launch_bounds__(256) void decode_split_rope_p4(DecodeArgs a, int dt
         int T0 = wave * kSuper;
         const int step = a.n_splits * kWaves * kSuper;
         for (; T0 + kSuper <= n_tok; T0 += step) tile(T0, std::true_type{});
-        if (T0 < n_tok) tile(T0, std::false_type{});
+        if (T0 < n_tok) tile(T0, std::false_type{});     // at most one ragged tile per wavefront
     }
 
     // ---------------- per-wavefront result to LDS (nobody needs the table any more after the barrier)
@@ -455,12 +506,11 @@ __global__ __launch_bounds__(256) void decode_split_rope_p4(DecodeArgs a, int dt
     }
 }
 
-template <bool PAGED>
 hipError_t launch_rope(const DecodeArgs& a, int dt, int block, dim3 grid, hipStream_t s) {
-    if (block == 16) decode_split_rope_p4<16, PAGED><<<grid, 256, 0, s>>>(a, dt);
-    else if (block == 32) decode_split_rope_p4<32, PAGED><<<grid, 256, 0, s>>>(a, dt);
-    else if (block == 64) decode_split_rope_p4<64, PAGED><<<grid, 256, 0, s>>>(a, dt);
-    else if (block == 128) decode_split_rope_p4<128, PAGED><<<grid, 256, 0, s>>>(a, dt);
+    if (block == 16) decode_split_rope_p4<16><<<grid, 256, 0, s>>>(a, dt);
+    else if (block == 32) decode_split_rope_p4<32><<<grid, 256, 0, s>>>(a, dt);
+    else if (block == 64) decode_split_rope_p4<64><<<grid, 256, 0, s>>>(a, dt);
+    else if (block == 128) decode_split_rope_p4<128><<<grid, 256, 0, s>>>(a, dt);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
@@ -469,11 +519,13 @@ hipError_t launch_rope(const DecodeArgs& a, int dt, int block, dim3 grid, hipStr
 
 namespace kvbfp {
 
-// 4-bit mantissas, 16-bit I/O, a.g_cnt <= 4 heads [a.g_base, a.g_base + a.g_cnt) of every KV head per launch.
+// 4-bit mantissas, 16-bit I/O, contiguous cache, a.g_cnt <= 4 heads [a.g_base, a.g_base + a.g_cnt) of every KV
+// head per launch.
 hipError_t launch_decode_split_rope(const DecodeArgs& a, int dtype, int block, int batch, hipStream_t s) {
-    if (dtype == KVBFP_F32 || a.g_cnt > 4 || !a.rope_theta || !a.rope_partner || !a.rope_sign) return hipErrorInvalidValue;
+    if (dtype == KVBFP_F32 || a.g_cnt > 4 || a.block_table || !a.rope_theta || !a.rope_partner || !a.rope_sign)
+        return hipErrorInvalidValue;
     const dim3 grid((unsigned)a.n_splits, (unsigned)a.H_kv, (unsigned)batch);
-    return a.block_table ? launch_rope<true>(a, dtype, block, grid, s) : launch_rope<false>(a, dtype, block, grid, s);
+    return launch_rope(a, dtype, block, grid, s);
 }
 
 }  // namespace kvbfp

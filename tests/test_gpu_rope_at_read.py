@@ -68,6 +68,47 @@ def test_token_indices_beyond_100k_keep_fp32_accuracy():
     assert_attention_close(got, want, torch.float32)
 
 
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
+def test_token_indices_beyond_100k_with_16_bit_io(dtype):
+    # the matrix-core pass: per-tile phasors stepped in fp32 from a double-precision start over 45 tiles
+    # per wavefront (12 splits), angles up to 1.3e5 radians
+    S = 131072 + 300
+    k, v, q, pk, pv = make_small(dtype, B=1, S=S, Hkv=1, G=4, seed=141)
+    got, want = run_both(k, v, q, 32, 4, [S], 128 ** -0.5, pk, pv, 1)
+    assert_attention_close(got, want, dtype)
+
+
+@pytest.mark.parametrize("n", [16, 32, 128])
+@pytest.mark.parametrize("k_shift,q_shift", [(-100, 0), (100, 0), (0, 90), (0, -90), (-60, -50)])
+def test_rotation_at_read_at_the_ends_of_the_range(n, k_shift, q_shift):
+    # block exponents are applied after the matrix product and the query is normalised per 32 channels:
+    # keys and queries anywhere in the fp32 range, with the softmax scale that brings the logits back
+    dtype = torch.bfloat16
+    B, S, Hkv, G = 2, 600, 2, 4
+    g = synth.outlier_gains(6, 0, Hkv, D)
+    mk = lambda t, sh: (t * 2.0 ** sh).to(dtype)
+    k = mk(synth.kv_rows(B, S, Hkv, D, "f32", g, 6, 2), k_shift)
+    v = synth.kv_rows(B, S, Hkv, D, "bf16", g, 6, 3)
+    q = mk(synth.queries(B, Hkv * G, D, "f32", 6, 4), q_shift)
+    pk = O.calibrate_perm(synth.to_f32_numpy(k[0, :64]))
+    scale = float(np.float32(D ** -0.5) * np.float32(2.0 ** (-(k_shift + q_shift))))
+    got, want = run_both(k, v, q, n, 4, [S, 259], scale, pk, None, 0)
+    assert bool(torch.isfinite(got).all())
+    assert_attention_close(got, want, dtype, "n=%d shifts k %d q %d" % (n, k_shift, q_shift))
+
+
+def test_blocks_of_16_with_very_different_exponents_inside_one_chunk():
+    # every second block of 16 channels 2^30 below its neighbour: the smaller block is scaled down inside
+    # the conversion, and what falls below 2^-24 of the larger block's unit is dropped
+    dtype = torch.bfloat16
+    k, v, q, pk, pv = make_small(dtype, B=1, S=400, Hkv=2, G=4, seed=151)
+    damp = torch.ones(D)
+    damp[torch.arange(D) % 32 >= 16] = 2.0 ** -30
+    k = (k.float() * damp).to(dtype)
+    got, want = run_both(k, v, q, 16, 4, [400], 0.3, None, pv, 1)
+    assert_attention_close(got, want, dtype)
+
+
 def test_profile_variant_returns_the_same_result_and_two_durations():
     k, v, q, pk, pv = make_small(torch.bfloat16, B=2, S=600, Hkv=2, G=4, seed=150)
     (got, split_ms, combine_ms), want = run_both(k, v, q, 16, 4, [600, 1], 0.09, pk, pv, 0, profile=True)
