@@ -573,7 +573,7 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
             return fail(KVBFP_ERR_INVALID_ARG, "append_decode_attention: negative stride");
         // Inside the LDS split pass the cast is done by the one wavefront that reads the new row, off
         // the path of everybody else; elsewhere the cache-write kernel goes first, as in the two calls.
-        const bool in_kernel = fast && dtype != KVBFP_F32 && L->mant_bits == 4;      // the LDS pipeline: every block size
+        const bool in_kernel = fast && dtype != KVBFP_F32;      // the LDS pipeline: every block size, both mantissa widths
         if (in_kernel) {
             a.k_new = k_new; a.v_new = v_new; a.new_stride_b = new_stride_b; a.new_stride_h = new_stride_h;
         } else {

@@ -76,7 +76,8 @@ __host__ __device__ inline int hidden_tokens(const DecodeArgs& a, int s) {
 hipError_t launch_decode_split_mfma(const DecodeArgs& a, int dtype, int block, int batch, hipStream_t s);
 // (a.g_cnt <= 8 heads per launch, 16 where the LDS pipeline applies; larger groups take several launches over
 // head subsets.)
-// The same for 8-bit mantissas (decode_mfma_p8.hip).
+// The same for 8-bit mantissas (decode_mfma_p8.hip: the LDS pipeline for 16-bit I/O, the register-staged pass
+// for fp32 I/O; a.g_cnt <= 8).
 hipError_t launch_decode_split_mfma_p8(const DecodeArgs& a, int dtype, int block, int batch, hipStream_t s);
 // Rotation at read on the matrix cores (decode_rope.hip): 4-bit mantissas, 16-bit I/O, a.g_cnt <= 4.
 hipError_t launch_decode_split_rope(const DecodeArgs& a, int dtype, int block, int batch, hipStream_t s);

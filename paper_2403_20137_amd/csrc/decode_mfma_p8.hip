@@ -25,6 +25,10 @@
 //   with zeros in the other parity's slots.
 // Each wavefront owns every fourth 64-token tile of its split and keeps its own online-softmax
 // state; the four wavefronts of a workgroup merge once at the end.
+//
+// This register-staged kernel serves fp32 I/O (three bf16 limbs for the query and the probabilities).
+// fp16/bf16 I/O goes through the LDS-DMA pipeline of decode_lds.h, instantiated at the end of this file
+// for 8-bit mantissas, where the key pieces enter the scaled FP8 MFMA without any conversion.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -34,6 +38,7 @@
 #include "decode_args.h"
 #include "decode_dev.h"
 #include "kvbfp_internal.h"
+#include "decode_lds.h"
 
 namespace {
 
@@ -379,6 +384,25 @@ hipError_t launch_n(const DecodeArgs& a, int dt, int block, dim3 grid, hipStream
     return hipGetLastError();
 }
 
+// The LDS-DMA pipeline (decode_lds.h) for 8-bit mantissas: 16-bit I/O.  Its staging area is twice that of the 4-bit
+// pipeline (68 KB per workgroup), so two workgroups share a compute unit.
+template <int N, int HG, bool PAGED>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 4)))
+void decode_split_lds_p8(DecodeArgs a, int dt) {
+    kvbfp::lds::decode_split_lds_body<8, N, HG, PAGED>(a, dt);
+}
+
+template <int HG, bool PAGED>
+hipError_t launch_lds(const DecodeArgs& a, int dt, int block, dim3 grid, hipStream_t s) {
+    switch (block) {
+        case 16: decode_split_lds_p8<16, HG, PAGED><<<grid, 256, 0, s>>>(a, dt); break;
+        case 32: decode_split_lds_p8<32, HG, PAGED><<<grid, 256, 0, s>>>(a, dt); break;
+        case 64: decode_split_lds_p8<64, HG, PAGED><<<grid, 256, 0, s>>>(a, dt); break;
+        default: decode_split_lds_p8<128, HG, PAGED><<<grid, 256, 0, s>>>(a, dt); break;
+    }
+    return hipGetLastError();
+}
+
 template <int HG, int PL>
 hipError_t launch_p(const DecodeArgs& a, int dt, int block, dim3 grid, hipStream_t s) {
     return a.block_table ? launch_n<HG, PL, true>(a, dt, block, grid, s) : launch_n<HG, PL, false>(a, dt, block, grid, s);
@@ -392,7 +416,8 @@ hipError_t launch_decode_split_mfma_p8(const DecodeArgs& a, int dtype, int block
     const dim3 grid((unsigned)a.n_splits, (unsigned)a.H_kv, (unsigned)batch);
     // fp32 outputs take three probability limbs (24 bits), 16-bit outputs two
     if (dtype == KVBFP_F32) return a.g_cnt <= 4 ? launch_p<1, 3>(a, dtype, block, grid, s) : launch_p<2, 3>(a, dtype, block, grid, s);
-    return a.g_cnt <= 4 ? launch_p<1, 2>(a, dtype, block, grid, s) : launch_p<2, 2>(a, dtype, block, grid, s);
+    if (a.block_table) return a.g_cnt <= 4 ? launch_lds<1, true>(a, dtype, block, grid, s) : launch_lds<2, true>(a, dtype, block, grid, s);
+    return a.g_cnt <= 4 ? launch_lds<1, false>(a, dtype, block, grid, s) : launch_lds<2, false>(a, dtype, block, grid, s);
 }
 
 }  // namespace kvbfp

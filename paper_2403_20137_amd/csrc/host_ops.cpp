@@ -75,15 +75,13 @@ int check_paging(const kvbfp_layout* pool, const Paging& pg, kvbfp_layout* logic
 SplitPlan plan_splits(const kvbfp_layout* L, int32_t n_q_heads, int64_t max_len) {
     // Enough workgroups to fill 256 compute units with as many as are resident per unit - three, or two
     // of the sixteen-head variant of the LDS pipeline (4-bit mantissas, blocks of 16/32, more than 8 heads
-    // per kv-head) - but no more splits than there are 256-token tiles: the tiles are dealt out
-    // round-robin over the splits.
+    // per kv-head) and of the passes for 8-bit mantissas - but no more splits than there are 256-token
+    // tiles: the tiles are dealt out round-robin over the splits.
     const int64_t units = (int64_t)L->batch * L->n_kv_heads;
     const int64_t tiles = (max_len + kTokenTile - 1) / kTokenTile;
     const bool sixteen = L->mant_bits == 4 && L->block <= 32 && n_q_heads / L->n_kv_heads > 8;
-#ifndef KVBFP_EXP_WGS_PER_CU
-#define KVBFP_EXP_WGS_PER_CU 3
-#endif
-    const int64_t target_wgs = 256 * (sixteen ? 2 : KVBFP_EXP_WGS_PER_CU);
+    const bool two_per_cu = sixteen || L->mant_bits == 8;      // 8-bit mantissas: twice the staging area per workgroup
+    const int64_t target_wgs = 256 * (two_per_cu ? 2 : 3);
     int64_t want = (target_wgs + units - 1) / units;
     if (want > tiles) want = tiles;
     if (want < 1) want = 1;

@@ -108,6 +108,13 @@ def test_cast_inside_the_split_pass_equals_two_calls(n, G, use_perm, qbits):
           units=[(0, 0), (0, 63), (1, 17), (2, 40), (3, 5)])
 
 
+@pytest.mark.parametrize("n,G,use_perm,qbits", [(16, 1, True, 0), (16, 8, False, 0), (32, 4, True, 8), (64, 2, True, 0), (128, 6, True, 0)])
+def test_cast_inside_the_split_pass_8_bit_mantissas(n, G, use_perm, qbits):
+    # the same with 8-bit mantissas (two workgroups per compute unit: 64 x 4 units ask for 2 splits)
+    _case(torch.bfloat16, n, 8, G, [1792, 700, 1300, 0], 1792, use_perm, seed=80 + n + G, qbits=qbits, Hkv=64,
+          units=[(0, 0), (0, 63), (1, 17), (2, 40), (3, 5)])
+
+
 def test_cast_inside_the_split_pass_fp16():
     _case(torch.float16, 32, 4, 1, [1700, 1792, 1537, 1], 1792, True, seed=77, Hkv=64,
           units=[(0, 3), (1, 63), (2, 31), (3, 0), (3, 62)])
