@@ -104,6 +104,13 @@ __device__ __forceinline__ void transpose_rows(u32x4& v) {
     v[0] = c[0]; v[1] = c[1]; v[2] = d[0]; v[3] = d[1];
 }
 
+// f(std::integral_constant<int, 0>{}) ... f(std::integral_constant<int, 3>{})
+template <class F>
+__device__ __forceinline__ void static_for4(F&& f) {
+    f(std::integral_constant<int, 0>{}); f(std::integral_constant<int, 1>{});
+    f(std::integral_constant<int, 2>{}); f(std::integral_constant<int, 3>{});
+}
+
 constexpr int kHeadStride = kD + 4;     // fp32 words per head of the normalised queries: four heads hit different banks
 
 template <int N>
@@ -276,42 +283,54 @@ __global__ __launch_bounds__(256) void decode_split_rope_p4(DecodeArgs a, int dt
         const int left = n_tok - T0;
         KeyRows d;
         fetch(T0, full_tag, d);          // the operand build below covers part of the wait
-        // ---------------- the tile's query operands: row j = 4 * head + limb (two binary16 limbs, rows of limb 2, 3 zero)
+        // ---------------- the tile's query operands: row j = 4 * head + limb, two binary16 limbs (rows of limb 0, 1;
+        // what sits in the rows of limb 2, 3 never reaches a score).  The four lanes of a head and lane group share
+        // the work: lane `limb` builds both limbs of chunk `limb`, and the quad exchanges them -- the rows of
+        // even limbs take the high limb of every chunk, those of odd limbs the low one.
         f16x8 A1[4], A2[4];
         {
             const int gi = j >> 2, limb = j & 3;
-            const uint32_t m_hi = limb == 0 ? 0xFFFFFFFFu : 0u, m_lo = limb == 1 ? 0xFFFFFFFFu : 0u;
+            const int at = limb * 32 + kg * 8;
+            float x[8], y[8], c0[8], s0[8];
 #pragma unroll
-            for (int blk = 0; blk < 4; ++blk) {
-                const int at = blk * 32 + kg * 8;
-                float x[8], y[8], c0[8], s0[8];
+            for (int h = 0; h < 2; ++h) {
+                const float4 xv = *(const float4*)&q1n_s[gi * kHeadStride + at + 4 * h];
+                const float4 yv = *(const float4*)&q2n_s[gi * kHeadStride + at + 4 * h];
+                const float4 cv = *(const float4*)&ph_s[wave][0][at + 4 * h];
+                const float4 sv = *(const float4*)&ph_s[wave][1][at + 4 * h];
+                x[4 * h] = xv.x; x[4 * h + 1] = xv.y; x[4 * h + 2] = xv.z; x[4 * h + 3] = xv.w;
+                y[4 * h] = yv.x; y[4 * h + 1] = yv.y; y[4 * h + 2] = yv.z; y[4 * h + 3] = yv.w;
+                c0[4 * h] = cv.x; c0[4 * h + 1] = cv.y; c0[4 * h + 2] = cv.z; c0[4 * h + 3] = cv.w;
+                s0[4 * h] = sv.x; s0[4 * h + 1] = sv.y; s0[4 * h + 2] = sv.z; s0[4 * h + 3] = sv.w;
+            }
+            uint32_t hi1[4], lo1[4], hi2[4], lo2[4];      // this lane's chunk: A1 and A2, high and low limbs, two slots per register
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const float4 xv = *(const float4*)&q1n_s[gi * kHeadStride + at + 4 * h];
-                    const float4 yv = *(const float4*)&q2n_s[gi * kHeadStride + at + 4 * h];
-                    const float4 cv = *(const float4*)&ph_s[wave][0][at + 4 * h];
-                    const float4 sv = *(const float4*)&ph_s[wave][1][at + 4 * h];
-                    x[4 * h] = xv.x; x[4 * h + 1] = xv.y; x[4 * h + 2] = xv.z; x[4 * h + 3] = xv.w;
-                    y[4 * h] = yv.x; y[4 * h + 1] = yv.y; y[4 * h + 2] = yv.z; y[4 * h + 3] = yv.w;
-                    c0[4 * h] = cv.x; c0[4 * h + 1] = cv.y; c0[4 * h + 2] = cv.z; c0[4 * h + 3] = cv.w;
-                    s0[4 * h] = sv.x; s0[4 * h + 1] = sv.y; s0[4 * h + 2] = sv.z; s0[4 * h + 3] = sv.w;
-                }
+            for (int i = 0; i < 8; i += 2) {
+                const f32x2 a1 = {fmaf(x[i], c0[i], y[i] * s0[i]), fmaf(x[i + 1], c0[i + 1], y[i + 1] * s0[i + 1])};
+                const f32x2 a2 = {fmaf(y[i], c0[i], -(x[i] * s0[i])), fmaf(y[i + 1], c0[i + 1], -(x[i + 1] * s0[i + 1]))};
+                const f16x2 h1 = __builtin_convertvector(a1, f16x2), h2 = __builtin_convertvector(a2, f16x2);
+                hi1[i / 2] = __builtin_bit_cast(uint32_t, h1);
+                hi2[i / 2] = __builtin_bit_cast(uint32_t, h2);
+                lo1[i / 2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(a1 - __builtin_convertvector(h1, f32x2), f16x2));
+                lo2[i / 2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(a2 - __builtin_convertvector(h2, f32x2), f16x2));
+            }
+            const bool odd = (limb & 1) != 0;
+            static_for4([&](auto BLK) {
+                constexpr int blk = decltype(BLK)::value;
+                constexpr int ctrl = blk * 0x55;            // DPP quad_perm [blk, blk, blk, blk]: every lane of a quad reads lane blk
                 uint32_t p1[4], p2[4];
 #pragma unroll
-                for (int i = 0; i < 8; i += 2) {          // two slots per register
-                    const f32x2 a1 = {fmaf(x[i], c0[i], y[i] * s0[i]), fmaf(x[i + 1], c0[i + 1], y[i + 1] * s0[i + 1])};
-                    const f32x2 a2 = {fmaf(y[i], c0[i], -(x[i] * s0[i])), fmaf(y[i + 1], c0[i + 1], -(x[i + 1] * s0[i + 1]))};
-                    const f16x2 h1 = __builtin_convertvector(a1, f16x2), h2 = __builtin_convertvector(a2, f16x2);
-                    const f16x2 l1 = __builtin_convertvector(a1 - __builtin_convertvector(h1, f32x2), f16x2);
-                    const f16x2 l2 = __builtin_convertvector(a2 - __builtin_convertvector(h2, f32x2), f16x2);
-                    // (masks, not selects: no branch around the low limb)
-                    p1[i / 2] = (__builtin_bit_cast(uint32_t, h1) & m_hi) | (__builtin_bit_cast(uint32_t, l1) & m_lo);
-                    p2[i / 2] = (__builtin_bit_cast(uint32_t, h2) & m_hi) | (__builtin_bit_cast(uint32_t, l2) & m_lo);
+                for (int r = 0; r < 4; ++r) {
+                    const uint32_t h1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)hi1[r], ctrl, 0xF, 0xF, false);
+                    const uint32_t l1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)lo1[r], ctrl, 0xF, 0xF, false);
+                    const uint32_t h2 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)hi2[r], ctrl, 0xF, 0xF, false);
+                    const uint32_t l2 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)lo2[r], ctrl, 0xF, 0xF, false);
+                    p1[r] = odd ? l1 : h1;
+                    p2[r] = odd ? l2 : h2;
                 }
                 A1[blk] = __builtin_bit_cast(f16x8, u32x4{p1[0], p1[1], p1[2], p1[3]});
                 A2[blk] = __builtin_bit_cast(f16x8, u32x4{p2[0], p2[1], p2[2], p2[3]});
-                __builtin_amdgcn_sched_barrier(0);      // one chunk's worth of LDS reads in registers at a time
-            }
+            });
             // everybody has read the phasor of this tile: advance it to the wavefront's next tile
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -354,6 +373,15 @@ __global__ __launch_bounds__(256) void decode_split_rope_p4(DecodeArgs a, int dt
             read_table(0, tb[0]);
             u32x4 w = {0u, 0u, 0u, 0u};
             float acc_s = 0.f;
+            // the partial sums of a step are picked up one step later, when its MFMAs have long finished
+            f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+            float post_scale[2] = {0.f, 0.f};
+            auto finish = [&](const int c) {                // step c: scale by the powers of two, add, close a stage
+                const int u = c >> 2, blk = c & 3;
+                if (blk == 0) acc_s = 0.f;
+                acc_s = fmaf(acc[c & 1][0] + acc[c & 1][1], post_scale[c & 1], acc_s);
+                if (blk == 3) s[u] = (FULL || 16 * u + j < left) ? acc_s : -INFINITY;
+            };
 #pragma unroll
             for (int c = 0; c < 16; ++c) {
                 const int u = c >> 2, blk = c & 3;
@@ -362,7 +390,6 @@ __global__ __launch_bounds__(256) void decode_split_rope_p4(DecodeArgs a, int dt
                 if (blk == 0) {
                     w = d.kw[u];
                     transpose_rows(w);              // w[blk] = dword kg of chunk blk: channels 32 blk + 8 kg ..+7
-                    acc_s = 0.f;
                 }
                 uint32_t Ec;
                 float cvt_scale = 512.0f;           // FP8 subnormal m 2^-9 -> the integer m
@@ -380,20 +407,22 @@ __global__ __launch_bounds__(256) void decode_split_rope_p4(DecodeArgs a, int dt
                     Ec = ex[0];
                 }
                 const UnpackedH m = unpack8_f16(w[blk], cvt_scale);
-                f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+                f32x4 a4 = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int kind = 0; kind < 4; ++kind) {
                     const uint4 t = tb[c & 1][kind];
                     const f16x8 kt = join_h(m.p[0] * __builtin_bit_cast(f16x2, t.x), m.p[1] * __builtin_bit_cast(f16x2, t.y),
                                             m.p[2] * __builtin_bit_cast(f16x2, t.z), m.p[3] * __builtin_bit_cast(f16x2, t.w));
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16((kind & 1) ? A2[blk] : A1[blk], kt, acc, 0, 0, 0);
+                    a4 = __builtin_amdgcn_mfma_f32_16x16x32_f16((kind & 1) ? A2[blk] : A1[blk], kt, a4, 0, 0, 0);
                 }
+                acc[c & 1] = a4;
                 // code m of exponent byte E is m 2^(E - 129); the query was divided by 2^qe
                 const int F = min(max((int)Ec + qe[blk] - 2, 0), 254);
-                acc_s = fmaf(acc[0] + acc[1], __uint_as_float((uint32_t)F << 23), acc_s);
-                if (blk == 3) s[u] = (FULL || 16 * u + j < left) ? acc_s : -INFINITY;
+                post_scale[c & 1] = __uint_as_float((uint32_t)F << 23);
+                if (c > 0) finish(c - 1);
                 __builtin_amdgcn_sched_barrier(0);
             }
+            finish(15);
         }
 
         // ---------------- online softmax; lane (j, kg) owns head kg, tokens 16u + j
