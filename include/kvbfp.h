@@ -200,7 +200,10 @@ int kvbfp_decode_attention(const kvbfp_layout* layout, const kvbfp_cache* cache,
  * power of two.  The cast happens inside the kernel; q in memory is not modified.
  *   q_mant_bits : 8 or 4; 0 behaves exactly like kvbfp_decode_attention.
  * All other arguments, the workspace size and the error behaviour are those of
- * kvbfp_decode_attention; a q_mant_bits outside {0, 4, 8} is INVALID_ARG. */
+ * kvbfp_decode_attention; a q_mant_bits outside {0, 4, 8} is INVALID_ARG.
+ * 8-bit mantissas in blocks of 32 or wider with q_mant_bits = 8 and fp16/bf16 I/O: the scores are integer
+ * matrix products of the query's and the keys' codes, one 32-bit sum per 32 channels, scaled once by the sum
+ * of the two block exponents (Sec. II-B); every block's partial score is exact. */
 int kvbfp_decode_attention_qbfp(const kvbfp_layout* layout, const kvbfp_cache* cache,
                                 int32_t n_q_heads, const void* q, kvbfp_dtype dtype,
                                 const int32_t* seq_len_dev, int64_t max_len, float softmax_scale,

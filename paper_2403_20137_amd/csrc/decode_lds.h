@@ -48,6 +48,14 @@ __device__ __forceinline__ Pieces8 unpack4_p8(uint32_t w, float s_hi, float s_lo
     r.l23 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, s_lo, true);
     return r;
 }
+typedef int v4i __attribute__((ext_vector_type(4)));
+// four sign-magnitude bytes -> four two's-complement bytes (a stored code is never "minus zero", so no carry
+// crosses a byte)
+__device__ __forceinline__ int twos_complement4(uint32_t w) {
+    const uint32_t mag = w & 0x7F7F7F7Fu, sgn = (w >> 7) & 0x01010101u;
+    const uint32_t ones = (sgn << 8) - sgn;             // 0xFF in every negative byte
+    return (int)((mag ^ ones) + sgn);
+}
 // channel offset inside a dword of MFMA slot x
 __device__ __forceinline__ int slot_channel(int x) { return (x < 4) ? 2 * x : 2 * (x - 4) + 1; }
 
@@ -117,6 +125,13 @@ __device__ __forceinline__ void lds_issue_4(uint32_t addr, uint32_t (&e)[4]) {
                      : "=&v"(e[0]), "=&v"(e[1]), "=&v"(e[2]), "=&v"(e[3])
                      : "v"(addr), "n"(OFF), "n"(OFF + STRIDE), "n"(OFF + 2 * STRIDE), "n"(OFF + 3 * STRIDE) : "memory");
 }
+// four dword reads, STRIDE apart
+template <int OFF, int STRIDE>
+__device__ __forceinline__ void lds_issue_4w(uint32_t addr, uint32_t (&e)[4]) {
+    asm volatile("ds_read_b32 %0, %4 offset:%5\n\tds_read_b32 %1, %4 offset:%6\n\tds_read_b32 %2, %4 offset:%7\n\tds_read_b32 %3, %4 offset:%8"
+                 : "=&v"(e[0]), "=&v"(e[1]), "=&v"(e[2]), "=&v"(e[3])
+                 : "v"(addr), "n"(OFF), "n"(OFF + STRIDE), "n"(OFF + 2 * STRIDE), "n"(OFF + 3 * STRIDE) : "memory");
+}
 // value mantissas of stage U: dwords at m_addr + 256 * (4U + i), i = 0..3
 template <int U>
 __device__ __forceinline__ void lds_issue_val_mant(uint32_t m_addr, uint64_t& w01, uint64_t& w23) {
@@ -176,9 +191,13 @@ constexpr int vmcnt_imm(int n) { return (n & 0xF) | (0x7 << 4) | (0xF << 8) | ((
 
 // PAGED: the planes are a pool of pages and every 64-token tile looks up its page (a scalar load, issued a
 // tile ahead of the requests that need it); a separate instantiation, so the contiguous case is untouched.
-template <int P, int N, int HG, bool PAGED>
+// QI8 (8-bit mantissas, blocks of 32 and wider, query cast to 8-bit BFP): the score product on the integer
+// datapath of Sec. II-B -- v_mfma_i32_16x16x64_i8 on the signed codes of query and keys, one accumulator per 32
+// channels, and the two block exponents added and applied to the integer sums afterwards.
+template <int P, int N, int HG, bool PAGED, bool QI8 = false>
 __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const int dt) {
     static_assert(P == 4 || P == 8, "mantissa widths of the format");
+    static_assert(!QI8 || (P == 8 && N >= 32), "integer score product: 8-bit codes, one key exponent per 32 channels");
     static_assert(P == 4 || HG <= 2, "8-bit mantissas: one or two groups of four heads");
     // value conversions produce value * 2^-kShift (the stored exponent byte is their scale operand); the
     // probabilities carry the inverse
@@ -448,6 +467,11 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
     // issued twice, once with the query's odd blocks of 16 zeroed and once with the even ones (a block of 16 of the
     // FP8 operand lies in one lane group: even blocks in even groups)
     v8i aq8e[(P == 8 && N == 16) ? HG : 1], aq8o[(P == 8 && N == 16) ? HG : 1];
+    // QI8: the query's signed 8-bit codes, row 4*head (the other rows zero), channels 64m + 16kg ..+15 for the
+    // MFMA m of a stage, once with the lane groups of the upper 32 channels zeroed and once with the lower ones;
+    // qei = the power of two of each 32-channel group of this lane's head, minus the 6 of the keys' code scale
+    v4i aqi[QI8 ? HG : 1][2][2];
+    int qei[QI8 ? HG : 1][4];
     {
         // Each block of 32 query values shares a power-of-two scale 2^sh chosen so that the largest lands in
         // [128, 256); limb l holds the FP8 rounding of the residual at scale 2^(sh - 4l), so four limbs carry 16
@@ -475,6 +499,39 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
         uint8_t* q8 = (uint8_t*)(qr + NH * kD);           // [NH * 4 limb rows][kD positions], beside the fp32 values
         uint8_t* qsc = qsc_lds;
         const int kb = qchan >> 5;
+        if constexpr (QI8) {
+            // the cast query (cache order, unscaled) is code * 2^e per block; per 32 channels the codes are taken
+            // relative to that group's own largest magnitude, which keeps them integers of at most 7 bits
+            int* const qexp = (int*)qsc_lds;              // [NH][4]
+            const int c = tid & (kD - 1);
+#pragma unroll
+            for (int k = 0; k < kQPerThread; ++k) {
+                const int g = (tid + 256 * k) / kD;
+                const float v = qr[g * kD + c];
+                float mx = row_max(fabsf(v));
+                mx = fmaxf(mx, __shfl_xor(mx, 16));
+                int e = 0;
+                if (mx > 0.f) (void)frexpf(mx, &e);        // mx = f * 2^e, f in [0.5, 1): codes below 2^7 at scale 2^(e - 7)
+                e -= 7;
+                q8[g * kD + c] = (uint8_t)(int8_t)(int)ldexpf(v, -e);
+                if ((c & 31) == 0) qexp[g * 4 + (c >> 5)] = mx > 0.f ? e : 0;
+            }
+            lds_barrier();
+#pragma unroll
+            for (int hg = 0; hg < HG; ++hg) {
+                const bool carries = (j & 3) == 0;        // row 4*head: the codes; rows of the other limbs: zero
+#pragma unroll
+                for (int m = 0; m < 2; ++m) {
+                    const u32x4 cw = *(const u32x4*)(q8 + (hg * 4 + (j >> 2)) * kD + 64 * m + 16 * kg);
+                    const v4i codes = carries ? v4i{(int)cw[0], (int)cw[1], (int)cw[2], (int)cw[3]} : v4i{0, 0, 0, 0};
+                    aqi[hg][m][0] = kg < 2 ? codes : v4i{0, 0, 0, 0};
+                    aqi[hg][m][1] = kg < 2 ? v4i{0, 0, 0, 0} : codes;
+                }
+#pragma unroll
+                for (int grp = 0; grp < 4; ++grp) qei[hg][grp] = qexp[(hg * 4 + kg) * 4 + grp] - 6;
+            }
+            lds_barrier();                                // the buffer goes over to the probabilities
+        } else {
 #pragma unroll
         for (int k = 0; k < kQPerThread; ++k) {
             const int g = (tid + 256 * k) / kD;
@@ -510,6 +567,7 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
             }
         }
         lds_barrier();                                    // the buffer goes over to the probabilities
+        }
     }
     if (appends && !appends_first) {
         float* const row = (float*)&p_lds[wave][0] + nr_which * kD;     // [2][kD] floats: this wavefront's 1 KB
@@ -544,7 +602,8 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
     // ---- LDS read offsets of this lane inside a stage --------------------------------------------
     const uint32_t kq = lds_addr(wbase + kKm + (4 * j + (kg ^ ((j >> 2) & 3))) * 16);       // row j, chunk kg
     // own exponent byte(s): the block of channels 32 kg .. 32 kg + 31 (two blocks of 16: a 16-bit read)
-    const uint32_t keq = lds_addr(wbase + kKe + j * kExpRow + (N == 16 ? 2 * kg : (32 * kg) / N));   // + 16 kExpRow per stage
+    // (QI8: all exponent bytes of token j, the lane scales the sums of every 32-channel group itself)
+    const uint32_t keq = lds_addr(wbase + kKe + j * kExpRow + (QI8 ? 0 : (N == 16 ? 2 * kg : (32 * kg) / N)));   // + 16 kExpRow per stage
     const uint32_t vq = lds_addr(wbase + kVm + kg * 64 + j * 4);                           // + i*256: row 4kg+i sits at position 4i+kg
     // 8-bit mantissas: chunks kg and 4 + kg of row j (slots swizzled with row/2 % 8); bytes 8j..8j+7 of position 4i + kg
     const int k8_slot = kg ^ ((j >> 1) & 7);
@@ -592,7 +651,8 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
             } else {
                 lds_issue_b128<0>(kq, rawk[0]);
             }
-            lds_issue_4<0, 16 * kExpRow, N == 16>(keq, kexp);
+            if constexpr (QI8 && N == 32) lds_issue_4w<0, 16 * kExpRow>(keq, kexp);
+            else lds_issue_4<0, 16 * kExpRow, N == 16 || (QI8 && N == 64)>(keq, kexp);
         };
         // wait for the DMA of a stage and issue its LDS reads (`more`: the next tile is being requested meanwhile)
         auto start_k = [&](auto U, const bool more) {             // key stage U >= 1
@@ -669,7 +729,29 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
                 const u32x4 raw = rawk[cur];
 #pragma unroll
                 for (int hg = 0; hg < HG; ++hg) s_acc[hg][u] = f32x4{0.f, 0.f, 0.f, 0.f};
-                if constexpr (P == 8) {
+                if constexpr (QI8) {
+                    // integer datapath (Sec. II-B): signed codes x signed codes into i32, one accumulator per 32
+                    // channels (the lane groups of the other 32 channels of a 64-wide product are zero in the query
+                    // operand), then one exponent addition and one scaling per group
+                    v4i kb2[2];
+#pragma unroll
+                    for (int m = 0; m < 2; ++m)
+                        kb2[m] = v4i{twos_complement4(rawk8[cur][m][0]), twos_complement4(rawk8[cur][m][1]),
+                                     twos_complement4(rawk8[cur][m][2]), twos_complement4(rawk8[cur][m][3])};
+#pragma unroll
+                    for (int hg = 0; hg < HG; ++hg) {
+                        float sc = 0.f;
+#pragma unroll
+                        for (int grp = 0; grp < 4; ++grp) {
+                            const v4i sum = __builtin_amdgcn_mfma_i32_16x16x64_i8(aqi[hg][grp >> 1][grp & 1], kb2[grp >> 1],
+                                                                                   v4i{0, 0, 0, 0}, 0, 0, 0);
+                            const int Ek = (int)((kexp[u] >> (N == 32 ? 8 * grp : (N == 64 ? 8 * (grp >> 1) : 0))) & 0xFFu);
+                            const int field = min(max(Ek + qei[hg][grp], 0), 254);     // key code scale 2^(Ek - 133), query 2^(qei + 6)
+                            sc = fmaf((float)sum[0], __uint_as_float((uint32_t)field << 23), sc);
+                        }
+                        s_acc[hg][u] = f32x4{sc * a.scale_log2e, 0.f, 0.f, 0.f};
+                    }
+                } else if constexpr (P == 8) {
                     // the two FP8 pieces of every byte are the B operands as they are (no conversion): magnitude =
                     // 8 hi + lo, so the high piece takes the block's exponent byte + 3 as its E8M0 scale
                     v8i bh, bl;

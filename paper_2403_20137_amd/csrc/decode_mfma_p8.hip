@@ -392,6 +392,24 @@ void decode_split_lds_p8(DecodeArgs a, int dt) {
     kvbfp::lds::decode_split_lds_body<8, N, HG, PAGED>(a, dt);
 }
 
+// The same with the query cast to 8-bit BFP and blocks of 32 and wider: the score product on the integer datapath
+// (v_mfma_i32_16x16x64_i8 on the codes, block exponents added afterwards; Sec. II-B).
+template <int N, int HG, bool PAGED>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 4)))
+void decode_split_lds_p8_qi8(DecodeArgs a, int dt) {
+    kvbfp::lds::decode_split_lds_body<8, N, HG, PAGED, true>(a, dt);
+}
+
+template <int HG, bool PAGED>
+hipError_t launch_lds_qi8(const DecodeArgs& a, int dt, int block, dim3 grid, hipStream_t s) {
+    switch (block) {
+        case 32: decode_split_lds_p8_qi8<32, HG, PAGED><<<grid, 256, 0, s>>>(a, dt); break;
+        case 64: decode_split_lds_p8_qi8<64, HG, PAGED><<<grid, 256, 0, s>>>(a, dt); break;
+        default: decode_split_lds_p8_qi8<128, HG, PAGED><<<grid, 256, 0, s>>>(a, dt); break;
+    }
+    return hipGetLastError();
+}
+
 template <int HG, bool PAGED>
 hipError_t launch_lds(const DecodeArgs& a, int dt, int block, dim3 grid, hipStream_t s) {
     switch (block) {
@@ -416,6 +434,10 @@ hipError_t launch_decode_split_mfma_p8(const DecodeArgs& a, int dtype, int block
     const dim3 grid((unsigned)a.n_splits, (unsigned)a.H_kv, (unsigned)batch);
     // fp32 outputs take three probability limbs (24 bits), 16-bit outputs two
     if (dtype == KVBFP_F32) return a.g_cnt <= 4 ? launch_p<1, 3>(a, dtype, block, grid, s) : launch_p<2, 3>(a, dtype, block, grid, s);
+    if (a.q_mant_bits == 8 && block >= 32) {      // 8-bit query codes x 8-bit key codes: integer matrix product
+        if (a.block_table) return a.g_cnt <= 4 ? launch_lds_qi8<1, true>(a, dtype, block, grid, s) : launch_lds_qi8<2, true>(a, dtype, block, grid, s);
+        return a.g_cnt <= 4 ? launch_lds_qi8<1, false>(a, dtype, block, grid, s) : launch_lds_qi8<2, false>(a, dtype, block, grid, s);
+    }
     if (a.block_table) return a.g_cnt <= 4 ? launch_lds<1, true>(a, dtype, block, grid, s) : launch_lds<2, true>(a, dtype, block, grid, s);
     return a.g_cnt <= 4 ? launch_lds<1, false>(a, dtype, block, grid, s) : launch_lds<2, false>(a, dtype, block, grid, s);
 }

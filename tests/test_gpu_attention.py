@@ -222,3 +222,26 @@ def test_split_partials_before_the_output_rounding(n, G):
     err = np.linalg.norm(merged - want, axis=-1) / np.linalg.norm(want, axis=-1)
     print("block %d, %d heads per kv-head: worst rel-L2 of the fp32 partials %.2e" % (n, G, err.max()))
     assert err.max() <= 1e-4, err
+
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
+@pytest.mark.parametrize("n", [32, 64, 128])
+@pytest.mark.parametrize("G", [1, 4, 6])
+def test_integer_score_product_of_8_bit_codes(dtype, n, G):
+    # 8-bit keys and an 8-bit BFP query, blocks of 32 and wider: the scores are integer matrix products of the
+    # codes with the two block exponents added afterwards (Sec. II-B), in the LDS pipeline
+    k, v, q, pk, pv = make_small(dtype, B=2, S=700, Hkv=2, G=G, seed=40 + G + n)
+    got, want = run_both(k, v, q, n, 8, [700, 259], 128 ** -0.5, pk, pv, S_max=720, q_mant_bits=8)
+    assert_attention_close(got, want, dtype, "integer scores n=%d G=%d" % (n, G))
+
+
+def test_integer_score_product_at_the_ends_of_the_range():
+    # queries and keys far from 1: the exponent sum of a group is formed in integers and applied once
+    dtype = torch.bfloat16
+    for k_shift, q_shift in ((-100, 60), (90, -100), (-60, -50)):
+        k, v, q, pk, pv = make_small(dtype, B=1, S=400, Hkv=2, G=4, seed=47)
+        k = (k.float() * 2.0 ** k_shift).to(dtype)
+        q = (q.float() * 2.0 ** q_shift).to(dtype)
+        scale = float(np.float32(128 ** -0.5) * np.float32(2.0 ** (-(k_shift + q_shift))))
+        got, want = run_both(k, v, q, 32, 8, [400], scale, pk, pv, q_mant_bits=8)
+        assert_attention_close(got, want, dtype, "integer scores, shifts %d %d" % (k_shift, q_shift))
