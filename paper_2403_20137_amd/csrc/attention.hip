@@ -341,20 +341,23 @@ __device__ __forceinline__ uint16_t narrow_bf16(float v) {
     return (uint16_t)(u >> 16);
 }
 
-// Pass 2: merge the splits of one (batch, query head).  grid = (H_q, B), block = 512: four slices of
-// the splits times 128 channels.  A round trip to memory costs far more than anything computed here,
-// so every thread first puts up to 8 or 32 partial-output loads in flight (enough for 32 or 128
-// splits in one go), then the (m, l) pairs go through LDS, and the four slices are added through LDS at the end.
-constexpr int kCombineSlices = 4;
-// kCombineBatch: loads in flight per thread, 8 (up to 32 splits without a second round) or 32.
-template <int kCombineBatch>
-__global__ __launch_bounds__(kD * kCombineSlices) void decode_combine(DecodeArgs a, int dt) {
+// Pass 2: merge the splits of one (batch, query head).  block = 512 threads: kChan channels times 512 / kChan
+// slices of the splits; grid = (H_q, B, 128 / kChan).  A round trip to memory costs far more than anything computed
+// here, so every thread first puts kCombineBatch partial-output loads in flight (enough for all splits in one go
+// up to kCombineBatch * slices of them), then the (m, l) pairs go through LDS, and the slices are added through LDS
+// at the end.  Few (batch, head) pairs with many splits -- one long sequence -- take the 32-channel form: four
+// times the workgroups, a quarter of the bytes through each compute unit.
+constexpr int kCombineThreads = 512;
+template <int kCombineBatch, int kChan>
+__global__ __launch_bounds__(kCombineThreads) void decode_combine(DecodeArgs a, int dt) {
+    constexpr int kSlices = kCombineThreads / kChan;
     constexpr int kMaxLds = 1024;
     __shared__ float m_s[kMaxLds];
     __shared__ float l_s[kMaxLds];
-    __shared__ float red[kCombineSlices][2][kD];
-    __shared__ float red_m[kCombineSlices];
-    const int j = threadIdx.x % kD, sl = threadIdx.x / kD;
+    __shared__ float red[kSlices][2][kChan];
+    __shared__ float red_m[kSlices];
+    const int jl = threadIdx.x % kChan, sl = threadIdx.x / kChan;
+    const int j = blockIdx.z * kChan + jl;      // channel (cache order)
     const int h = blockIdx.x, b = blockIdx.y;
     const int64_t bh = (int64_t)b * a.H_q + h;
     const float* ml = a.part_ml + bh * a.n_splits * 2;
@@ -362,14 +365,14 @@ __global__ __launch_bounds__(kD * kCombineSlices) void decode_combine(DecodeArgs
     const int n = a.n_splits;
     const bool staged = n <= kMaxLds;           // otherwise (m, l) are read from global memory each time
 
-    float v[kCombineBatch];                     // first batch of this thread's partial outputs: splits sl + 4k
+    float v[kCombineBatch];                     // first batch of this thread's partial outputs: splits sl + kSlices k
 #pragma unroll
     for (int k = 0; k < kCombineBatch; ++k) {
-        const int i = sl + k * kCombineSlices;
+        const int i = sl + k * kSlices;
         v[k] = i < n ? po[(int64_t)i * kD + j] : 0.f;
     }
     if (staged) {
-        for (int i = threadIdx.x; i < n; i += kD * kCombineSlices) {
+        for (int i = threadIdx.x; i < n; i += kCombineThreads) {
             const float2 t = *(const float2*)(ml + 2 * i);
             m_s[i] = t.x;
             l_s[i] = t.y;
@@ -384,44 +387,44 @@ __global__ __launch_bounds__(kD * kCombineSlices) void decode_combine(DecodeArgs
     float Ms = -INFINITY;
 #pragma unroll
     for (int k = 0; k < kCombineBatch; ++k) {
-        const int i = sl + k * kCombineSlices;
+        const int i = sl + k * kSlices;
         mk[k] = i < n ? m_of(i) : -INFINITY;
         Ms = fmaxf(Ms, mk[k]);
     }
-    for (int i = sl + kCombineBatch * kCombineSlices; i < n; i += kCombineSlices) Ms = fmaxf(Ms, m_of(i));
+    for (int i = sl + kCombineBatch * kSlices; i < n; i += kSlices) Ms = fmaxf(Ms, m_of(i));
     float num = 0.f, den = 0.f;
     if (Ms > -INFINITY) {                       // empty splits carry m = -inf -> weight 0
 #pragma unroll
         for (int k = 0; k < kCombineBatch; ++k) {
-            const int i = sl + k * kCombineSlices;
+            const int i = sl + k * kSlices;
             if (i < n) {
                 const float w = exp2f(mk[k] - Ms);
                 num = fmaf(w, v[k], num);
                 den = fmaf(w, l_of(i), den);
             }
         }
-        for (int i = sl + kCombineBatch * kCombineSlices; i < n; i += kCombineSlices) {
+        for (int i = sl + kCombineBatch * kSlices; i < n; i += kSlices) {
             const float w = exp2f(m_of(i) - Ms);
             num = fmaf(w, po[(int64_t)i * kD + j], num);
             den = fmaf(w, l_of(i), den);
         }
     }
-    red[sl][0][j] = num;
-    red[sl][1][j] = den;
-    if (j == 0) red_m[sl] = Ms;
+    red[sl][0][jl] = num;
+    red[sl][1][jl] = den;
+    if (jl == 0) red_m[sl] = Ms;
     __syncthreads();
     if (sl != 0) return;
     float M = -INFINITY;
 #pragma unroll
-    for (int k = 0; k < kCombineSlices; ++k) M = fmaxf(M, red_m[k]);
+    for (int k = 0; k < kSlices; ++k) M = fmaxf(M, red_m[k]);
     num = 0.f;
     den = 0.f;
     if (M > -INFINITY) {
 #pragma unroll
-        for (int k = 0; k < kCombineSlices; ++k) {
+        for (int k = 0; k < kSlices; ++k) {
             const float w = exp2f(red_m[k] - M);        // 0 for a slice without cached tokens
-            num = fmaf(w, red[k][0][j], num);
-            den = fmaf(w, red[k][1][j], den);
+            num = fmaf(w, red[k][0][jl], num);
+            den = fmaf(w, red[k][1][jl], den);
         }
     }
     const float r = den > 0.f ? num / den : 0.f;
@@ -635,9 +638,15 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
     }
     if (kernel_ms) (void)hipEventRecord(ev[1], s);
     for (int r = 0; r < reps && err == hipSuccess; ++r) {
-        const dim3 grid2((unsigned)n_q_heads, (unsigned)L->batch, 1);
-        if (sp.n_splits <= 8 * kCombineSlices) decode_combine<8><<<grid2, kD * kCombineSlices, 0, s>>>(a, (int)dtype);
-        else decode_combine<32><<<grid2, kD * kCombineSlices, 0, s>>>(a, (int)dtype);
+        // few (batch, head) pairs with many splits: 32 channels per workgroup (16 slices x 8 loads cover 128 splits)
+        if (sp.n_splits > 32 && (int64_t)n_q_heads * L->batch < 256) {
+            const dim3 grid2((unsigned)n_q_heads, (unsigned)L->batch, kD / 32);
+            decode_combine<8, 32><<<grid2, kCombineThreads, 0, s>>>(a, (int)dtype);
+        } else {
+            const dim3 grid2((unsigned)n_q_heads, (unsigned)L->batch, 1);
+            if (sp.n_splits <= 32) decode_combine<8, kD><<<grid2, kCombineThreads, 0, s>>>(a, (int)dtype);
+            else decode_combine<32, kD><<<grid2, kCombineThreads, 0, s>>>(a, (int)dtype);
+        }
         err = hipGetLastError();
     }
     if (kernel_ms) {
