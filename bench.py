@@ -488,11 +488,12 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(ring)
     if not args.no_extra:
-        # the other workloads of the contract, decode attention only (the timed region of `value` is the headline's)
+        # the other workloads of the contract and the headline shapes at the other block sizes and at 8 bits, decode
+        # attention only (the timed region of `value` is the headline's)
         del ring
         torch.cuda.empty_cache()
         result["workloads"] = {}
-        for name in ("llama2_7b_4k", "batched_8k_p4", "batched_8k_p8", "long_128k"):
+        for name in ("llama2_7b_4k", "batched_8k_p4", "batched_8k_p8", "long_128k", "gqa_32k_n64", "gqa_32k_n128", "gqa_32k_p8n16"):
             if name == w.name:
                 continue
             try:
