@@ -478,6 +478,23 @@ def main():
                                                    workspace=ring.workspace, profile=True)[1] * 1e3 for i in range(8)]
             return float(np.median(rope_us[2:]))
 
+        def general_pass_vector_alu():
+            # the same cache through the general split pass (fp32 multiply-adds on the vector ALUs, no matrix cores):
+            # what the matrix-core passes are measured against.  Reached the way a caller reaches it: exponent planes
+            # that are not 16-byte aligned.
+            c0 = ring.caches[0]
+            moved = []
+            for t in (c0.k_exp, c0.v_exp):
+                buf = torch.zeros((t.numel() + 64,), dtype=torch.uint8, device=t.device)
+                view = buf[1:1 + t.numel()].view(t.shape)
+                view.copy_(t)
+                moved.append(view)
+            odd = kvbfp.Cache(c0.layout, c0.k_mant, moved[0], c0.v_mant, moved[1])
+            us = [kvbfp.decode_attention_profile(odd, ring.q, ring.S_max, ring.scale, perm_k=ring.perm_k, perm_v=ring.perm_v,
+                                                 out=ring.out, workspace=ring.workspace)[1] * 1e3 for _ in range(6)]
+            return float(np.median(us[2:]))
+
+        extra("decode_split_us_median_general_pass_vector_alu", general_pass_vector_alu)
         extra("decode_split_us_median_query_bfp8", query_bfp8)
         extra("decode_us_median_single_cache_llc_assisted", single_cache_hot)
         extra("decode_4_query_tokens_us_median", four_query_tokens)
