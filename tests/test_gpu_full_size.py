@@ -17,7 +17,12 @@ SAMPLES = {  # workload -> sampled (batch, kv-head) units
     "batched_8k_p8": [(3, 5), (15, 30)],
     "llama3_8b_gqa_32k": [(0, 0), (5, 3), (7, 7)],
     "long_128k": [(0, 2), (0, 7)],
+    "gqa_32k_n64": [(1, 2), (7, 6)],         # the headline shapes at Table I's other block sizes and at 8 bits
+    "gqa_32k_n128": [(2, 1), (6, 7)],
+    "gqa_32k_p8n16": [(0, 4), (5, 0)],
+    "gqa_32k_p8n32": [(3, 3), (4, 6)],       # with the query cast to 8-bit BFP: the integer score product
 }
+Q_MANT_BITS = {"gqa_32k_p8n32": 8}
 
 
 @pytest.mark.parametrize("name", list(SAMPLES))
@@ -37,7 +42,11 @@ def test_full_size_sampled_units(name):
     pos = torch.full((w.batch,), w.seq, dtype=torch.int32, device="cuda")
     kvbfp.quantize_append(cache, k1, v1, pos_dev=pos, perm_k=pkd, perm_v=pvd)             # one decode-step append
     scale = float(np.float32(w.head_dim ** -0.5))
-    out = kvbfp.decode_attention(cache, d["q"], w.seq + 1, scale, perm_k=pkd, perm_v=pvd)
+    qbits = Q_MANT_BITS.get(name, 0)
+    if qbits:
+        out = kvbfp.decode_attention_qbfp(cache, d["q"], w.seq + 1, scale, qbits, perm_k=pkd, perm_v=pvd)
+    else:
+        out = kvbfp.decode_attention(cache, d["q"], w.seq + 1, scale, perm_k=pkd, perm_v=pvd)
     torch.cuda.synchronize()
     G = w.group
     worst = 0.0
@@ -51,7 +60,7 @@ def test_full_size_sampled_units(name):
             assert np.array_equal(got[b, h].cpu().numpy(), ref[0, 0]), (name, b, h, nm)
         qq = synth.to_f32_numpy(d["q"][b:b + 1, h * G:(h + 1) * G])
         want = O.decode_attention(km, ke, vm, ve, w.head_dim, w.block, w.mant_bits, qq, [w.seq + 1], scale,
-                                  pk[h:h + 1], pv[h:h + 1])
+                                  pk[h:h + 1], pv[h:h + 1], q_mant_bits=qbits)
         per_head, _ = assert_attention_close(out[b:b + 1, h * G:(h + 1) * G], want, tdt, "%s unit (%d,%d)" % (name, b, h))
         worst = max(worst, per_head)
     print("%s: worst rel-L2 over sampled units %.3e" % (name, worst))

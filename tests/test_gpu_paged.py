@@ -127,6 +127,19 @@ def test_query_cast_and_profile_variant_on_pages():
     assert split_ms > 0 and combine_ms > 0
 
 
+def test_integer_score_product_on_pages():
+    # 8-bit keys in blocks of 32, query cast to 8-bit BFP: the int8 matrix product of the LDS pipeline over a pool
+    lens = [700, 300]
+    k, v, q, pk, pv = make_small(torch.bfloat16, B=2, S=700, Hkv=2, G=6, seed=185)
+    pool, table, planes = fill_both(k, v, 32, 8, 128, 6, lens, pk, pv, seed=11)
+    want = O.decode_attention(*planes, D, 32, 8, synth.to_f32_numpy(q), lens, float(np.float32(0.09)), pk, pv,
+                              q_mant_bits=8)
+    got = kvbfp.decode_attention_paged(pool, table, q.cuda(), 700, float(np.float32(0.09)), q_mant_bits=8,
+                                       seq_len_dev=dev_i32(lens), perm_k=dev_i32(pk), perm_v=dev_i32(pv))
+    torch.cuda.synchronize()
+    assert_attention_close(got, want, torch.bfloat16)
+
+
 def test_dequantize_from_pages_equals_the_oracle():
     lens = [500, 321]
     k, v, q, pk, pv = make_small(torch.bfloat16, B=2, S=500, Hkv=2, G=1, seed=190)
