@@ -306,6 +306,21 @@ def workload_entry(name, steps, batches=5):
     torch.cuda.synchronize()
     call = np.array([a.elapsed_time(b) for a, b in ev])[2:] * 1e3
     stream = np.array([ring.stream_read_us(i) for i in range(10)])[2:]
+    # the same call captured 64 times (cycling over the ring) into one graph, as a model's per-token graph would hold it
+    n_graph = max(n_layers, 64)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=torch.cuda.Stream()):
+        for i in range(n_graph):
+            ring.decode(i)
+    torch.cuda.synchronize()
+    in_graph = []
+    for _ in range(4):
+        t0 = time.perf_counter()
+        g.replay()
+        torch.cuda.synchronize()
+        in_graph.append((time.perf_counter() - t0) / n_graph * 1e6)
+    in_graph_us = float(np.median(in_graph[1:]))
+    del g
     counters = profile_counters().get(name, {})
     entry = {"algorithmic_bytes": dec_bytes, "layer_caches_in_ring": n_layers,
              "split_pass_us_avg": float(split.mean()), "split_pass_us_min": float(split.min()),
@@ -315,6 +330,8 @@ def workload_entry(name, steps, batches=5):
              "whole_call_us_median": float(np.median(call)), "whole_call_us_min": float(call.min()),
              "whole_call_gb_s": dec_bytes / float(np.median(call)) / 1e3,
              "whole_call_frac_of_hbm_peak": dec_bytes / float(np.median(call)) / 1e3 / HBM_PEAK_GBS,
+             "whole_call_us_in_graph": in_graph_us, "whole_call_in_graph_calls": n_graph,
+             "whole_call_in_graph_frac_of_hbm_peak": dec_bytes / in_graph_us / 1e3 / HBM_PEAK_GBS,
              "stream_read_us_median": float(np.median(stream)),
              "stream_read_gb_s": dec_bytes / float(np.median(stream)) / 1e3,
              "valu_busy_from_profile": counters.get("valu_busy"), "hbm_traffic_bytes_from_profile": counters.get("traffic")}
