@@ -120,7 +120,7 @@ class LayerRing:
 
 
 def paged_split_us(ring: LayerRing, page=256, n_pools=4):
-    """The workload's caches again as pools of 256-token pages, every sequence's pages scattered over its
+    """The workload's caches again as pools of pages of `page` tokens, every sequence's pages scattered over its
     pool by a seeded shuffle; split pass of kvbfp_decode_attention_paged, HIP events inside the call,
     cycling over pools that together exceed the last-level cache."""
     w = ring.w
@@ -537,6 +537,7 @@ def main():
         extra("decode_4_query_tokens_us_median", four_query_tokens)
         extra("decode_split_us_median_rotary_at_read", rotary_at_read)
         extra("decode_split_us_median_paged_256", lambda: paged_split_us(ring))
+        extra("decode_split_us_median_paged_16", lambda: paged_split_us(ring, page=16))
         extra("quantize_append_bulk", bulk_quantize_rate)
     result["device"] = device_info()
     if not args.no_cpu_baseline:

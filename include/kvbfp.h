@@ -302,7 +302,7 @@ int kvbfp_decode_attention_rope(const kvbfp_layout* layout, const kvbfp_cache* c
 
 /* Paged caches.  The four planes form a POOL of pages instead of one region per sequence:
  *   pool layout : batch = number of pages in the pool, max_seq = tokens per page (a power of two, at
- *                 least 64: the 64 tokens a wavefront handles at a time never straddle two pages); planes
+ *                 least 16: the decode kernels look a page up per 16 tokens); planes
  *                 [n_pages][n_kv_heads][page_tokens][..] as kvbfp_cache_bytes(pool) sizes them.
  *   block_table : DEVICE int32 [batch][table_stride]; tokens [i * page_tokens, (i + 1) * page_tokens) of
  *                 sequence b live in page block_table[b * table_stride + i].  Entries that no token of the
@@ -316,7 +316,7 @@ int kvbfp_decode_attention_rope(const kvbfp_layout* layout, const kvbfp_cache* c
  * kvbfp_dequantize_paged returns out [batch][n_tok][n_kv_heads][head_dim] as kvbfp_dequantize does.
  * kvbfp_decode_attention_paged takes q_mant_bits like kvbfp_decode_attention_qbfp (0 = query as given)
  * and kernel_ms like kvbfp_decode_attention_rope (NULL = asynchronous).
- * Errors: as the plain calls, plus UNSUPPORTED for a page size that is not a power of two >= 64. */
+ * Errors: as the plain calls, plus UNSUPPORTED for a page size that is not a power of two >= 16. */
 int kvbfp_quantize_append_paged(const kvbfp_layout* pool, const kvbfp_cache* cache, const int32_t* block_table,
                                 int64_t table_stride, int32_t batch, const void* k_new, const void* v_new,
                                 kvbfp_dtype dtype, int32_t n_new, int64_t stride_b, int64_t stride_t,

@@ -188,10 +188,12 @@ __global__ __launch_bounds__(kTile) void decode_split_generic(DecodeArgs a, int 
             }
             __syncthreads();
         }
-        // rows of the planes are addressed as base + token; a paged cache has one base per 64 tokens, the
-        // share of a wavefront in both phases below (pages hold a multiple of 64 tokens)
+        // rows of the planes are addressed as base + token; a paged cache with pages of 64 tokens or more has one
+        // base per 64 tokens, the share of a wavefront in both phases below; with smaller pages every token looks
+        // up its own row
         const int64_t tw = tile0 + wave * 64;
-        const int64_t base = tw < t_end ? kvbfp::cache_row(a, b, kvh, tw) - tw : 0;
+        const bool per_token = a.block_table != nullptr && a.log2_page < 6;
+        const int64_t base = (tw < t_end && !per_token) ? kvbfp::cache_row(a, b, kvh, tw) - tw : 0;
         // ---- scores: one cached token per thread
         const int64_t t = tile0 + tid;
         float s[kHeadsPerWg];
@@ -199,10 +201,11 @@ __global__ __launch_bounds__(kTile) void decode_split_generic(DecodeArgs a, int 
         for (int g = 0; g < kHeadsPerWg; ++g) s[g] = -INFINITY;
         if (t < t_end) {
             uint4 raw[kRowVec];
-            const uint4* rp = (const uint4*)(a.k_mant + (base + t) * kRowBytes);
+            const int64_t krow = per_token ? kvbfp::cache_row(a, b, kvh, t) : base + t;
+            const uint4* rp = (const uint4*)(a.k_mant + krow * kRowBytes);
 #pragma unroll
             for (int i = 0; i < kRowVec; ++i) raw[i] = rp[i];
-            const uint8_t* ep = a.k_exp + (base + t) * nb;
+            const uint8_t* ep = a.k_exp + krow * nb;
 #pragma unroll
             for (int g = 0; g < kHeadsPerWg; ++g) s[g] = 0.f;
 #pragma unroll
@@ -294,15 +297,16 @@ __global__ __launch_bounds__(kTile) void decode_split_generic(DecodeArgs a, int 
         const int cnt = (int)max((int64_t)0, min((int64_t)64, t_end - tw0));
         for (int k = 0; k < cnt; ++k) {
             const int64_t tt = tw0 + k;
-            const int E = a.v_exp[(base + tt) * nb + ((2 * cp) >> a.log2_block)];
+            const int64_t vrow = per_token ? kvbfp::cache_row(a, b, kvh, tt) : base + tt;
+            const int E = a.v_exp[vrow * nb + ((2 * cp) >> a.log2_block)];
             const float scale = ldexpf(1.0f, E - 127 - (P - 2));
             float v0, v1;
             if (P == 4) {
-                const uint32_t byte = a.v_mant[(base + tt) * kRowBytes + cp];
+                const uint32_t byte = a.v_mant[vrow * kRowBytes + cp];
                 v0 = code_value<4>(byte & 0xFu) * scale;
                 v1 = code_value<4>(byte >> 4) * scale;
             } else {
-                const uint32_t two = ((const uint16_t*)(a.v_mant + (base + tt) * kRowBytes))[cp];
+                const uint32_t two = ((const uint16_t*)(a.v_mant + vrow * kRowBytes))[cp];
                 v0 = code_value<8>(two & 0xFFu) * scale;
                 v1 = code_value<8>(two >> 8) * scale;
             }

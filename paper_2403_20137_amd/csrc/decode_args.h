@@ -46,7 +46,8 @@ struct DecodeArgs {
     // Paged cache (kvbfp_decode_attention_paged): the planes are a pool [n_pages][H_kv][2^log2_page][..]
     // and tokens [i 2^log2_page, (i+1) 2^log2_page) of sequence b live in page
     // block_table[b * table_stride + i]; nullptr = one contiguous region of max_seq tokens per sequence.
-    // A page holds a multiple of 64 tokens, so the 64-token tile of a wavefront never straddles two pages.
+    // A page holds 16 tokens or a power of two above: a 64-token tile of a wavefront may span up to four pages,
+    // one per 16-token stage (StageBases below).
     const int32_t* block_table;
     int64_t table_stride;
     int32_t log2_page, n_pages;
@@ -59,6 +60,27 @@ __device__ inline int64_t cache_row(const DecodeArgs& a, int b, int kvh, int64_t
     int page = a.block_table[(int64_t)b * a.table_stride + (t >> a.log2_page)];
     page = page < 0 ? 0 : (page >= a.n_pages ? a.n_pages - 1 : page);
     return (((int64_t)page * a.H_kv + kvh) << a.log2_page) + (t & (((int64_t)1 << a.log2_page) - 1));
+}
+
+// Paged caches: the rows of a 64-token tile that starts at token t_tile (a multiple of 64) of sequence b, one
+// additive base per 16-token stage: token t of stage u lies in plane row v[u] + t.  t_end = cached tokens
+// (> t_tile).  A stage that starts at or beyond t_end takes the base of the stage that holds the last cached
+// token, so that a token index clamped to t_end - 1 can be added to the base of the stage that asks.
+struct StageBases { int64_t v[4]; };
+__device__ inline StageBases stage_bases(const DecodeArgs& a, int b, int kvh, int64_t t_tile, int64_t t_end) {
+    StageBases s;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        int64_t t = t_tile + 16 * u;
+        if (t >= t_end) t = (t_end - 1) & ~(int64_t)15;
+        s.v[u] = cache_row(a, b, kvh, t) - t;
+    }
+    return s;
+}
+// v[st] for a per-lane stage index (compares and selects, no indexed register access)
+__device__ inline int64_t stage_base_of(const StageBases& s, int st) {
+    const int64_t lo = (st & 1) ? s.v[1] : s.v[0], hi = (st & 1) ? s.v[3] : s.v[2];
+    return (st & 2) ? hi : lo;
 }
 
 // Row of q / out, in units of head_dim elements, of virtual head s of kv-head kvh in batch b.

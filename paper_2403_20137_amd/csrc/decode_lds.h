@@ -189,8 +189,9 @@ constexpr int kStreamAux = 2;
 
 constexpr int vmcnt_imm(int n) { return (n & 0xF) | (0x7 << 4) | (0xF << 8) | ((n >> 4) << 14); }
 
-// PAGED: the planes are a pool of pages and every 64-token tile looks up its page (a scalar load, issued a
-// tile ahead of the requests that need it); a separate instantiation, so the contiguous case is untouched.
+// PAGED: the planes are a pool of pages and every 16-token stage of a 64-token tile looks up its page (scalar
+// loads, issued a tile ahead of the requests that need them); a separate instantiation, so the contiguous case
+// is untouched.
 // QI8 (8-bit mantissas, blocks of 32 and wider, query cast to 8-bit BFP): the score product on the integer
 // datapath of Sec. II-B -- v_mfma_i32_16x16x64_i8 on the signed codes of query and keys, one accumulator per 32
 // channels, and the two block exponents added and applied to the integer sums afterwards.
@@ -327,8 +328,31 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
     }
 
     const int64_t base = PAGED ? 0 : ((int64_t)b * a.H_kv + kvh) * a.max_seq + t_begin;
-    // row (relative to the bases below) of the 64-token tile that starts at token T of the split
-    auto tile_row = [&](const int T) -> int64_t { return PAGED ? kvbfp::cache_row(a, b, kvh, t_begin + T) : (int64_t)T; };
+    // Where the 64-token tile that starts at token T of the split lies in the planes.  One region per sequence,
+    // and pages of 64 tokens or more (a tile has one page): r[0] = first row of the tile relative to the bases below.
+    // Pages of 16 or 32 tokens: one entry per 16-token stage, r[u] + (token of the split) = plane row of a token of
+    // stage u.
+    const bool small_pages = PAGED && a.log2_page < 6;          // wave-uniform
+    struct TileRows { int64_t r[PAGED ? 4 : 1]; };
+    auto tile_rows = [&](const int T, const bool live) -> TileRows {
+        TileRows tr;
+        if constexpr (PAGED) {
+            if (live && !small_pages) {
+                tr.r[0] = kvbfp::cache_row(a, b, kvh, t_begin + T);
+                tr.r[1] = tr.r[2] = tr.r[3] = 0;
+            } else if (live) {
+                const kvbfp::StageBases sb = kvbfp::stage_bases(a, b, kvh, t_begin + T, t_end);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) tr.r[u] = sb.v[u] + t_begin;
+            } else {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) tr.r[u] = 0;
+            }
+        } else {
+            tr.r[0] = live ? (int64_t)T : 0;
+        }
+        return tr;
+    };
     const uint8_t* __restrict__ k_mant = a.k_mant + base * kRowB;
     const uint8_t* __restrict__ v_mant = a.v_mant + base * kRowB;
     const uint8_t* __restrict__ k_exp = a.k_exp + base * NB;
@@ -361,10 +385,29 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
     // row `row` (tile_row of the tile).  A full tile takes the immediate-offset form (the offset applies to the
     // global and to the LDS address alike, 1024 bytes per stage in both); in a ragged one rows past the last
     // cached token re-read that token.  `left` values are wave-uniform, so these are scalar branches.
-    auto fill_mant = [&](auto U, const bool keys, const bool tile_full, const int t, const int64_t row) {
+    auto fill_mant = [&](auto U, const bool keys, const bool tile_full, const int t, const TileRows& rows) {
         constexpr int u = decltype(U)::value;
-        const uint8_t* __restrict__ mp = (keys ? k_mant : v_mant) + row * kRowB;
         uint8_t* const lm = wbase + (keys ? kKm : kVm);
+        if (PAGED && small_pages) {
+            // the stage's own page: first row of the stage, then (row of the stage, chunk) of this lane
+            const uint8_t* __restrict__ sp = (keys ? k_mant : v_mant) + (rows.r[u] + t + 16 * u) * kRowB;
+            const int left = n_tok - (t + 16 * u);       // may be <= 0: then every lane re-reads the last cached token
+#pragma unroll
+            for (int i = 0; i < kM; ++i) {
+                int r, c;
+                if constexpr (P == 8) {
+                    r = keys ? k8_row[i] : v8_row[i];
+                    c = keys ? k8_chunk[i] : (lane & 7);
+                } else {
+                    r = keys ? kd_row : vrow_of_slot;
+                    c = keys ? kd_chunk : vp_c;
+                }
+                if (!tile_full) r = min(r, left - 1);
+                __builtin_amdgcn_global_load_lds(KVBFP_GPTR(sp + (r * kRowB + c * 16)), KVBFP_LPTR(lm + u * kStageB + i * 1024), 16, 0, kStreamAux);
+            }
+            return;
+        }
+        const uint8_t* __restrict__ mp = (keys ? k_mant : v_mant) + rows.r[0] * kRowB;
         if constexpr (P == 8) {
             const int left = n_tok - (t + 16 * u);       // may be <= 0: then every lane re-reads the last cached token
 #pragma unroll
@@ -385,9 +428,27 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
         }
     };
     // Exponents of a whole tile, [64 tokens][NB] as they lie in the plane.
-    auto fill_exp = [&](const bool keys, const bool tile_full, const int t, const int64_t row) {
-        const uint8_t* __restrict__ ep = (keys ? k_exp : v_exp) + row * NB;
+    auto fill_exp = [&](const bool keys, const bool tile_full, const int t, const TileRows& rows) {
         uint8_t* const le = wbase + (keys ? kKe : kVe);
+        if (PAGED && small_pages) {
+            const uint8_t* __restrict__ pp = keys ? k_exp : v_exp;
+            const int left = n_tok - t;                    // >= 1
+#pragma unroll
+            for (int x = 0; x < kExpDma; ++x) {
+                const int byte = (int)e_src + 256 * x;      // offset in the tile's exponent rows: this lane's token and byte
+                int tk = byte / NB;
+                if (!tile_full) tk = min(tk, left - 1);
+                const int st = tk >> 4;
+                const int64_t lo = (st & 1) ? rows.r[1] : rows.r[0], hi = (st & 1) ? rows.r[3] : rows.r[2];
+                const int64_t row = ((st & 2) ? hi : lo) + t + tk;
+                const uint8_t* __restrict__ src = pp + (row * NB + byte % NB);
+                if constexpr (NB >= 4) __builtin_amdgcn_global_load_lds(KVBFP_GPTR(src), KVBFP_LPTR(le + 256 * x), 4, 0, kStreamAux);
+                else if constexpr (NB == 2) __builtin_amdgcn_global_load_lds(KVBFP_GPTR(src), KVBFP_LPTR(le + 256 * x), 2, 0, kStreamAux);
+                else __builtin_amdgcn_global_load_lds(KVBFP_GPTR(src), KVBFP_LPTR(le + 256 * x), 1, 0, kStreamAux);
+            }
+            return;
+        }
+        const uint8_t* __restrict__ ep = (keys ? k_exp : v_exp) + rows.r[0] * NB;
         if (tile_full) {
             if constexpr (NB >= 4) __builtin_amdgcn_global_load_lds(KVBFP_GPTR(ep + e_src), KVBFP_LPTR(le), 4, 0, kStreamAux);
             else if constexpr (NB == 2) __builtin_amdgcn_global_load_lds(KVBFP_GPTR(ep + e_src), KVBFP_LPTR(le), 2, 0, kStreamAux);
@@ -448,7 +509,7 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
     const int T_first = wave * kTileTok;
     const bool has_work = T_first < n_tok;
     if (has_work) {
-        const int64_t row0 = tile_row(T_first);
+        const TileRows row0 = tile_rows(T_first, true);
         const bool full0 = n_tok - T_first >= kTileTok;
         static_for<4>([&](auto U) {
             fill_mant(U, true, full0, T_first, row0);
@@ -695,7 +756,7 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
         // One tile.  STEADY: this tile is complete and seen whole by every head, and a complete next tile is being
         // requested -- the common case, compiled without the ragged-tile branches, clamps and masks.
         auto tile_body = [&](auto steady_tag, const int T0, const int T1, const bool more_rt, const bool full1_rt,
-                             const bool masked_rt, const int64_t row1) {
+                             const bool masked_rt, const TileRows& row1) {
             constexpr bool STEADY = decltype(steady_tag)::value;
             const bool more = STEADY ? true : more_rt;
             const bool full1 = STEADY ? true : full1_rt;
@@ -931,7 +992,7 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
         for (int T0 = T_first; T0 < n_tok; T0 += kStep) {
             const int T1 = T0 + kStep;
             const bool more = T1 < n_tok;            // wave-uniform
-            const int64_t row1 = more ? tile_row(T1) : 0;
+            const TileRows row1 = tile_rows(T1, more);
             const bool full1 = n_tok - T1 >= kTileTok;       // the next tile is complete
             if (appends && more && T1 + kStep >= n_tok) {      // next comes the tile with the new row: its stores first
                 __builtin_amdgcn_sched_barrier(0);

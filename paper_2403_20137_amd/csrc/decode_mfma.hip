@@ -70,7 +70,7 @@ __device__ __forceinline__ int slot_channel(int x) { return (x < 4) ? 2 * x : 2 
 // N = block size, HG = groups of four query heads per KV head (G <= 4*HG).
 // grid = (n_splits, H_kv, B), block = 256 (four wavefronts).
 // PL = bf16 limbs of a probability: 2 (16 bits, enough for 16-bit outputs) or 3 (24 bits, fp32 outputs).
-// PAGED: the planes are a pool of pages and every tile looks up its page (a separate instantiation: the
+// PAGED: the planes are a pool of pages and every 16-token stage of a tile looks up its page (a separate instantiation: the
 // contiguous case keeps its 32-bit offsets from one scalar base).
 template <int N, int HG, int PL, bool PAGED>
 __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt) {
@@ -154,7 +154,7 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
 
     // Plane bases of this (batch, kv-head) are wave-uniform (scalar registers); everything inside
     // the split is addressed with 32-bit offsets from them.
-    // (Paged cache: the bases are those of the pool and every tile looks up its page.)
+    // (Paged cache: the bases are those of the pool and every 16-token stage of a tile looks up its page.)
     const int64_t base = PAGED ? 0 : ((int64_t)b * a.H_kv + kvh) * a.max_seq + t_begin;
     const uint8_t* __restrict__ k_mant = a.k_mant + base * 64;
     const uint8_t* __restrict__ v_mant = a.v_mant + base * 64;
@@ -190,17 +190,18 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
     // clamping or masking; otherwise rows are clamped to the last cached token and masked.
     auto tile = [&](const int T0, auto full_tag) {
         constexpr bool FULL = decltype(full_tag)::value;
-        const size_t R0 = PAGED ? (size_t)kvbfp::cache_row(a, b, kvh, t_begin + T0) : (size_t)T0;   // wave-uniform
-        const uint8_t* __restrict__ kp = k_mant + R0 * 64;
-        const uint8_t* __restrict__ vp = v_mant + R0 * 64;
-        const uint8_t* __restrict__ kep = k_exp + R0 * NB;
-        const uint8_t* __restrict__ vep = v_exp + R0 * NB;
+        // first row of the tile, wave-uniform; a pool of pages has one base per 16-token stage (a page may hold 16 tokens)
+        kvbfp::StageBases sb{};
+        if constexpr (PAGED) sb = kvbfp::stage_bases(a, b, kvh, t_begin + T0, t_end);
+        auto tile_base = [&](const int u) -> size_t { return PAGED ? (size_t)(sb.v[u] + t_begin + T0) : (size_t)T0; };
         const int left = n_tok - T0;                 // cached tokens from T0 on (>= 1)
 
         // ---------------- scores of 64 tokens
         f32x4 s_acc[HG][4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
+            const uint8_t* __restrict__ kp = k_mant + tile_base(u) * 64;
+            const uint8_t* __restrict__ kep = k_exp + tile_base(u) * NB;
             uint32_t mo, eo;
             if (FULL) {
                 mo = koff + 1024u * u;
@@ -283,6 +284,8 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p4(DecodeArgs a, int dt
         // ---------------- values of the same 64 tokens
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
+            const uint8_t* __restrict__ vp = v_mant + tile_base(u) * 64;
+            const uint8_t* __restrict__ vep = v_exp + tile_base(u) * NB;
             Unpacked vv[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {

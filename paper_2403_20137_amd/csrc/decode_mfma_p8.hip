@@ -72,7 +72,7 @@ __device__ __forceinline__ Pieces unpack4(uint32_t w, float s_hi, float s_lo) {
 // N = block size, HG = groups of four query heads per KV head (G <= 4*HG).
 // grid = (n_splits, H_kv, B), block = 256 (four wavefronts).
 // PL = bf16 limbs of a probability: 2 (16 bits, enough for 16-bit outputs) or 3 (24 bits, fp32 outputs).
-// PAGED: the planes are a pool of pages and every tile looks up its page (a separate instantiation: the
+// PAGED: the planes are a pool of pages and every 16-token stage of a tile looks up its page (a separate instantiation: the
 // contiguous case keeps its 32-bit offsets from one scalar base).
 template <int N, int HG, int PL, bool PAGED>
 __global__ __launch_bounds__(256) void decode_split_mfma_p8(DecodeArgs a, int dt) {
@@ -159,7 +159,7 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p8(DecodeArgs a, int dt
 
     // Plane bases of this (batch, kv-head) are wave-uniform; everything inside the split is
     // addressed with 32-bit offsets from them.
-    // (Paged cache: the bases are those of the pool and every tile looks up its page.)
+    // (Paged cache: the bases are those of the pool and every 16-token stage of a tile looks up its page.)
     const int64_t base = PAGED ? 0 : ((int64_t)b * a.H_kv + kvh) * a.max_seq + t_begin;
     const uint8_t* __restrict__ k_mant = a.k_mant + base * 128;
     const uint8_t* __restrict__ v_mant = a.v_mant + base * 128;
@@ -193,17 +193,18 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p8(DecodeArgs a, int dt
     // otherwise rows are clamped to the last cached token and masked.
     auto tile = [&](const int T0, auto full_tag) {
         constexpr bool FULL = decltype(full_tag)::value;
-        const size_t R0 = PAGED ? (size_t)kvbfp::cache_row(a, b, kvh, t_begin + T0) : (size_t)T0;   // wave-uniform
-        const uint8_t* __restrict__ kp = k_mant + R0 * 128;
-        const uint8_t* __restrict__ vp = v_mant + R0 * 128;
-        const uint8_t* __restrict__ kep = k_exp + R0 * NB;
-        const uint8_t* __restrict__ vep = v_exp + R0 * NB;
+        // first row of the tile, wave-uniform; a pool of pages has one base per 16-token stage (a page may hold 16 tokens)
+        kvbfp::StageBases sb{};
+        if constexpr (PAGED) sb = kvbfp::stage_bases(a, b, kvh, t_begin + T0, t_end);
+        auto tile_base = [&](const int u) -> size_t { return PAGED ? (size_t)(sb.v[u] + t_begin + T0) : (size_t)T0; };
         const int left = n_tok - T0;                 // cached tokens from T0 on (>= 1)
 
         // ---------------- scores of 64 tokens
         f32x4 s_acc[HG][4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
+            const uint8_t* __restrict__ kp = k_mant + tile_base(u) * 128;
+            const uint8_t* __restrict__ kep = k_exp + tile_base(u) * NB;
             const uint32_t r = FULL ? (uint32_t)(16 * u + j) : (uint32_t)min(16 * u + j, left - 1);
             const u32x4 raw0 = __builtin_nontemporal_load((const u32x4*)(kp + r * 128u + kchunk));   // streamed once
             const u32x4 raw1 = __builtin_nontemporal_load((const u32x4*)(kp + r * 128u + kchunk + 64u));
@@ -273,6 +274,8 @@ __global__ __launch_bounds__(256) void decode_split_mfma_p8(DecodeArgs a, int dt
         // ---------------- values of the same 64 tokens
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
+            const uint8_t* __restrict__ vp = v_mant + tile_base(u) * 128;
+            const uint8_t* __restrict__ vep = v_exp + tile_base(u) * NB;
             Pieces va[4], vb[4];   // channels 8j..8j+3 and 8j+4..8j+7 of tokens 16u + 4kg + i
 #pragma unroll
             for (int i = 0; i < 4; ++i) {

@@ -34,9 +34,9 @@ constexpr int kTokenTile = 256;
 SplitPlan plan_splits(const kvbfp_layout* L, int32_t n_q_heads, int64_t max_len);
 
 // A paged cache: `pool` describes the pool of pages (batch = pages, max_seq = tokens per page, a power of
-// two and at least kPageMin: the 64 tokens a wavefront handles at a time never straddle two pages);
+// two and at least kPageMin: the 16 tokens of a stage of the decode kernels never straddle two pages);
 // sequence b keeps tokens [i page, (i+1) page) in page block_table[b * table_stride + i].
-constexpr int kPageMin = 64;
+constexpr int kPageMin = 16;
 struct Paging {
     const int32_t* block_table;   // DEVICE int32 [batch][table_stride]
     int64_t table_stride;

@@ -83,7 +83,7 @@ def fill_both(k, v, n, p, page, pages_per_seq, lens, pk, pv, seed, chunks=(None,
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.float16, torch.bfloat16])
 @pytest.mark.parametrize("p,n", [(4, 16), (4, 32), (4, 64), (8, 16), (8, 128)])
-@pytest.mark.parametrize("G,page", [(1, 256), (4, 256), (8, 512), (4, 64), (2, 128)])
+@pytest.mark.parametrize("G,page", [(1, 256), (4, 256), (8, 512), (4, 64), (2, 128), (4, 16), (8, 32), (1, 16)])
 def test_paged_cache_matches_oracle(dtype, p, n, G, page):
     # 1300 and 700 tokens: six and three 256-token pages (or three and two of 512), last page ragged
     lens = [1300, 700]
@@ -99,7 +99,7 @@ def test_paged_cache_matches_oracle(dtype, p, n, G, page):
 def test_paged_equals_contiguous_bit_for_bit_and_wide_groups():
     # same kernels, same order of operations: the paged result is the contiguous one exactly; G = 40 takes
     # the general pass, G = 12 two launches of the matrix-core pass
-    for G, page in ((12, 256), (40, 256), (40, 64)):
+    for G, page in ((12, 256), (40, 256), (40, 64), (12, 16), (40, 32)):
         lens = [900, 900]
         k, v, q, pk, pv = make_small(torch.bfloat16, B=2, S=900, Hkv=1, G=G, seed=170 + G)
         pool, table, planes = fill_both(k, v, 32, 4, page, 1024 // page, lens, pk, pv, seed=G)
@@ -127,11 +127,12 @@ def test_query_cast_and_profile_variant_on_pages():
     assert split_ms > 0 and combine_ms > 0
 
 
-def test_integer_score_product_on_pages():
+@pytest.mark.parametrize("page", [128, 16])
+def test_integer_score_product_on_pages(page):
     # 8-bit keys in blocks of 32, query cast to 8-bit BFP: the int8 matrix product of the LDS pipeline over a pool
     lens = [700, 300]
     k, v, q, pk, pv = make_small(torch.bfloat16, B=2, S=700, Hkv=2, G=6, seed=185)
-    pool, table, planes = fill_both(k, v, 32, 8, 128, 6, lens, pk, pv, seed=11)
+    pool, table, planes = fill_both(k, v, 32, 8, page, 768 // page, lens, pk, pv, seed=11)
     want = O.decode_attention(*planes, D, 32, 8, synth.to_f32_numpy(q), lens, float(np.float32(0.09)), pk, pv,
                               q_mant_bits=8)
     got = kvbfp.decode_attention_paged(pool, table, q.cuda(), 700, float(np.float32(0.09)), q_mant_bits=8,
@@ -175,6 +176,9 @@ def test_paged_argument_errors():
     (torch.bfloat16, 4, 128, 8, 512, 2),
     (torch.bfloat16, 8, 16, 2, 256, 2),     # 8-bit mantissas and fp32 I/O: the cache-write kernel goes first
     (torch.float32, 4, 32, 2, 128, 2),
+    (torch.bfloat16, 4, 32, 4, 16, 64),     # pages of 16 and 32 tokens: a page per stage of a tile
+    (torch.bfloat16, 8, 32, 2, 32, 2),
+    (torch.float32, 4, 16, 1, 16, 2),
 ])
 def test_current_token_appended_and_attended_on_pages(dtype, p, n, G, page, Hkv):
     # the current tokens: the first row of a fresh page (1025 = 4 x 256 + 1 = 16 x 64 + 1), mid-page, the very
@@ -232,6 +236,9 @@ def test_current_token_appended_and_attended_on_pages(dtype, p, n, G, page, Hkv)
     (torch.float16, 4, 16, 1, 8, 64),
     (torch.bfloat16, 8, 32, 3, 7, 128),     # 21 virtual heads: three launches over head subsets
     (torch.bfloat16, 4, 64, 4, 9, 256),     # 36 virtual heads: general pass
+    (torch.bfloat16, 4, 32, 4, 4, 16),
+    (torch.bfloat16, 8, 16, 2, 3, 32),
+    (torch.float16, 4, 128, 5, 8, 16),      # 40 virtual heads: general pass over pages of 16
 ])
 def test_several_query_tokens_on_pages(dtype, p, n, G, Tq, page):
     lens = [830, max(Tq - 2, 1), 257 + Tq // 2]

@@ -174,7 +174,8 @@ def test_device_calls_reject_bad_arguments_before_launching():
 
     pages = kvbfp.make_layout(128, 32, 4, 2, 6, 256)
     assert dap(kvbfp.make_layout(128, 32, 4, 2, 6, 384)) == kvbfp.ERR_UNSUPPORTED and "page" in kvbfp.last_error()
-    assert dap(kvbfp.make_layout(128, 32, 4, 2, 6, 32)) == kvbfp.ERR_UNSUPPORTED
+    assert dap(kvbfp.make_layout(128, 32, 4, 2, 6, 8)) == kvbfp.ERR_UNSUPPORTED           # below 16 tokens per page
+    assert dap(kvbfp.make_layout(128, 32, 4, 2, 40, 16), stride=20) == kvbfp.ERR_WORKSPACE  # pages of 16 tokens are taken
     assert dap(pages, table=None) == kvbfp.ERR_INVALID_ARG
     assert dap(pages, batch=0) == kvbfp.ERR_INVALID_ARG
     assert dap(pages, max_len=513) == kvbfp.ERR_INVALID_ARG          # two pages of 256 tokens
