@@ -295,9 +295,7 @@ __global__ __launch_bounds__(kTile) void decode_split_generic(DecodeArgs a, int 
         }
         const int64_t tw0 = tile0 + wave * 64;
         const int cnt = (int)max((int64_t)0, min((int64_t)64, t_end - tw0));
-        for (int k = 0; k < cnt; ++k) {
-            const int64_t tt = tw0 + k;
-            const int64_t vrow = per_token ? kvbfp::cache_row(a, b, kvh, tt) : base + tt;
+        auto add_value_row = [&](const int k, const int64_t vrow) {
             const int E = a.v_exp[vrow * nb + ((2 * cp) >> a.log2_block)];
             const float scale = ldexpf(1.0f, E - 127 - (P - 2));
             float v0, v1;
@@ -316,6 +314,11 @@ __global__ __launch_bounds__(kTile) void decode_split_generic(DecodeArgs a, int 
                 o[g][0] = fmaf(pw, v0, o[g][0]);
                 o[g][1] = fmaf(pw, v1, o[g][1]);
             }
+        };
+        if (per_token) {      // its own loop: the look-up stays out of the common one
+            for (int k = 0; k < cnt; ++k) add_value_row(k, kvbfp::cache_row(a, b, kvh, tw0 + k));
+        } else {
+            for (int k = 0; k < cnt; ++k) add_value_row(k, base + tw0 + k);
         }
         __syncthreads();   // sc and alpha_s are rewritten by the next tile
     }
