@@ -539,15 +539,14 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
     if ((int64_t)L->batch > 65535 || (int64_t)n_q_heads > 65535)
         return fail(KVBFP_ERR_UNSUPPORTED, "decode_attention: batch/heads exceed the grid limits");
 
-    const SplitPlan sp = plan_splits(L, n_q_heads, max_len);
+    SplitPlan sp = plan_splits(L, n_q_heads, max_len);       // what the workspace is sized for
     DecodeArgs a{};
     a.k_mant = cache->k_mant; a.k_exp = cache->k_exp; a.v_mant = cache->v_mant; a.v_exp = cache->v_exp;
     a.q = q; a.out = out; a.seq_len = seq_len_dev; a.perm_k = perm_k; a.perm_v = perm_v;
     a.part_o = (float*)workspace;
-    a.part_ml = a.part_o + (size_t)L->batch * n_q_heads * sp.n_splits * kD;
     a.max_seq = L->max_seq; a.max_len = max_len;
     a.H_kv = L->n_kv_heads; a.H_q = n_q_heads; a.G = n_q_heads / L->n_kv_heads;
-    a.n_splits = sp.n_splits; a.log2_block = log2_exact(L->block);
+    a.log2_block = log2_exact(L->block);
     a.n_q_tokens = n_q_tokens; a.real_Hq = real_heads; a.real_G = real_heads / L->n_kv_heads;
     a.q_mant_bits = q_mant_bits;
     a.scale_log2e = softmax_scale * 1.4426950408889634f;
@@ -562,7 +561,6 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
     const int gg = (a.G + kHeadsPerWg - 1) / kHeadsPerWg;
     if ((int64_t)a.H_kv * gg > 65535)
         return fail(KVBFP_ERR_UNSUPPORTED, "decode_attention: too many heads for the grid");
-    const dim3 grid1((unsigned)sp.n_splits, (unsigned)(a.H_kv * gg), (unsigned)L->batch);
     auto aligned16 = [](const void* p) { return ((uintptr_t)p & 15u) == 0; };
     // Matrix-core passes (not with the rotation at read): up to 8 (virtual) heads of a kv-head per launch; larger groups take
     // several launches over head subsets (the cache is then read once per subset), up to 4 of them.
@@ -572,6 +570,15 @@ static int decode_impl(const kvbfp_layout* L, const kvbfp_cache* cache, int32_t 
     // rotation at read: the matrix-core pass takes 4-bit mantissas with 16-bit I/O, four heads per launch
     const bool rope_fast = rope && !paging && dtype != KVBFP_F32 && L->mant_bits == 4 && a.G <= 32 &&
                            aligned16(a.k_exp) && aligned16(a.v_exp);
+    // (its workgroups hold a 64 KB table in LDS, two fit a compute unit: fewer splits, one resident round)
+    if (rope_fast) {
+        const int64_t units = (int64_t)L->batch * L->n_kv_heads;
+        const int64_t two_per_cu = (512 + units - 1) / units;
+        if (sp.n_splits > two_per_cu) sp.n_splits = (int32_t)two_per_cu;
+    }
+    a.n_splits = sp.n_splits;
+    a.part_ml = a.part_o + (size_t)L->batch * n_q_heads * sp.n_splits * kD;
+    const dim3 grid1((unsigned)sp.n_splits, (unsigned)(a.H_kv * gg), (unsigned)L->batch);
     a.g_base = 0;
     a.g_cnt = a.G < 8 ? a.G : 8;
     // The current token (kvbfp_append_decode_attention): cast inside the LDS split pass, else by the

@@ -329,27 +329,30 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
 
     const int64_t base = PAGED ? 0 : ((int64_t)b * a.H_kv + kvh) * a.max_seq + t_begin;
     // Where the 64-token tile that starts at token T of the split lies in the planes.  One region per sequence,
-    // and pages of 64 tokens or more (a tile has one page): r[0] = first row of the tile relative to the bases below.
-    // Pages of 16 or 32 tokens: one entry per 16-token stage, r[u] + (token of the split) = plane row of a token of
-    // stage u.
+    // and pages of 64 tokens or more (a tile has one page): r0 = first row of the tile relative to the bases below.
+    // Pages of 16 or 32 tokens: one entry per 16-token stage, q[u] = (first plane row of stage u) / 16 -- a stage
+    // starts at a multiple of 16 rows, and the quotient fits 32 bits.  A stage that starts beyond the last cached
+    // token takes the entry of the stage that holds that token.
     const bool small_pages = PAGED && a.log2_page < 6;          // wave-uniform
-    struct TileRows { int64_t r[PAGED ? 4 : 1]; };
+    struct TileRows { int64_t r0; int32_t q[PAGED ? 4 : 1]; };
     auto tile_rows = [&](const int T, const bool live) -> TileRows {
         TileRows tr;
+        tr.r0 = 0;
+#pragma unroll
+        for (int u = 0; u < (PAGED ? 4 : 1); ++u) tr.q[u] = 0;
         if constexpr (PAGED) {
             if (live && !small_pages) {
-                tr.r[0] = kvbfp::cache_row(a, b, kvh, t_begin + T);
-                tr.r[1] = tr.r[2] = tr.r[3] = 0;
+                tr.r0 = kvbfp::cache_row(a, b, kvh, t_begin + T);
             } else if (live) {
-                const kvbfp::StageBases sb = kvbfp::stage_bases(a, b, kvh, t_begin + T, t_end);
 #pragma unroll
-                for (int u = 0; u < 4; ++u) tr.r[u] = sb.v[u] + t_begin;
-            } else {
-#pragma unroll
-                for (int u = 0; u < 4; ++u) tr.r[u] = 0;
+                for (int u = 0; u < 4; ++u) {
+                    int64_t t = t_begin + T + 16 * u;
+                    if (t >= t_end) t = (t_end - 1) & ~(int64_t)15;
+                    tr.q[u] = (int32_t)(kvbfp::cache_row(a, b, kvh, t) >> 4);
+                }
             }
         } else {
-            tr.r[0] = live ? (int64_t)T : 0;
+            tr.r0 = live ? (int64_t)T : 0;
         }
         return tr;
     };
@@ -390,8 +393,9 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
         uint8_t* const lm = wbase + (keys ? kKm : kVm);
         if (PAGED && small_pages) {
             // the stage's own page: first row of the stage, then (row of the stage, chunk) of this lane
-            const uint8_t* __restrict__ sp = (keys ? k_mant : v_mant) + (rows.r[u] + t + 16 * u) * kRowB;
-            const int left = n_tok - (t + 16 * u);       // may be <= 0: then every lane re-reads the last cached token
+            const uint8_t* __restrict__ sp = (keys ? k_mant : v_mant) + ((int64_t)rows.q[u] << 4) * kRowB;
+            // rows of the stage past the last cached token re-read a cached row of the stage that holds that token
+            const int last = (n_tok - (t + 16 * u) >= 16) ? 15 : ((n_tok - 1) & 15);
 #pragma unroll
             for (int i = 0; i < kM; ++i) {
                 int r, c;
@@ -402,12 +406,12 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
                     r = keys ? kd_row : vrow_of_slot;
                     c = keys ? kd_chunk : vp_c;
                 }
-                if (!tile_full) r = min(r, left - 1);
+                if (!tile_full) r = min(r, last);
                 __builtin_amdgcn_global_load_lds(KVBFP_GPTR(sp + (r * kRowB + c * 16)), KVBFP_LPTR(lm + u * kStageB + i * 1024), 16, 0, kStreamAux);
             }
             return;
         }
-        const uint8_t* __restrict__ mp = (keys ? k_mant : v_mant) + rows.r[0] * kRowB;
+        const uint8_t* __restrict__ mp = (keys ? k_mant : v_mant) + rows.r0 * kRowB;
         if constexpr (P == 8) {
             const int left = n_tok - (t + 16 * u);       // may be <= 0: then every lane re-reads the last cached token
 #pragma unroll
@@ -439,8 +443,8 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
                 int tk = byte / NB;
                 if (!tile_full) tk = min(tk, left - 1);
                 const int st = tk >> 4;
-                const int64_t lo = (st & 1) ? rows.r[1] : rows.r[0], hi = (st & 1) ? rows.r[3] : rows.r[2];
-                const int64_t row = ((st & 2) ? hi : lo) + t + tk;
+                const int32_t lo = (st & 1) ? rows.q[1] : rows.q[0], hi = (st & 1) ? rows.q[3] : rows.q[2];
+                const int64_t row = ((int64_t)((st & 2) ? hi : lo) << 4) + (tk & 15);
                 const uint8_t* __restrict__ src = pp + (row * NB + byte % NB);
                 if constexpr (NB >= 4) __builtin_amdgcn_global_load_lds(KVBFP_GPTR(src), KVBFP_LPTR(le + 256 * x), 4, 0, kStreamAux);
                 else if constexpr (NB == 2) __builtin_amdgcn_global_load_lds(KVBFP_GPTR(src), KVBFP_LPTR(le + 256 * x), 2, 0, kStreamAux);
@@ -448,7 +452,7 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
             }
             return;
         }
-        const uint8_t* __restrict__ ep = (keys ? k_exp : v_exp) + rows.r[0] * NB;
+        const uint8_t* __restrict__ ep = (keys ? k_exp : v_exp) + rows.r0 * NB;
         if (tile_full) {
             if constexpr (NB >= 4) __builtin_amdgcn_global_load_lds(KVBFP_GPTR(ep + e_src), KVBFP_LPTR(le), 4, 0, kStreamAux);
             else if constexpr (NB == 2) __builtin_amdgcn_global_load_lds(KVBFP_GPTR(ep + e_src), KVBFP_LPTR(le), 2, 0, kStreamAux);
