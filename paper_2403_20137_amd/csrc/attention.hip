@@ -372,6 +372,10 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine(DecodeArgs a, 
     const int n = a.n_splits;
     const bool staged = n <= kMaxLds;           // otherwise (m, l) are read from global memory each time
 
+    // where this channel goes in the output row: requested with the partial outputs, not after the sums (a load here
+    // costs nothing, at the end it is one more round trip to memory)
+    const int kvh = h / a.G;
+    const int c_raw = a.perm_v ? a.perm_v[kvh * kD + j] : j;
     float v[kCombineBatch];                     // first batch of this thread's partial outputs: splits sl + kSlices k
 #pragma unroll
     for (int k = 0; k < kCombineBatch; ++k) {
@@ -435,8 +439,7 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine(DecodeArgs a, 
         }
     }
     const float r = den > 0.f ? num / den : 0.f;
-    const int kvh = h / a.G;
-    const int c = a.perm_v ? (a.perm_v[kvh * kD + j] & (kD - 1)) : j;   // masked: the store stays inside the row
+    const int c = c_raw & (kD - 1);             // masked: the store stays inside the row
     const int64_t oi = kvbfp::query_row(a, b, kvh, h % a.G) * kD + c;
     if (dt == KVBFP_F32) ((float*)a.out)[oi] = r;
     else if (dt == KVBFP_F16) ((uint16_t*)a.out)[oi] = __builtin_bit_cast(unsigned short, (_Float16)r);
