@@ -272,10 +272,27 @@ def bulk_quantize_rate(device="cuda", reps=5):
     us_perm = rate(perm)
     elems = 2 * k.numel()
     bytes_ = elems * 2 + elems * w.mant_bits // 8 + elems // w.block
+    # the way back (kvbfp_dequantize): the K plane of the same cache to bf16 rows, in cache order and un-permuted
+    out = torch.empty_like(k)
+    def back(perm):
+        kvbfp.dequantize(cache, 0, 0, w.seq, perm=perm, out=out)
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, b in ev:
+            a.record()
+            kvbfp.dequantize(cache, 0, 0, w.seq, perm=perm, out=out)
+            b.record()
+        torch.cuda.synchronize()
+        return np.array([a.elapsed_time(b) for a, b in ev]) * 1e3
+    dq, dq_perm = back(None), back(perm)
     return {"workload": w.name, "elements": elems, "us_median": float(np.median(us)), "us_min": float(us.min()),
             "gelem_s": elems / np.median(us) / 1e3, "hbm_gb_s": bytes_ / np.median(us) / 1e3,
             "hbm_frac": bytes_ / np.median(us) / 1e3 / HBM_PEAK_GBS,
-            "with_perm_us_median": float(np.median(us_perm)), "with_perm_gelem_s": elems / np.median(us_perm) / 1e3}
+            "with_perm_us_median": float(np.median(us_perm)), "with_perm_gelem_s": elems / np.median(us_perm) / 1e3,
+            "dequantize_k_elements": elems // 2, "dequantize_k_us_median": float(np.median(dq)),
+            "dequantize_k_gelem_s": elems / 2 / np.median(dq) / 1e3,
+            "dequantize_k_hbm_frac": bytes_ / 2 / np.median(dq) / 1e3 / HBM_PEAK_GBS,
+            "dequantize_k_with_perm_us_median": float(np.median(dq_perm))}
 
 
 def profile_counters():

@@ -150,9 +150,11 @@ int kvbfp_quantize_append(const kvbfp_layout* layout, const kvbfp_cache* cache, 
  *   perm  : DEVICE int32 [n_kv_heads][head_dim] or NULL.  NULL leaves cache (permuted) order;
  *           otherwise out[perm[h][j]] = value at cache position j (original channel order).
  *           `out` must be 16-byte aligned.
+ *           A perm that is not a permutation is memory-safe (entries are masked to the row); the output
+ *           channels it does not reach are then unspecified.
  * fp32 output is exact; fp16/bf16 output is the IEEE round-to-nearest-even conversion.
  * Errors: INVALID_ARG (NULL, range outside [0, max_seq], bad which/dtype, `out` not 16-byte aligned),
- * UNSUPPORTED, HIP. */
+ * UNSUPPORTED (also: batch * n_kv_heads * n_tok above 2^31 - 1 in one call), HIP. */
 int kvbfp_dequantize(const kvbfp_layout* layout, const kvbfp_cache* cache, int32_t which,
                      int64_t t0, int64_t n_tok, const int32_t* perm, void* out, kvbfp_dtype dtype,
                      void* hip_stream);

@@ -145,6 +145,31 @@ def test_dequantize_matches_oracle(dtype, p, n, with_perm):
             assert torch.equal(g.view(torch.int16), want.view(torch.int16))
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_dequantize_many_rows_ragged_tail_and_unaligned_permutation(dtype):
+    # 3 x 5 x 211 rows: many 64-row workgroups and a ragged last one; the permutation once 16-byte aligned and
+    # once at an address that is only 4-byte aligned (its entries are then loaded one by one): same bits
+    B, T, H, D, n, p = 3, 211, 5, 128, 32, 4
+    rng = np.random.default_rng(19)
+    ms, es = O.plane_shapes(B, H, D, n, p, T + 5)
+    mant = rng.integers(0, 256, size=ms, dtype=np.uint8)
+    exp = rng.integers(100, 150, size=es).astype(np.uint8)
+    perm = np.stack([rng.permutation(D) for _ in range(H)]).astype(np.int32)
+    L = kvbfp.make_layout(D, n, p, H, B, T + 5)
+    cache = kvbfp.Cache(L, torch.from_numpy(mant).cuda(), torch.from_numpy(exp).cuda(), None, None)
+    want = torch.from_numpy(O.dequantize(mant, exp, D, n, p, 3, T, perm=perm)).to(dtype)
+    aligned = dev_i32(perm)
+    holder = torch.zeros(H * D + 1, dtype=torch.int32, device="cuda")
+    holder[1:] = aligned.reshape(-1)
+    shifted = holder[1:].view(H, D)
+    assert aligned.data_ptr() % 16 == 0 and shifted.data_ptr() % 16 == 4
+    for pr in (aligned, shifted):
+        got = kvbfp.dequantize(cache, 0, 3, T, dtype=dtype, perm=pr)
+        torch.cuda.synchronize()
+        assert torch.equal(got.cpu().view(torch.int16 if dtype == torch.bfloat16 else torch.int32),
+                           want.view(torch.int16 if dtype == torch.bfloat16 else torch.int32))
+
+
 def test_round_trip_through_both_kernels():
     # cast then decode on the GPU: within half a mantissa step of the input (Sec. II-B)
     w = synth.WORKLOADS["llama2_7b_4k"]
