@@ -242,6 +242,10 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
     // pass through there before the limbs are written); the limbs' scale bytes [NH*4][4] sit beside.
     static_assert(sizeof(p_lds) == NH * kD * 4 + NH * 4 * kD, "query staging fills the probability buffer exactly");
     __shared__ __align__(16) uint8_t qsc_lds[NH * 16];
+    // sixteen heads: the query operand (4 x 8 registers) does not stay in registers between tiles; it lives in LDS,
+    // [NH * 4 limb rows][128], and every tile reads it back for its score phase
+    constexpr bool kQueryInLds = HG == 4;
+    __shared__ __align__(16) uint8_t qop_lds[kQueryInLds ? NH * 4 * kD : 16];
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS bases stay in scalar registers
@@ -561,7 +565,7 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
 #pragma unroll
             for (int k = 0; k < kQPerThread; ++k) qv[k] = qr[((tid + 256 * k) / kD) * kD + perm_c] * a.scale_log2e;
         }
-        uint8_t* q8 = (uint8_t*)(qr + NH * kD);           // [NH * 4 limb rows][kD positions], beside the fp32 values
+        uint8_t* q8 = kQueryInLds ? qop_lds : (uint8_t*)(qr + NH * kD);   // [NH * 4 limb rows][kD positions], beside the fp32 values
         uint8_t* qsc = qsc_lds;
         const int kb = qchan >> 5;
         if constexpr (QI8) {
@@ -697,6 +701,12 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
         uint64_t vw01[kPipe ? 2 : 1], vw23[kPipe ? 2 : 1], ppv[kPipeP ? 2 : 1][HG];
         u32x4 vexp32[4];          // blocks of 32: per stage the exponent dwords of tokens 4kg..4kg+3
         uint32_t vexp16[16];      // blocks of 16: per (stage, token) this lane's exponent byte
+        // sixteen heads: the sixteen exponent bytes this lane needs of a tile, packed into four registers right after
+        // they arrive (blocks of 32: register i = token 4kg + i, byte u = stage; blocks of 16: register u, byte i)
+        constexpr bool kPackVexp = HG == 4;
+        uint32_t vexp_pk[4];
+        const uint32_t pk_sel01 = (uint32_t)(j >> 2) | ((4u + (uint32_t)(j >> 2)) << 8) | 0x0c0c0000u;
+        const uint32_t pk_sel23 = ((uint32_t)(j >> 2) << 16) | ((4u + (uint32_t)(j >> 2)) << 24) | 0x00000c0cu;
         // DMA completes in issue order; per tile that is K0, key exponents, K1..K3, V0, value exponents, V1..V3.
         // "The oldest stage still outstanding has landed" = at most (instructions issued after it) outstanding:
         // with kM instructions per stage, 7 kM + kExpDma after the first stage of a plane (it ends with the exponents),
@@ -770,9 +780,22 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
             // read pending must not be live across the loop's back edge (the compiler may copy it there)
             wait_dma(true, std::integral_constant<int, kAfterFirst>{}, std::integral_constant<int, 0>{});
             issue_k0();
+            if constexpr (kQueryInLds) {
+                asm volatile("" ::: "memory");            // a fresh read every tile: the values must not stay live in between
+#pragma unroll
+                for (int hg = 0; hg < HG; ++hg) {
+                    const u32x4 lo = *(const u32x4*)(qop_lds + (hg * 16 + j) * kD + kg * 32);
+                    const u32x4 hi = *(const u32x4*)(qop_lds + (hg * 16 + j) * kD + kg * 32 + 16);
+                    aq8[hg] = v8i{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+                }
+            }
 
             // ---------------- scores
             f32x4 s_acc[HG][4];
+            // sixteen heads: the four limb rows of a stage are added up while the next stage's products run, so that
+            // one stage of accumulators is live at a time instead of four (64 registers less at the peak)
+            constexpr bool kEarlySum = HG == 4;
+            float s_sum[kEarlySum ? HG : 1][4];
             static_for<4>([&](auto U) {
                 constexpr int u = decltype(U)::value;
                 constexpr int cur = kPipe ? (u & 1) : 0;
@@ -852,11 +875,14 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
                                     (int)(raw[3] & 0xBBBBBBBBu), 0, 0, 0, 0};
                     const v8i b2 = {(int)(raw[0] & 0xCCCCCCCCu), (int)(raw[1] & 0xCCCCCCCCu), (int)(raw[2] & 0xCCCCCCCCu),
                                     (int)(raw[3] & 0xCCCCCCCCu), 0, 0, 0, 0};
+                    // (operand by operand over the head groups: one key operand is live at a time, and consecutive
+                    // products go to different accumulators)
 #pragma unroll
-                    for (int hg = 0; hg < HG; ++hg) {
+                    for (int hg = 0; hg < HG; ++hg)
                         s_acc[hg][u] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aq8[hg], b1, s_acc[hg][u], 0, 4, 0, sa8[hg], 0, sb);
+#pragma unroll
+                    for (int hg = 0; hg < HG; ++hg)
                         s_acc[hg][u] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aq8[hg], b2, s_acc[hg][u], 0, 4, 0, sa8[hg], 0, sb);
-                    }
                 } else {
                     // the lane's 32 nibbles are two blocks of 16 (dwords 0-1 and 2-3) with an exponent each
                     const int sb0 = (int)(kexp[u] & 0xFFu), sb1 = (int)(kexp[u] >> 8);
@@ -865,21 +891,36 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
                     const v8i hi1 = {0, 0, (int)(raw[2] & 0xBBBBBBBBu), (int)(raw[3] & 0xBBBBBBBBu), 0, 0, 0, 0};
                     const v8i hi2 = {0, 0, (int)(raw[2] & 0xCCCCCCCCu), (int)(raw[3] & 0xCCCCCCCCu), 0, 0, 0, 0};
 #pragma unroll
-                    for (int hg = 0; hg < HG; ++hg) {
+                    for (int hg = 0; hg < HG; ++hg)
                         s_acc[hg][u] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aq8[hg], lo1, s_acc[hg][u], 0, 4, 0, sa8[hg], 0, sb0);
+#pragma unroll
+                    for (int hg = 0; hg < HG; ++hg)
                         s_acc[hg][u] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aq8[hg], lo2, s_acc[hg][u], 0, 4, 0, sa8[hg], 0, sb0);
+#pragma unroll
+                    for (int hg = 0; hg < HG; ++hg)
                         s_acc[hg][u] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aq8[hg], hi1, s_acc[hg][u], 0, 4, 0, sa8[hg], 0, sb1);
+#pragma unroll
+                    for (int hg = 0; hg < HG; ++hg)
                         s_acc[hg][u] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(aq8[hg], hi2, s_acc[hg][u], 0, 4, 0, sa8[hg], 0, sb1);
-                    }
+                }
+                if constexpr (kEarlySum && u > 0) {
+#pragma unroll
+                    for (int hg = 0; hg < HG; ++hg)
+                        s_sum[hg][u - 1] = (s_acc[hg][u - 1][0] + s_acc[hg][u - 1][1]) + (s_acc[hg][u - 1][2] + s_acc[hg][u - 1][3]);
                 }
             });
+            if constexpr (kEarlySum) {
+#pragma unroll
+                for (int hg = 0; hg < HG; ++hg) s_sum[hg][3] = (s_acc[hg][3][0] + s_acc[hg][3][1]) + (s_acc[hg][3][2] + s_acc[hg][3][3]);
+            }
 
             // ---------------- online softmax; lane (j, kg) owns head kg of each group, tokens 16u + j
 #pragma unroll
             for (int hg = 0; hg < HG; ++hg) {
                 float s[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) s[u] = (s_acc[hg][u][0] + s_acc[hg][u][1]) + (s_acc[hg][u][2] + s_acc[hg][u][3]);   // the limb rows
+                for (int u = 0; u < 4; ++u)      // the limb rows
+                    s[u] = kEarlySum ? s_sum[kEarlySum ? hg : 0][u] : (s_acc[hg][u][0] + s_acc[hg][u][1]) + (s_acc[hg][u][2] + s_acc[hg][u][3]);
                 if (masked) {
                     const int vis = min(left, lim[hg] - T0);
 #pragma unroll
@@ -924,6 +965,16 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
                 if constexpr (P == 8) lds_wait<HG>(vw8a[cur], vw8b[cur], ppv[pc]);
                 else lds_wait<HG>(vw01[cur], vw23[cur], ppv[pc]);
                 if (u == 0) { if (N == 32) lds_wait(vexp32); else lds_wait(vexp16); }
+                if constexpr (kPackVexp && u == 0) {
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) {
+                        if (N == 32)
+                            vexp_pk[x] = __builtin_amdgcn_perm(vexp32[1][x], vexp32[0][x], pk_sel01) |
+                                         __builtin_amdgcn_perm(vexp32[3][x], vexp32[2][x], pk_sel23);
+                        else
+                            vexp_pk[x] = vexp16[4 * x] | (vexp16[4 * x + 1] << 8) | (vexp16[4 * x + 2] << 16) | (vexp16[4 * x + 3] << 24);
+                    }
+                }
                 __builtin_amdgcn_sched_barrier(0);
                 if (more) {
                     fill_mant(U, false, full1, T1, row1);
@@ -970,8 +1021,15 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
                 for (int i = 0; i < 4; ++i) {
                     // scale operand: the exponent byte in the exponent field (the conversion looks at nothing else:
                     // for blocks of 32 the other bytes of the dword stay where the rotation leaves them)
-                    const float sc = N == 32 ? __uint_as_float(__builtin_amdgcn_alignbit(vexp32[u][i], vexp32[u][i], ve_rot))
-                                             : scale_operand(vexp16[4 * u + i]);
+                    float sc;
+                    if constexpr (kPackVexp) {
+                        constexpr int reg = N == 32 ? 0 : u;            // + i for blocks of 32 (not a constant expression there)
+                        const uint32_t pk = vexp_pk[N == 32 ? i : reg];
+                        sc = __uint_as_float(__builtin_amdgcn_alignbit(pk, pk, (uint32_t)((8 * (N == 32 ? u : i) + 9) & 31)));
+                    } else {
+                        sc = N == 32 ? __uint_as_float(__builtin_amdgcn_alignbit(vexp32[u][i], vexp32[u][i], ve_rot))
+                                     : scale_operand(vexp16[4 * u + i]);
+                    }
                     vv[i] = unpack8_p4(vw[i], sc);
                 }
 #pragma unroll
