@@ -244,7 +244,7 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
     __shared__ __align__(16) uint8_t qsc_lds[NH * 16];
     // sixteen heads: the query operand (4 x 8 registers) does not stay in registers between tiles; it lives in LDS,
     // [NH * 4 limb rows][128], and every tile reads it back for its score phase
-    constexpr bool kQueryInLds = HG == 4;
+    constexpr bool kQueryInLds = HG == 4 || (HG == 2 && N == 32 && PAGED && P == 4);   // (and where paging would push a three-wavefront variant over its registers)
     __shared__ __align__(16) uint8_t qop_lds[kQueryInLds ? NH * 4 * kD : 16];
 
     const int tid = threadIdx.x;
@@ -703,7 +703,7 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
         uint32_t vexp16[16];      // blocks of 16: per (stage, token) this lane's exponent byte
         // sixteen heads: the sixteen exponent bytes this lane needs of a tile, packed into four registers right after
         // they arrive (blocks of 32: register i = token 4kg + i, byte u = stage; blocks of 16: register u, byte i)
-        constexpr bool kPackVexp = HG == 4;
+        constexpr bool kPackVexp = HG == 4 || (HG == 2 && N == 32 && PAGED && P == 4);   // (and where paging would push a three-wavefront variant over its registers)
         uint32_t vexp_pk[4];
         const uint32_t pk_sel01 = (uint32_t)(j >> 2) | ((4u + (uint32_t)(j >> 2)) << 8) | 0x0c0c0000u;
         const uint32_t pk_sel23 = ((uint32_t)(j >> 2) << 16) | ((4u + (uint32_t)(j >> 2)) << 24) | 0x00000c0cu;
