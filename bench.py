@@ -565,7 +565,8 @@ def main():
         del ring
         torch.cuda.empty_cache()
         result["workloads"] = {}
-        for name in ("llama2_7b_4k", "batched_8k_p4", "batched_8k_p8", "long_128k", "gqa_32k_n64", "gqa_32k_n128", "gqa_32k_p8n16"):
+        for name in ("llama2_7b_4k", "batched_8k_p4", "batched_8k_p8", "long_128k", "gqa_32k_n64", "gqa_32k_n128", "gqa_32k_p8n16",
+                     "gqa8_32k"):
             if name == w.name:
                 continue
             try:
