@@ -411,7 +411,8 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
                     c = keys ? kd_chunk : vp_c;
                 }
                 if (!tile_full) r = min(r, last);
-                __builtin_amdgcn_global_load_lds(KVBFP_GPTR(sp + (r * kRowB + c * 16)), KVBFP_LPTR(lm + u * kStageB + i * 1024), 16, 0, kStreamAux);
+                // (an unsigned 32-bit lane offset from a wave-uniform base: no 64-bit address arithmetic per lane)
+                __builtin_amdgcn_global_load_lds(KVBFP_GPTR(sp + (uint32_t)(r * kRowB + c * 16)), KVBFP_LPTR(lm + u * kStageB + i * 1024), 16, 0, kStreamAux);
             }
             return;
         }
