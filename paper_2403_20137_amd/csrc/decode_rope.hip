@@ -314,19 +314,28 @@ __global__ __launch_bounds__(256) void decode_split_rope_p4(DecodeArgs a, int dt
                 lo1[i / 2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(a1 - __builtin_convertvector(h1, f32x2), f16x2));
                 lo2[i / 2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(a2 - __builtin_convertvector(h2, f32x2), f16x2));
             }
+            // Lane `blk` of the quad built chunk blk.  Its low limb first goes to the neighbour lane blk ^ 1, so that one
+            // register holds the high limb in one lane of the pair and the low limb in the other; a quad permute
+            // [blk, blk^1, blk, blk^1] then hands the high limb to the even lanes and the low limb to the odd ones.
             const bool odd = (limb & 1) != 0;
+            uint32_t ze1[4], zo1[4], ze2[4], zo2[4];       // for even / odd blk
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const uint32_t x1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)lo1[r], 0xB1, 0xF, 0xF, false);   // quad_perm [1,0,3,2]
+                const uint32_t x2 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)lo2[r], 0xB1, 0xF, 0xF, false);
+                ze1[r] = odd ? x1 : hi1[r];
+                zo1[r] = odd ? hi1[r] : x1;
+                ze2[r] = odd ? x2 : hi2[r];
+                zo2[r] = odd ? hi2[r] : x2;
+            }
             static_for4([&](auto BLK) {
                 constexpr int blk = decltype(BLK)::value;
-                constexpr int ctrl = blk * 0x55;            // DPP quad_perm [blk, blk, blk, blk]: every lane of a quad reads lane blk
+                constexpr int ctrl = blk | ((blk ^ 1) << 2) | (blk << 4) | ((blk ^ 1) << 6);
                 uint32_t p1[4], p2[4];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const uint32_t h1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)hi1[r], ctrl, 0xF, 0xF, false);
-                    const uint32_t l1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)lo1[r], ctrl, 0xF, 0xF, false);
-                    const uint32_t h2 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)hi2[r], ctrl, 0xF, 0xF, false);
-                    const uint32_t l2 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)lo2[r], ctrl, 0xF, 0xF, false);
-                    p1[r] = odd ? l1 : h1;
-                    p2[r] = odd ? l2 : h2;
+                    p1[r] = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)((blk & 1) ? zo1[r] : ze1[r]), ctrl, 0xF, 0xF, false);
+                    p2[r] = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)((blk & 1) ? zo2[r] : ze2[r]), ctrl, 0xF, 0xF, false);
                 }
                 A1[blk] = __builtin_bit_cast(f16x8, u32x4{p1[0], p1[1], p1[2], p1[3]});
                 A2[blk] = __builtin_bit_cast(f16x8, u32x4{p2[0], p2[1], p2[2], p2[3]});
