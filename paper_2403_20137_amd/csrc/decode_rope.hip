@@ -308,11 +308,15 @@ __global__ __launch_bounds__(256) void decode_split_rope_p4(DecodeArgs a, int dt
             for (int i = 0; i < 8; i += 2) {
                 const f32x2 a1 = {fmaf(x[i], c0[i], y[i] * s0[i]), fmaf(x[i + 1], c0[i + 1], y[i + 1] * s0[i + 1])};
                 const f32x2 a2 = {fmaf(y[i], c0[i], -(x[i] * s0[i])), fmaf(y[i + 1], c0[i + 1], -(x[i + 1] * s0[i + 1]))};
-                const f16x2 h1 = __builtin_convertvector(a1, f16x2), h2 = __builtin_convertvector(a2, f16x2);
+                // high limb = the value cut to binary16 (one pack instruction for two values), low limb = what is left,
+                // cut again: the pair carries 22 bits whichever way each part is rounded
+                const f16x2 h1 = __builtin_bit_cast(f16x2, __builtin_amdgcn_cvt_pkrtz(a1[0], a1[1]));
+                const f16x2 h2 = __builtin_bit_cast(f16x2, __builtin_amdgcn_cvt_pkrtz(a2[0], a2[1]));
+                const f32x2 r1 = a1 - __builtin_convertvector(h1, f32x2), r2 = a2 - __builtin_convertvector(h2, f32x2);
                 hi1[i / 2] = __builtin_bit_cast(uint32_t, h1);
                 hi2[i / 2] = __builtin_bit_cast(uint32_t, h2);
-                lo1[i / 2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(a1 - __builtin_convertvector(h1, f32x2), f16x2));
-                lo2[i / 2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(a2 - __builtin_convertvector(h2, f32x2), f16x2));
+                lo1[i / 2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(r1[0], r1[1]));
+                lo2[i / 2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(r2[0], r2[1]));
             }
             // Lane `blk` of the quad built chunk blk.  Its low limb first goes to the neighbour lane blk ^ 1, so that one
             // register holds the high limb in one lane of the pair and the low limb in the other; a quad permute
