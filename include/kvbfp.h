@@ -292,7 +292,7 @@ int kvbfp_permute_rope(const float* theta, kvbfp_rope_pairs pairs, int32_t n_hea
  * cos/sin per token offset; same bars as kvbfp_decode_attention, any exponent bytes 3..254, queries
  * and softmax_scale whose product stays finite in fp32); 8-bit mantissas and fp32 I/O take a vector-ALU
  * pass that is several times slower.  Either way the rotation costs arithmetic per cached key element
- * that the plain path does not have: about 2.6x the time of kvbfp_decode_attention on the same cache
+ * that the plain path does not have: about 2.3x the time of kvbfp_decode_attention on the same cache
  * (a cache of already rotated keys, reordered at append time, needs none of it).
  * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP. */
 int kvbfp_decode_attention_rope(const kvbfp_layout* layout, const kvbfp_cache* cache, int32_t n_q_heads,
