@@ -241,11 +241,15 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
     // its FP8 limbs [NH*4 rows][128] in the second (the permutation and the block maxima of the BFP cast
     // pass through there before the limbs are written); the limbs' scale bytes [NH*4][4] sit beside.
     static_assert(sizeof(p_lds) == NH * kD * 4 + NH * 4 * kD, "query staging fills the probability buffer exactly");
-    __shared__ __align__(16) uint8_t qsc_lds[NH * 16];
     // sixteen heads: the query operand (4 x 8 registers) does not stay in registers between tiles; it lives in LDS,
     // [NH * 4 limb rows][128], and every tile reads it back for its score phase
-    constexpr bool kQueryInLds = HG == 4 || (HG == 2 && N == 32 && PAGED && P == 4);   // (and where paging would push a three-wavefront variant over its registers)
-    __shared__ __align__(16) uint8_t qop_lds[kQueryInLds ? NH * 4 * kD : 16];
+    constexpr bool kQueryInLds = HG == 4 || (HG == 2 && PAGED && ((P == 4 && N == 32) || (P == 8 && N == 16)));   // (and where paging would push a three-wavefront variant over its registers)
+    // One small LDS object either way: the limbs' scale bytes [NH * 4][4] of the set-up, or -- where the query
+    // operand lives in LDS -- that operand; the scale bytes then sit at the end of the query staging area, whose
+    // second half the limbs do not need in that case.
+    __shared__ __align__(16) uint8_t qaux_lds[kQueryInLds ? NH * 4 * kD : NH * 16];
+    uint8_t* const qop_lds = qaux_lds;
+    uint8_t* const qsc_lds = kQueryInLds ? (uint8_t*)&p_lds[0][0] + sizeof(p_lds) - NH * 16 : qaux_lds;
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS bases stay in scalar registers
@@ -788,6 +792,11 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
                     const u32x4 lo = *(const u32x4*)(qop_lds + (hg * 16 + j) * kD + kg * 32);
                     const u32x4 hi = *(const u32x4*)(qop_lds + (hg * 16 + j) * kD + kg * 32 + 16);
                     aq8[hg] = v8i{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+                    if constexpr (P == 8 && N == 16) {
+                        const v8i zero = {0, 0, 0, 0, 0, 0, 0, 0};
+                        aq8e[hg] = (kg & 1) ? zero : aq8[hg];
+                        aq8o[hg] = (kg & 1) ? aq8[hg] : zero;
+                    }
                 }
             }
 
