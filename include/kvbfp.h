@@ -389,11 +389,12 @@ int kvbfp_decode_attention_profile_ring(const kvbfp_layout* layout, const kvbfp_
 /* DEVICE, SYNCHRONOUS, for measurement.  Reads rows [0, n_tok) of the four planes of every (batch,
  * kv-head) once -- the bytes one kvbfp_decode_attention call over n_tok cached tokens streams (Sec. III:
  * the cached keys and values are read back each step) -- with plain 16-byte loads and no arithmetic, and
- * returns the kernel's duration.  This is the rate a read-only kernel of the same size reaches on the
+ * returns the kernel's duration (the sweep is launched twice, with two and with eight loads in flight per
+ * lane, and the shorter duration is returned).  This is the rate a read-only kernel of the same size reaches on the
  * machine; the split pass of decode attention is reported against it next to the nominal HBM peak.
  *   wgs_per_unit : workgroups per (batch, kv-head); 0 = a default of about eight per compute unit.
  *   sink         : DEVICE, 4 writable bytes (keeps the loads alive; practically never written).
- *   kernel_ms    : HOST float[1], milliseconds between HIP events recorded on `hip_stream` around the kernel.
+ *   kernel_ms    : HOST float[1], milliseconds between HIP events recorded on `hip_stream` around the faster launch.
  * Up to 15 bytes at either end of an exponent region that is not 16-byte aligned are skipped.
  * Errors: INVALID_ARG (NULL, n_tok outside (0, max_seq]), UNSUPPORTED (geometry), HIP. */
 int kvbfp_measure_stream_read(const kvbfp_layout* layout, const kvbfp_cache* cache, int64_t n_tok,
