@@ -255,3 +255,38 @@ def test_several_query_tokens_on_pages(dtype, p, n, G, Tq, page):
         seen = [max(l - (Tq - 1 - i), 0) for l in lens]
         want = O.decode_attention(*planes, D, n, p, synth.to_f32_numpy(q[:, i]), seen, scale, pk, pv)
         assert_attention_close(got[:, i], want, dtype, "query token %d of %d sees %s" % (i, Tq, seen))
+
+
+@pytest.mark.parametrize("page", [16, 256])
+def test_many_tiles_per_wavefront_on_pages(page):
+    # 768 (sequence, kv-head) units leave one split per unit, so every wavefront walks 67 tiles: more than the 64 whose
+    # page numbers it fetches at kernel start -- the last ones are looked up when they are due.  Sampled units
+    # against the oracle (bytes through the table bit for bit, attention within the bar).
+    B, Hkv, G, S, n, p = 96, 8, 2, 66 * 256 + 37, 32, 4
+    gains = synth.outlier_gains(77, 0, Hkv, D)
+    k = synth.kv_rows(B, S, Hkv, D, "bf16", gains, 77, 2, "cuda")
+    v = synth.kv_rows(B, S, Hkv, D, "bf16", gains, 77, 3, "cuda")
+    q = synth.queries(B, Hkv * G, D, "bf16", 77, 4, "cuda")
+    rng = np.random.default_rng(page)
+    pk = np.stack([rng.permutation(D) for _ in range(Hkv)]).astype(np.int32)
+    pv = np.stack([rng.permutation(D) for _ in range(Hkv)]).astype(np.int32)
+    per_seq = -(-S // page)
+    table = rng.permutation(B * per_seq).reshape(B, per_seq).astype(np.int32)
+    table_dev = dev_i32(table)
+    L = kvbfp.make_layout(D, n, p, Hkv, B * per_seq, page)
+    pool = kvbfp.alloc_cache(L, "cuda", fill=SENTINEL)
+    kvbfp.quantize_append_paged(pool, table_dev, k, v, pos0=0, perm_k=dev_i32(pk), perm_v=dev_i32(pv))
+    scale = float(np.float32(128 ** -0.5))
+    got = kvbfp.decode_attention_paged(pool, table_dev, q, S, scale, perm_k=dev_i32(pk), perm_v=dev_i32(pv))
+    torch.cuda.synchronize()
+    for (b, h) in [(0, 0), (41, 5), (95, 7)]:
+        km, ke = O.quantize_append(synth.to_f32_numpy(k[b:b + 1, :, h:h + 1].cpu()), n, p, per_seq * page, 0, perm=pk[h:h + 1])
+        vm, ve = O.quantize_append(synth.to_f32_numpy(v[b:b + 1, :, h:h + 1].cpu()), n, p, per_seq * page, 0, perm=pv[h:h + 1])
+        pages = torch.as_tensor(table[b], device="cuda", dtype=torch.long)
+        for plane, ref, nm in ((pool.k_mant, km, "k_mant"), (pool.k_exp, ke, "k_exp"), (pool.v_mant, vm, "v_mant"),
+                               (pool.v_exp, ve, "v_exp")):
+            rows = plane[pages, h].reshape(per_seq * page, -1)[:S].cpu().numpy()
+            assert np.array_equal(rows, ref[0, 0, :S]), (nm, b, h)
+        want = O.decode_attention(km, ke, vm, ve, D, n, p, synth.to_f32_numpy(q[b:b + 1, h * G:(h + 1) * G].cpu()), [S], scale,
+                                  pk[h:h + 1], pv[h:h + 1])
+        assert_attention_close(got[b:b + 1, h * G:(h + 1) * G], want, torch.bfloat16, "page %d unit (%d,%d)" % (page, b, h))
