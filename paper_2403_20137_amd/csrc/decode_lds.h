@@ -278,29 +278,37 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
         return;
     }
 
-    // The page numbers of this wavefront's first kPreTiles tiles are fetched once, here, by its 64 lanes (tile lane/4,
-    // stage lane%4, as quotients like q[u]) and kept in LDS.  A table look-up inside the main loop shares its counter
-    // with the LDS reads that the loop waits for one by one, so every such wait also waited for the table: over
-    // 16-token pages the pass took 61.5 us with the look-ups in the loop and 54.7 us without any.  Tiles beyond the
-    // first kPreTiles still look their pages up when they are due (and all tiles of the one variant whose 80 KB of
-    // LDS leave no room for the list).
+    // The page numbers of a wavefront's tiles do not come from look-ups inside the main loop: a load there shares a
+    // counter with the requests the loop keeps in flight and waits for one by one, and every wait then also waits for
+    // the table (over 16-token pages the pass took 61.5 us with a look-up per tile and 54.7 us in an experiment
+    // without any).  They are fetched in bulk by the 64 lanes (tile lane/4, stage lane%4, as quotients like q[u] below)
+    // into a list of kPreTiles tiles in LDS, slot = tile index % kPreTiles: all of it at kernel start, and one half of
+    // it, for the tiles 32..63 ahead, whenever the loop enters the other half.  (One variant's 80 KB of LDS leave no
+    // room for the list: it looks its pages up tile by tile.)
     constexpr int kPreTiles = !PAGED || (P == 8 && HG == 2 && N == 16) ? 0 : 64;      // 4 KB of LDS per workgroup
     __shared__ __align__(16) int32_t pt_lds[kPreTiles > 0 ? kWaves * kPreTiles * 4 : 4];
-    if constexpr (kPreTiles > 0) {
-        const int64_t tile_step = (int64_t)a.n_splits * kWaves * kTileTok;
-        int32_t got[kPreTiles / 16];
+    const int64_t tile_step = (int64_t)a.n_splits * kWaves * kTileTok;
+    auto fetch_pages = [&](auto n_tag, const int first_tile) {    // tiles first_tile .. first_tile + n - 1, n = 32 or 64
+        constexpr int n = decltype(n_tag)::value;
+        int32_t got[n / 16];
 #pragma unroll
-        for (int pass = 0; pass < kPreTiles / 16; ++pass) {      // all loads first, then the stores
-            int64_t t = t_begin + wave * kTileTok + (int64_t)(16 * pass + (lane >> 2)) * tile_step + 16 * (lane & 3);
+        for (int pass = 0; pass < n / 16; ++pass) {               // all loads first, then the stores
+            const int tile = first_tile + 16 * pass + (lane >> 2);
+            int64_t t = t_begin + wave * kTileTok + (int64_t)tile * tile_step + 16 * (lane & 3);
             if (t >= t_end) t = (t_end - 1) & ~(int64_t)15;
             got[pass] = (int32_t)(kvbfp::cache_row(a, b, kvh, t) >> 4);
         }
 #pragma unroll
-        for (int pass = 0; pass < kPreTiles / 16; ++pass) pt_lds[wave * kPreTiles * 4 + 64 * pass + lane] = got[pass];
+        for (int pass = 0; pass < n / 16; ++pass) {
+            const int tile = first_tile + 16 * pass + (lane >> 2);
+            pt_lds[(wave * (kPreTiles > 0 ? kPreTiles : 1) + (tile & (kPreTiles > 0 ? kPreTiles - 1 : 0))) * 4 + (lane & 3)] = got[pass];
+        }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    }
+    };
+    if constexpr (kPreTiles > 0) fetch_pages(std::integral_constant<int, 64>{}, 0);
+
     // ---- kvbfp_append_decode_attention: the current token, position L - 1, is cast and stored by the
     // one wavefront whose 64-token tiles include that position (nobody else ever reads the row), off
     // everybody else's path.  Lanes 0-7 take the key row, lanes 8-15 the value row; the rest of the
@@ -373,8 +381,8 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
 #pragma unroll
         for (int u = 0; u < (PAGED ? 4 : 1); ++u) tr.q[u] = 0;
         if constexpr (PAGED) {
-            if (kPreTiles > 0 && live && ti < kPreTiles) {
-                const int4 e = *(const int4*)&pt_lds[(wave * kPreTiles + ti) * 4];
+            if (kPreTiles > 0 && live) {
+                const int4 e = *(const int4*)&pt_lds[(wave * kPreTiles + (ti & (kPreTiles - 1))) * 4];
                 tr.q[0] = __builtin_amdgcn_readfirstlane(e.x);
                 tr.q[1] = __builtin_amdgcn_readfirstlane(e.y);
                 tr.q[2] = __builtin_amdgcn_readfirstlane(e.z);
@@ -1096,6 +1104,11 @@ __device__ __forceinline__ void decode_split_lds_body(const DecodeArgs& a, const
         for (int T0 = T_first; T0 < n_tok; T0 += kStep, ++ti) {
             const int T1 = T0 + kStep;
             const bool more = T1 < n_tok;            // wave-uniform
+            if constexpr (kPreTiles > 0) {
+                // entering a half of the page list: the other half takes the tiles 32..63 ahead (rare: its loads are
+                // ordinary ones, waited for right here)
+                if (ti > 0 && (ti & 31) == 0 && more) fetch_pages(std::integral_constant<int, 32>{}, ti + 32);
+            }
             const TileRows row1 = tile_rows(T1, more, ti + 1);
             const bool full1 = n_tok - T1 >= kTileTok;       // the next tile is complete
             if (appends && more && T1 + kStep >= n_tok) {      // next comes the tile with the new row: its stores first
