@@ -566,7 +566,7 @@ def main():
         torch.cuda.empty_cache()
         result["workloads"] = {}
         for name in ("llama2_7b_4k", "batched_8k_p4", "batched_8k_p8", "long_128k", "gqa_32k_n64", "gqa_32k_n128", "gqa_32k_p8n16",
-                     "gqa8_32k"):
+                     "gqa8_32k", "gqa_32k_b96"):
             if name == w.name:
                 continue
             try:

@@ -64,6 +64,8 @@ WORKLOADS = {
     "gqa_32k_n128": Workload("gqa_32k_n128", 8, 32, 8, 128, 32768, "bf16", 128, 4, (2, 6), (20.0, 20.0)),
     "gqa_32k_p8n16": Workload("gqa_32k_p8n16", 8, 32, 8, 128, 32768, "bf16", 16, 8, (2, 6), (20.0, 20.0)),
     "gqa_32k_p8n32": Workload("gqa_32k_p8n32", 8, 32, 8, 128, 32768, "bf16", 32, 8, (2, 6), (20.0, 20.0)),
+    # the headline shapes with 96 sequences: 768 (sequence, kv-head) units, one split each, 3.4 GB per call
+    "gqa_32k_b96": Workload("gqa_32k_b96", 96, 32, 8, 128, 32768, "bf16", 32, 4, (2, 6), (20.0, 20.0)),
     "prefill_bulk": Workload("prefill_bulk", 32, 8, 8, 128, 4096, "bf16", 16, 4, (2, 6), (10.0, 50.0),
                              extra={"note": "32 layers x 8 KV heads x 4096 tokens, layer index plays the batch role"}),
 }
